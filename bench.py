@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the VLA forward hot path on one MI355X.
+
+A "step" is one vla_forward call (the whole per-head recurrence: key normalisation,
+Sherman-Morrison update of A, write direction, residual update of S, read-out) over one
+batch of synthetic input already resident in HBM.  Default workload: the large-batch
+configuration (B=64, H=32, T=8192, d_h=128, bf16 q/k/v/o, float32 A and S).
+
+Prints ONE JSON line: whole-job head-tokens/s, the roofline object for the dominant
+kernel (HIP-event timed on the launch stream) and the fp64 oracle timed on the host
+cores on a bounded sample of the same workload (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_TFLOPS = 157.3   # MI355X FP32 vector (and FP32 matrix) peak, TFLOP/s
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by the
+# same counter's reading for a plain copy kernel of known size); see profiles/. None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="large_batch",
+                    choices=["tiny", "norm_growth", "recall", "long_context", "large_batch"])
+    ap.add_argument("--T", type=int, default=None, help="sequence length override (long_context)")
+    ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=None, help="heads in the oracle timing sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (heads are independent, so more GPUs "
+              "would only split the batch); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_11196_amd as vla
+    import vla_inputs
+
+    c = dict(vla_inputs.CONFIGS[args.workload])
+    if args.workload == "long_context":
+        c["T"] = args.T or 65536
+    elif args.T:
+        c["T"] = args.T
+    B, H, T, d = c["B"], c["H"], c["T"], c["d"]
+    dtype = c["dtype"]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    io = vla.VLA_BF16 if dtype == "bf16" else vla.VLA_F32
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.workload == "recall":
+        qn, kn, vn, _ = vla_inputs.recall_task(B, H, T, d, c["seed"], c["n_pairs"])
+        q, k, v = (torch.from_numpy(x).to(dev) for x in (qn, kn, vn))
+    elif dtype == "bf16":
+        q, k, v = vla_inputs.device_gaussian(B, H, T, d, c["seed"], c["std"], tdt)
+    else:
+        q, k, v = (torch.from_numpy(x).to(dev)
+                   for x in vla_inputs.gaussian_qkv(B, H, T, d, c["seed"], c["std"]))
+
+    o = torch.empty_like(v)
+    S_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    A_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+    mode = args.mode
+    need = vla.vla_forward_workspace_bytes(B, H, T, d, d, io, lambda0=c["lambda0"], mode=mode)
+    ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    resolved = vla.resolve_mode(B, H, T, d, d, io, mode=mode)
+    stream = torch.cuda.current_stream(dev)
+
+    def step():
+        rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(),
+                                 S_T.data_ptr(), A_T.data_ptr(), B, H, T, d, d, io,
+                                 lambda0=c["lambda0"], mode=mode, workspace=ws.data_ptr(),
+                                 workspace_bytes=need, stream=stream.cuda_stream)
+        if rc != 0:
+            raise RuntimeError(vla.status_string(rc))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # per-launch device time with HIP events recorded on the launch stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    dev_ms = [a.elapsed_time(b) for a, b in ev]
+    avg_launch_s = sum(dev_ms) / len(dev_ms) / 1e3
+
+    head_tokens = B * H * T
+    value = head_tokens * args.steps / wall
+    flops = 10.0 * d * d * head_tokens           # algorithmic flop per launch (5 d^2 FMA per head-token)
+    io_bytes = (2 if dtype == "bf16" else 4) * 4 * d * head_tokens   # q,k,v read + o written
+    achieved_tflops = flops / avg_launch_s / 1e12
+    mode_names = {1: "scan", 2: "chunked", 3: "two_phase"}
+    workload = (f"{args.workload}: B={B} H={H} T={T} d_h={d} {dtype} q/k/v/o, fp32 A and S, "
+                f"lambda0={c['lambda0']}")
+    out = {
+        "metric": "VLA forward tokens/sec (B*H*T/s)",
+        "value": value,
+        "unit": "head-tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": workload, "io_dtype": dtype, "kernel_mode": mode_names.get(resolved, str(resolved)),
+                   "global_batch": B, "heads": H, "seq_len": T, "d_h": d, "parallelism": "single-gpu"},
+        "roofline": {
+            "bound": "mfma" if resolved == 2 else "alu",
+            "achieved": achieved_tflops,
+            "peak": PEAK_FP32_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved_tflops / PEAK_FP32_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T, resolved)),
+            "kernel_ms": avg_launch_s * 1e3,
+            "algorithmic_flop_per_launch": flops,
+            "algorithmic_bytes_per_launch": io_bytes,
+            "hbm_GBps": io_bytes / avg_launch_s / 1e9,
+            "hbm_frac": io_bytes / avg_launch_s / 1e9 / PEAK_HBM_GBS,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        # bounded sample: a deterministic subset of heads over the full sequence
+        n_all = B * H
+        want = args.cpu_heads or max(1, min(n_all, int(3.0e6 * (128.0 / d) ** 2 / max(T, 1))))
+        idx = sorted(set(int(i) for i in np.linspace(0, n_all - 1, num=min(want, n_all))))
+        sel = torch.tensor(idx, device=dev)
+        pick = lambda x: x.reshape(n_all, *x.shape[2:]).index_select(0, sel).float().cpu().numpy()[None]
+        qs, ks, vs = (pick(x).astype(np.float64) for x in (q, k, v))
+        oracle.load()
+        tc0 = time.perf_counter()
+        ref = oracle.forward(qs, ks, vs, lambda0=c["lambda0"])
+        tc1 = time.perf_counter()
+        cpu_rate = len(idx) * T / (tc1 - tc0)
+        got = pick(o).astype(np.float64)
+        err = float((np.abs(got - ref["o"]).max(axis=(2, 3)) / np.abs(ref["o"]).max(axis=(2, 3))).max())
+        out["cpu_baseline"] = {
+            "value": cpu_rate, "unit": "head-tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(idx)} of {n_all} heads (evenly spaced) x all {T} tokens, fp64, "
+                      f"{tc1 - tc0:.1f} s",
+            "gpu_vs_oracle_max_rel_err_o": err,
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

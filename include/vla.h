@@ -1,0 +1,125 @@
+/*
+ * vla.h -- C ABI of the MI355X (gfx950) Variational Linear Attention forward library.
+ *
+ * One operation: the causal per-head VLA forward recurrence (paper Section 3.3,
+ * eq. (sm), eq. (s-update), numerator of eq. (output); Algorithm 1).  For every
+ * (batch b, head h) independently, starting from S = S0[b,h], A = A0[b,h], for
+ * t = 1..T:
+ *
+ *     k^_t     = k_t / max(||k_t||, eps)                       (Section 3.1)
+ *     u_t      = k^_t               (penalty direction aligned with the key, Section 7.1)
+ *     z_t      = A_{t-1} u_t ;  delta_t = max(1 + u_t . z_t, eps)
+ *     A_t      = A_{t-1} - z_t z_t^T / delta_t                 (eq. (sm))
+ *     alpha^_t = A_t k^_t / max(||A_t k^_t||, eps)             (post-update A)
+ *     e_t      = v_t - S_{t-1} k^_t
+ *     S_t      = S_{t-1} + e_t alpha^_t^T                      (eq. (s-update))
+ *     o_t      = S_t q_t                                       (post-update S)
+ *
+ * and finally S_T, A_T are written out.  The identity refresh of Algorithm 1 and
+ * the denominator of eq. (output) are not applied.
+ *
+ * Every pointer is a DEVICE pointer unless stated otherwise.  The library never
+ * allocates, frees or retains memory: the caller owns every buffer for the
+ * duration of the call's execution on `stream`.  Calls are asynchronous with
+ * respect to the host (kernels are enqueued on `stream`, no host synchronisation)
+ * and re-entrant.  All validation happens on the host before anything is enqueued;
+ * on any error nothing has been launched and no output has been touched.
+ */
+#ifndef VLA_H_
+#define VLA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of q, k, v and o.  The states S and A are always float32, and all
+ * arithmetic is float32 regardless of the I/O type (bf16 inputs are widened
+ * exactly; o is rounded to nearest-even on the final store). */
+typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
+
+/* Which kernel family runs the recurrence.
+ *   AUTO     : the library picks (currently by head size, dtype and B*H).
+ *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
+ *              resident in registers (FP32 vector ALU).
+ *   CHUNKED  : tokens are processed in blocks; the block form of the same
+ *              recurrence turns the matrix-vector work into dense FP32 matrix
+ *              products (MFMA).  Same result up to float32 rounding order.
+ *   TWO_PHASE: phase 1 runs the A recurrence and writes k^_t, alpha^_t to the
+ *              workspace; phase 2 runs the S recurrence with the rows of S spread
+ *              over several workgroups (for small B*H).  Allowed because A never
+ *              reads S (eq. (sm)); Algorithm 2 takes k^, alpha^ as given inputs.
+ */
+typedef enum {
+  VLA_MODE_AUTO = 0,
+  VLA_MODE_SCAN = 1,
+  VLA_MODE_CHUNKED = 2,
+  VLA_MODE_TWO_PHASE = 3
+} vla_mode;
+
+typedef enum {
+  VLA_OK = 0,
+  VLA_ERR_INVALID_ARG = 1, /* null required pointer, non-positive size, misaligned pointer, bad enum */
+  VLA_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for (head size, d_k != d_v, mode) */
+  VLA_ERR_WORKSPACE = 3,   /* workspace missing or smaller than vla_forward_workspace_bytes() */
+  VLA_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
+} vla_status;
+
+/* Options; pass NULL for the defaults in brackets. */
+typedef struct vla_opts {
+  float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
+  float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^|| (Section 5.4) */
+  int mode;      /* [VLA_MODE_AUTO] a vla_mode */
+} vla_opts;
+
+/* Fills *opts with the defaults above. */
+void vla_default_opts(vla_opts* opts);
+
+/* Bytes of device workspace vla_forward needs for these arguments (0 for the
+ * modes that need none).  Returns 0 as well when the arguments are invalid --
+ * vla_forward will then report the error. */
+size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
+                                   const vla_opts* opts);
+
+/*
+ * vla_forward -- run the recurrence above for all B*H heads over T tokens.
+ *
+ *   q, k   [B, H, T, d_k]   io_dtype, contiguous, read-only
+ *   v      [B, H, T, d_v]   io_dtype, contiguous, read-only
+ *   S0     [B, H, d_v, d_k] float32 row-major, or NULL for S_0 = 0     (Algorithm 1)
+ *   A0     [B, H, d_k, d_k] float32 row-major, or NULL for I / lambda0 (Algorithm 1).
+ *          Must be symmetric positive definite (precondition, not checked).
+ *   o      [B, H, T, d_v]   io_dtype, written; must not overlap any input
+ *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may alias S0
+ *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may alias A0
+ *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
+ *   d_k == d_v in {16, 32, 64, 128}
+ *   opts   host pointer or NULL
+ *   workspace, workspace_bytes: device scratch of at least
+ *          vla_forward_workspace_bytes(...) bytes (may be NULL/0 when that is 0)
+ *   stream a hipStream_t passed as void*; NULL is the default stream
+ *
+ * All device pointers must be 16-byte aligned.  Returns a vla_status.
+ * Running [0,T1) and then [T1,T) with the carried S_T, A_T gives the same result
+ * as one call over [0,T) (the fixed-size state is the whole memory, Section 7.4).
+ */
+int vla_forward(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
+                void* stream);
+
+/* Human-readable name of a vla_status (static storage, never NULL). */
+const char* vla_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int vla_version(void);
+
+/* Which concrete mode AUTO resolves to for these arguments (a vla_mode, never AUTO),
+ * or -1 if the arguments are invalid/unsupported.  Host-only, launches nothing. */
+int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts* opts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLA_H_ */

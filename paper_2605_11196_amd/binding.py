@@ -1,0 +1,156 @@
+"""ctypes binding for libvla.so: argument marshalling only.
+
+Every step of the recurrence runs in the HIP kernels behind the C ABI
+(include/vla.h); there is no Python or CPU fallback -- if the shared library is
+missing, loading raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libvla.so"
+
+VLA_F32, VLA_BF16 = 0, 1
+MODE_AUTO, MODE_SCAN, MODE_CHUNKED, MODE_TWO_PHASE = 0, 1, 2, 3
+
+EXPORTS = ("vla_default_opts", "vla_forward_workspace_bytes", "vla_forward",
+           "vla_status_string", "vla_version", "vla_resolve_mode")
+
+
+class VlaError(RuntimeError):
+    def __init__(self, status, name):
+        super().__init__(f"vla_forward failed: {name} ({status})")
+        self.status = status
+
+
+class VlaOpts(ctypes.Structure):
+    _fields_ = [("lambda0", ctypes.c_float), ("eps", ctypes.c_float), ("mode", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load libvla.so (built in-tree by paper_2605_11196_amd/build.py). Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # PyTorch owns the device memory and the streams handed to the library, so libvla must bind
+    # to the HIP runtime instance torch has loaded: import torch before dlopen-ing libvla.so
+    # (loading in the other order would bring a second, separate copy of the runtime).
+    import torch  # noqa: F401
+
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2605_11196_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    P, I = ctypes.c_void_p, ctypes.c_int
+    OP = ctypes.POINTER(VlaOpts)
+    lib.vla_default_opts.argtypes = [OP]
+    lib.vla_default_opts.restype = None
+    lib.vla_forward_workspace_bytes.argtypes = [I] * 6 + [OP]
+    lib.vla_forward_workspace_bytes.restype = ctypes.c_size_t
+    lib.vla_forward.argtypes = [P] * 8 + [I] * 6 + [OP, P, ctypes.c_size_t, P]
+    lib.vla_forward.restype = I
+    lib.vla_status_string.argtypes = [I]
+    lib.vla_status_string.restype = ctypes.c_char_p
+    lib.vla_version.argtypes = []
+    lib.vla_version.restype = I
+    lib.vla_resolve_mode.argtypes = [I] * 6 + [OP]
+    lib.vla_resolve_mode.restype = I
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().vla_version())
+
+
+def status_string(status: int) -> str:
+    return load_library().vla_status_string(int(status)).decode()
+
+
+def _opts(lambda0, eps, mode):
+    o = VlaOpts()
+    load_library().vla_default_opts(ctypes.byref(o))
+    if lambda0 is not None:
+        o.lambda0 = float(lambda0)
+    if eps is not None:
+        o.eps = float(eps)
+    if mode is not None:
+        o.mode = int(mode)
+    return o
+
+
+def vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, *, lambda0=None, eps=None,
+                                mode=None) -> int:
+    o = _opts(lambda0, eps, mode)
+    return int(load_library().vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype,
+                                                          ctypes.byref(o)))
+
+
+def resolve_mode(B, H, T, d_k, d_v, io_dtype, *, mode=None) -> int:
+    o = _opts(None, None, mode)
+    return int(load_library().vla_resolve_mode(B, H, T, d_k, d_v, io_dtype, ctypes.byref(o)))
+
+
+def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *, lambda0=None,
+                    eps=None, mode=None, workspace=0, workspace_bytes=0, stream=0) -> int:
+    """Direct call with integer device addresses (0 = NULL); returns the vla_status."""
+    op = _opts(lambda0, eps, mode)
+    n = lambda x: ctypes.c_void_p(int(x) if x else None)
+    return int(load_library().vla_forward(n(q), n(k), n(v), n(S0), n(A0), n(o), n(S_T), n(A_T),
+                                          B, H, T, d_k, d_v, io_dtype, ctypes.byref(op),
+                                          n(workspace), int(workspace_bytes), n(stream)))
+
+
+def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None, stream=None,
+                return_state=True):
+    """Torch-tensor front end: q,k [B,H,T,d_k], v [B,H,T,d_v] on the GPU (float32 or bfloat16).
+
+    Allocates o (and S_T, A_T, workspace) with torch, enqueues the kernels on `stream`
+    (default: torch's current stream) and returns (o, S_T, A_T).
+    """
+    import torch
+
+    if not (q.is_cuda and k.is_cuda and v.is_cuda):
+        raise ValueError("q, k, v must be GPU tensors (no CPU path exists)")
+    if q.dtype == torch.float32:
+        io = VLA_F32
+    elif q.dtype == torch.bfloat16:
+        io = VLA_BF16
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share a dtype")
+    if q.dim() != 4 or k.shape != q.shape or v.shape[:3] != q.shape[:3]:
+        raise ValueError("expected q,k [B,H,T,d_k] and v [B,H,T,d_v]")
+    q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+    B, H, T, dk = q.shape
+    dv = v.shape[-1]
+    dev = q.device
+    for name, s, shape in (("S0", S0, (B, H, dv, dk)), ("A0", A0, (B, H, dk, dk))):
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != shape
+                              or not s.is_contiguous() or s.device != dev):
+            raise ValueError(f"{name} must be a contiguous float32 tensor of shape {shape} on {dev}")
+    with torch.cuda.device(dev):
+        o = torch.empty((B, H, T, dv), dtype=q.dtype, device=dev)
+        S_T = torch.empty((B, H, dv, dk), dtype=torch.float32, device=dev) if return_state else None
+        A_T = torch.empty((B, H, dk, dk), dtype=torch.float32, device=dev) if return_state else None
+        need = vla_forward_workspace_bytes(B, H, T, dk, dv, io, lambda0=lambda0, eps=eps, mode=mode)
+        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev) if need else None
+        st = stream if stream is not None else torch.cuda.current_stream(dev)
+        handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
+        p = lambda x: 0 if x is None else x.data_ptr()
+        rc = vla_forward_raw(p(q), p(k), p(v), p(S0), p(A0), p(o), p(S_T), p(A_T), B, H, T, dk, dv,
+                             io, lambda0=lambda0, eps=eps, mode=mode, workspace=p(ws),
+                             workspace_bytes=need, stream=handle)
+    if rc != 0:
+        raise VlaError(rc, status_string(rc))
+    return o, S_T, A_T

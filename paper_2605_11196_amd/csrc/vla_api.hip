@@ -1,0 +1,125 @@
+// Host side of the C ABI declared in include/vla.h: validation, mode selection, dispatch.
+#include "../../include/vla.h"
+
+#include "vla_common.h"
+
+#include <stdio.h>
+
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+bool supported_head_size(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+vla_opts resolve_opts(const vla_opts* o) {
+  vla_opts r;
+  vla_default_opts(&r);
+  if (o != nullptr) r = *o;
+  return r;
+}
+
+// Shared shape/enum checks; returns VLA_OK when a kernel exists for the request.
+int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts& o) {
+  if (B <= 0 || H <= 0 || T < 0 || d_k <= 0 || d_v <= 0) return VLA_ERR_INVALID_ARG;
+  if (io_dtype != VLA_F32 && io_dtype != VLA_BF16) return VLA_ERR_INVALID_ARG;
+  if (o.mode < VLA_MODE_AUTO || o.mode > VLA_MODE_TWO_PHASE) return VLA_ERR_INVALID_ARG;
+  if (!(o.lambda0 > 0.0f) || !(o.eps > 0.0f)) return VLA_ERR_INVALID_ARG;
+  if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
+  if (d_k != d_v || !supported_head_size(d_k)) return VLA_ERR_UNSUPPORTED;
+  return VLA_OK;
+}
+
+int pick_mode(int /*B*/, int /*H*/, int /*T*/, int /*d*/, int /*io_dtype*/, const vla_opts& o) {
+  if (o.mode != VLA_MODE_AUTO) return o.mode;
+  return VLA_MODE_SCAN;
+}
+
+bool mode_available(int mode) { return mode == VLA_MODE_SCAN; }
+
+}  // namespace
+
+extern "C" {
+
+void vla_default_opts(vla_opts* opts) {
+  if (opts == nullptr) return;
+  opts->lambda0 = 0.1f;
+  opts->eps = 1e-4f;
+  opts->mode = VLA_MODE_AUTO;
+}
+
+int vla_version(void) { return kVersion; }
+
+const char* vla_status_string(int status) {
+  switch (status) {
+    case VLA_OK: return "VLA_OK";
+    case VLA_ERR_INVALID_ARG: return "VLA_ERR_INVALID_ARG";
+    case VLA_ERR_UNSUPPORTED: return "VLA_ERR_UNSUPPORTED";
+    case VLA_ERR_WORKSPACE: return "VLA_ERR_WORKSPACE";
+    case VLA_ERR_HIP: return "VLA_ERR_HIP";
+    default: return "VLA_ERR_UNKNOWN";
+  }
+}
+
+int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts* opts) {
+  const vla_opts o = resolve_opts(opts);
+  if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return -1;
+  const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
+  return mode_available(mode) ? mode : -1;
+}
+
+size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
+                                   const vla_opts* opts) {
+  const vla_opts o = resolve_opts(opts);
+  if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
+  return 0;
+}
+
+int vla_forward(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
+                void* stream) {
+  const vla_opts op = resolve_opts(opts);
+  const int st = check_shape(B, H, T, d_k, d_v, io_dtype, op);
+  if (st != VLA_OK) return st;
+  if (T > 0 && (q == nullptr || k == nullptr || v == nullptr || o == nullptr)) {
+    return VLA_ERR_INVALID_ARG;
+  }
+  const void* ptrs[] = {q, k, v, S0, A0, o, S_T, A_T, workspace};
+  for (const void* p : ptrs) {
+    if (p != nullptr && !aligned16(p)) return VLA_ERR_INVALID_ARG;
+  }
+  if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
+
+  const int mode = pick_mode(B, H, T, d_k, io_dtype, op);
+  if (!mode_available(mode)) return VLA_ERR_UNSUPPORTED;
+  const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return VLA_ERR_WORKSPACE;
+  if (T == 0 && S_T == nullptr && A_T == nullptr) return VLA_OK;  // nothing to compute or copy
+
+  vla::ForwardArgs a;
+  a.q = q; a.k = k; a.v = v; a.S0 = S0; a.A0 = A0;
+  a.o = o; a.S_T = S_T; a.A_T = A_T;
+  a.n_heads = B * H;
+  a.T = T;
+  a.lambda0 = op.lambda0;
+  a.eps = op.eps;
+
+  hipError_t err = hipSuccess;
+  switch (mode) {
+    case VLA_MODE_SCAN:
+      err = vla::launch_scan(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      break;
+    default:
+      return VLA_ERR_UNSUPPORTED;
+  }
+  if (err != hipSuccess) {
+    fprintf(stderr, "libvla: kernel launch failed: %s (%d)\n", hipGetErrorString(err),
+            static_cast<int>(err));
+    return VLA_ERR_HIP;
+  }
+  return VLA_OK;
+}
+
+}  // extern "C"

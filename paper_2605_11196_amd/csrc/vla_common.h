@@ -1,0 +1,38 @@
+// Internal declarations shared by the HIP translation units of libvla (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vla {
+
+struct ForwardArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const float* S0;
+  const float* A0;
+  void* o;
+  float* S_T;
+  float* A_T;
+  int n_heads;  // B*H
+  int T;
+  float lambda0;
+  float eps;
+};
+
+// bf16 <-> f32 helpers on raw bit patterns (bf16 is the upper half of an IEEE float32).
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t x = __float_as_uint(f);
+  if ((x & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((x >> 16) | 0x40u);  // quiet NaN
+  x += 0x7fffu + ((x >> 16) & 1u);
+  return static_cast<uint16_t>(x >> 16);
+}
+
+// Token-by-token scan, one workgroup per head (vla_scan.hip).
+hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+
+}  // namespace vla

@@ -1,0 +1,223 @@
+// Token-by-token VLA scan: one workgroup per (batch, head), A and S resident in registers.
+//
+// Paper Section 3.3 (eq. (sm), eq. (s-update)), read-out numerator of eq. (output).
+//
+// Thread layout (2*D threads): thread i in [0, D) owns row i of A, thread D+i owns row i of S,
+// each as D floats in VGPRs.  Tokens are staged through LDS in tiles of kTile tokens (coalesced
+// global loads, bf16 widened on the way in); the per-token vectors are read back from LDS as
+// broadcasts, so the matrix-vector products need no cross-lane reduction.
+//
+// Per token, with z' = A_{t-1} k (raw key), n = max(||k||, eps):
+//   k^ = k/n, z = z'/n, delta = max(1 + (k.z')/n^2, eps),  A -= z z^T / delta
+//   A_t k^ = z/delta (holds because u = k^), so alpha^ = z' * ca with
+//   ca = 1 / (n delta max(||z'||/(n delta), eps))
+//   e = v - (S_{t-1} k)/n,  S += e alpha^^T,  o = S_{t-1} q + e (alpha^ . q)  ( = S_t q )
+// Only four scalars (k.k, k.z', z'.z', z'.q) need a cross-thread reduction, so one barrier per
+// token suffices (the exchange buffers are double-buffered on token parity).
+#include "vla_common.h"
+
+namespace vla {
+namespace {
+
+constexpr int kTile = 32;  // tokens per LDS tile; even, so token parity == in-tile parity
+
+__device__ __forceinline__ void load4(const float* p, float out[4]) {
+  const float4 x = *reinterpret_cast<const float4*>(p);
+  out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;
+}
+__device__ __forceinline__ void load4(const uint16_t* p, float out[4]) {
+  const uint2 x = *reinterpret_cast<const uint2*>(p);
+  out[0] = bf16_to_f32(static_cast<uint16_t>(x.x & 0xffffu));
+  out[1] = bf16_to_f32(static_cast<uint16_t>(x.x >> 16));
+  out[2] = bf16_to_f32(static_cast<uint16_t>(x.y & 0xffffu));
+  out[3] = bf16_to_f32(static_cast<uint16_t>(x.y >> 16));
+}
+__device__ __forceinline__ void store1(float* p, float x) { *p = x; }
+__device__ __forceinline__ void store1(uint16_t* p, float x) { *p = f32_to_bf16_rne(x); }
+
+template <int D, typename IO>
+__global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
+  constexpr int NT = 2 * D;
+  constexpr int RED_LANES = D < 64 ? D : 64;  // A-role lanes that share one wave
+  constexpr int NWA = (D + 63) / 64;          // waves publishing partial sums
+
+  __shared__ __align__(16) float qs[kTile * D];
+  __shared__ __align__(16) float ks[kTile * D];
+  __shared__ __align__(16) float vs[kTile * D];
+  __shared__ __align__(16) float zb[2][D];
+  __shared__ __align__(16) float red[2][NWA][4];
+
+  const int head = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int role = tid / D;  // 0: a row of A, 1: a row of S
+  const int i = tid - role * D;
+  const int T = a.T;
+
+  float row[D];
+  {
+    const float* src = role == 0 ? a.A0 : a.S0;
+    if (src != nullptr) {
+      const float* p = src + (static_cast<size_t>(head) * D + i) * D;
+#pragma unroll
+      for (int j = 0; j < D; j += 4) load4(p + j, &row[j]);
+    } else {
+      const float diag = role == 0 ? 1.0f / a.lambda0 : 0.0f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) row[j] = (j == i) ? diag : 0.0f;
+    }
+  }
+
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+  const float eps = a.eps;
+
+  for (int t0 = 0; t0 < T; t0 += kTile) {
+    const int nt = (T - t0) < kTile ? (T - t0) : kTile;
+    __syncthreads();  // every thread is done with the previous tile
+    for (int idx = tid; idx < nt * (D / 4); idx += NT) {
+      const size_t off = static_cast<size_t>(t0) * D + static_cast<size_t>(idx) * 4;
+      float x[4];
+      load4(qh + off, x);
+      *reinterpret_cast<float4*>(&qs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+      load4(kh + off, x);
+      *reinterpret_cast<float4*>(&ks[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+      load4(vh + off, x);
+      *reinterpret_cast<float4*>(&vs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+    }
+    __syncthreads();
+
+    for (int tt = 0; tt < nt; ++tt) {
+      const int par = tt & 1;
+      const float4* k4 = reinterpret_cast<const float4*>(&ks[tt * D]);
+      const float4* q4 = reinterpret_cast<const float4*>(&qs[tt * D]);
+
+      // ---- matrix-vector products against the pre-update state
+      float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;  // role 0: z' = A k ; role 1: p' = S k
+      float r0 = 0.f, r1 = 0.f, r2 = 0.f, r3 = 0.f;  // role 1: r = S q
+      if (role == 0) {
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 kk = k4[j / 4];
+          m0 = fmaf(row[j + 0], kk.x, m0);
+          m1 = fmaf(row[j + 1], kk.y, m1);
+          m2 = fmaf(row[j + 2], kk.z, m2);
+          m3 = fmaf(row[j + 3], kk.w, m3);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 kk = k4[j / 4];
+          const float4 qq = q4[j / 4];
+          m0 = fmaf(row[j + 0], kk.x, m0);
+          m1 = fmaf(row[j + 1], kk.y, m1);
+          m2 = fmaf(row[j + 2], kk.z, m2);
+          m3 = fmaf(row[j + 3], kk.w, m3);
+          r0 = fmaf(row[j + 0], qq.x, r0);
+          r1 = fmaf(row[j + 1], qq.y, r1);
+          r2 = fmaf(row[j + 2], qq.z, r2);
+          r3 = fmaf(row[j + 3], qq.w, r3);
+        }
+      }
+      const float mv = (m0 + m1) + (m2 + m3);
+      const float rv = (r0 + r1) + (r2 + r3);
+
+      // ---- the four scalars that need all of z': partial sums per wave, then through LDS
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+      if (role == 0) {
+        const float ki = ks[tt * D + i];
+        const float qi = qs[tt * D + i];
+        s0 = ki * ki;
+        s1 = ki * mv;
+        s2 = mv * mv;
+        s3 = mv * qi;
+        zb[par][i] = mv;
+      }
+#pragma unroll
+      for (int off = RED_LANES / 2; off >= 1; off >>= 1) {
+        s0 += __shfl_xor(s0, off);
+        s1 += __shfl_xor(s1, off);
+        s2 += __shfl_xor(s2, off);
+        s3 += __shfl_xor(s3, off);
+      }
+      if (role == 0 && (i % RED_LANES) == 0) {
+        *reinterpret_cast<float4*>(&red[par][i / RED_LANES][0]) = make_float4(s0, s1, s2, s3);
+      }
+      __syncthreads();
+
+      float kk = 0.f, kz = 0.f, zz = 0.f, zq = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWA; ++w) {
+        const float4 p = *reinterpret_cast<const float4*>(&red[par][w][0]);
+        kk += p.x; kz += p.y; zz += p.z; zq += p.w;
+      }
+      const float n = fmaxf(sqrtf(kk), eps);
+      const float inv_n = 1.0f / n;
+      const float delta = fmaxf(1.0f + kz * inv_n * inv_n, eps);
+      const float inv_nd = inv_n / delta;                 // z'/(n delta) = A_t k^
+      const float aden = fmaxf(sqrtf(zz) * inv_nd, eps);  // max(||A_t k^||, eps)
+      const float ca = inv_nd / aden;                     // alpha^ = z' * ca
+      const float4* z4 = reinterpret_cast<const float4*>(&zb[par][0]);
+
+      if (role == 0) {
+        const float f = -(mv * inv_n) * inv_nd;  // -(z_i / delta)
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 zj = z4[j / 4];
+          row[j + 0] = fmaf(f, zj.x, row[j + 0]);
+          row[j + 1] = fmaf(f, zj.y, row[j + 1]);
+          row[j + 2] = fmaf(f, zj.z, row[j + 2]);
+          row[j + 3] = fmaf(f, zj.w, row[j + 3]);
+        }
+      } else {
+        const float e = vs[tt * D + i] - mv * inv_n;
+        const float g = e * ca;
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 zj = z4[j / 4];
+          row[j + 0] = fmaf(g, zj.x, row[j + 0]);
+          row[j + 1] = fmaf(g, zj.y, row[j + 1]);
+          row[j + 2] = fmaf(g, zj.z, row[j + 2]);
+          row[j + 3] = fmaf(g, zj.w, row[j + 3]);
+        }
+        store1(oh + static_cast<size_t>(t0 + tt) * D + i, fmaf(g, zq, rv));
+      }
+    }
+  }
+
+  float* dst = role == 0 ? a.A_T : a.S_T;
+  if (dst != nullptr) {
+    float* p = dst + (static_cast<size_t>(head) * D + i) * D;
+#pragma unroll
+    for (int j = 0; j < D; j += 4) {
+      *reinterpret_cast<float4*>(p + j) = make_float4(row[j], row[j + 1], row[j + 2], row[j + 3]);
+    }
+  }
+}
+
+template <int D, typename IO>
+hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
+  // hipLaunchKernel reports this launch's own status; the sticky hipGetLastError() value may
+  // belong to an unrelated earlier call made by the host program.
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_kernel<D, IO>), dim3(a.n_heads),
+                         dim3(2 * D), params, 0, stream);
+}
+
+}  // namespace
+
+hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 16: return bf ? launch<16, uint16_t>(a, stream) : launch<16, float>(a, stream);
+    case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
+    case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
+    case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace vla

@@ -1,0 +1,87 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/vla.h declares, and
+rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_11196_amd as vla
+from paper_2605_11196_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "vla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vla_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = vla.load_library()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings():
+    assert vla.version() >= 100
+    assert vla.status_string(0) == "VLA_OK"
+    assert vla.status_string(1) == "VLA_ERR_INVALID_ARG"
+    assert vla.status_string(2) == "VLA_ERR_UNSUPPORTED"
+    assert vla.status_string(3) == "VLA_ERR_WORKSPACE"
+    assert vla.status_string(4) == "VLA_ERR_HIP"
+    assert vla.status_string(99) == "VLA_ERR_UNKNOWN"
+
+
+def test_default_opts():
+    o = binding.VlaOpts()
+    vla.load_library().vla_default_opts(ctypes.byref(o))
+    assert abs(o.lambda0 - 0.1) < 1e-7 and abs(o.eps - 1e-4) < 1e-10 and o.mode == vla.MODE_AUTO
+
+
+FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on these paths
+
+
+def call(**kw):
+    a = dict(q=FAKE, k=FAKE + 0x1000, v=FAKE + 0x2000, S0=0, A0=0, o=FAKE + 0x3000, S_T=0, A_T=0,
+             B=1, H=1, T=8, d_k=16, d_v=16, io_dtype=vla.VLA_F32)
+    opt = dict(lambda0=None, eps=None, mode=None, workspace=0, workspace_bytes=0)
+    for key, val in kw.items():
+        (a if key in a else opt)[key] = val
+    return vla.vla_forward_raw(a["q"], a["k"], a["v"], a["S0"], a["A0"], a["o"], a["S_T"], a["A_T"],
+                               a["B"], a["H"], a["T"], a["d_k"], a["d_v"], a["io_dtype"], **opt)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), 1), (dict(H=-1), 1), (dict(T=-1), 1), (dict(d_k=0, d_v=0), 1),
+    (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
+    (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
+    (dict(o=FAKE), 1),                       # o aliases q
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=32), 2), (dict(d_k=256, d_v=256), 2),
+])
+def test_host_side_validation_returns_status_without_launch(kw, status):
+    assert call(**kw) == status
+
+
+def test_zero_tokens_without_state_outputs_is_ok_and_launches_nothing():
+    assert call(T=0, q=0, k=0, v=0, o=0) == 0
+
+
+def test_workspace_query_and_mode_resolution():
+    assert vla.vla_forward_workspace_bytes(1, 1, 8, 16, 16, vla.VLA_F32, mode=vla.MODE_SCAN) == 0
+    assert vla.vla_forward_workspace_bytes(0, 1, 8, 16, 16, vla.VLA_F32) == 0
+    assert vla.resolve_mode(1, 1, 8, 16, 16, vla.VLA_F32, mode=vla.MODE_SCAN) == vla.MODE_SCAN
+    assert vla.resolve_mode(1, 1, 8, 48, 48, vla.VLA_F32) == -1
+    m = vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16)
+    assert m in (vla.MODE_SCAN, vla.MODE_CHUNKED, vla.MODE_TWO_PHASE)
+
+
+def test_torch_front_end_refuses_cpu_tensors():
+    import torch
+
+    x = torch.zeros(1, 1, 4, 16)
+    with pytest.raises(ValueError):
+        vla.vla_forward(x, x, x)
