@@ -31,12 +31,16 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   return VLA_OK;
 }
 
-int pick_mode(int /*B*/, int /*H*/, int /*T*/, int /*d*/, int /*io_dtype*/, const vla_opts& o) {
+int pick_mode(int /*B*/, int /*H*/, int /*T*/, int d, int /*io_dtype*/, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
-  return VLA_MODE_SCAN;
+  return vla::chunk_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
 }
 
-bool mode_available(int mode) { return mode == VLA_MODE_SCAN; }
+bool mode_available(int mode, int d) {
+  if (mode == VLA_MODE_SCAN) return true;
+  if (mode == VLA_MODE_CHUNKED) return vla::chunk_supported(d);
+  return false;
+}
 
 }  // namespace
 
@@ -66,7 +70,7 @@ int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const 
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return -1;
   const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  return mode_available(mode) ? mode : -1;
+  return mode_available(mode, d_k) ? mode : -1;
 }
 
 size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
@@ -93,7 +97,7 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
 
   const int mode = pick_mode(B, H, T, d_k, io_dtype, op);
-  if (!mode_available(mode)) return VLA_ERR_UNSUPPORTED;
+  if (!mode_available(mode, d_k)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return VLA_ERR_WORKSPACE;
   if (T == 0 && S_T == nullptr && A_T == nullptr) return VLA_OK;  // nothing to compute or copy
@@ -110,6 +114,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   switch (mode) {
     case VLA_MODE_SCAN:
       err = vla::launch_scan(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      break;
+    case VLA_MODE_CHUNKED:
+      err = vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
       break;
     default:
       return VLA_ERR_UNSUPPORTED;

@@ -1,0 +1,438 @@
+// Block ("chunked") form of the VLA recurrence on FP32 MFMA, 16 tokens per block.
+//
+// Same recurrence as paper Section 3.3 (eq. (sm), eq. (s-update)) and the read-out numerator of
+// eq. (output); within a block of C = 16 tokens the token-by-token matrix-vector work is regrouped
+// into dense products, which is exact algebra (results differ only in float32 rounding order).
+//
+// With A0, S0 the state entering the block, K^ (C x d) the normalised keys, Q, V the queries and
+// values of the block (rows = tokens), and u = k^:
+//
+//   Y^T = K^ A0                                   (C x d)      z before the in-block corrections
+//   G   = Y^T K^^T ,  GQ = Y^T Q^T                (C x C)      Gram matrices in the A0 metric
+//   I + G = L L^T                                 (Cholesky)   L_tt = sqrt(delta_t), L_ts = w_s . k^_t
+//   W^T = L^{-1} Y^T                              (C x d)      w_t = z_t / sqrt(delta_t)
+//   A1  = A0 - W W^T                                           C Sherman-Morrison steps at once
+//   alpha^_t = c_t w_t ,  c_t = (1/L_tt) / max(||w_t|| / L_tt, eps)       (A_t k^_t = w_t / L_tt)
+//   F^T = V - K^ S0^T                             (C x d_v)    residuals against the entering state
+//   E^T = Z F^T ,  Z = (I + strict_lower(L) diag(c))^{-1}      residuals e_t of the recurrence
+//   O^T = Q S0^T + NQ^T E^T ,  NQ[s][t] = c_s (L^{-1} GQ)[s][t] for s <= t, else 0
+//   S1^T = S0^T + W diag(c) E^T
+//
+// A zero key gives an all-zero row in Y, W and E, so padding the last block with zero tokens is exact.
+//
+// Work split: NW waves per (batch, head); wave w owns columns [SL*w, SL*w+SL) of A and the same rows of
+// S, as 16x16 MFMA accumulator tiles that stay in VGPRs for the whole sequence (A is symmetric, so an
+// accumulator tile of A can be fed straight back as the B operand).  The C x C factorisations run on
+// one wave (rotating with the block index) with lanes = rows and v_readlane broadcasts.
+//
+// v_mfma_f32_16x16x4_f32 register layout, lane l = 16*g + c:
+//   A operand: A[m = c][k = g]      B operand: B[k = g][n = c]      C/D: reg r -> D[m = 4g + r][n = c]
+#include "vla_common.h"
+
+namespace vla {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int C = 16;       // tokens per block
+constexpr int LT = C + 4;   // row stride (floats) of the 16-column LDS arrays: conflict-free b128 rows
+
+__device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float readlane(float x, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+__device__ __forceinline__ f4 lds4(const float* p) { return *reinterpret_cast<const f4*>(p); }
+
+__device__ __forceinline__ float io_load(const float* p) { return *p; }
+__device__ __forceinline__ float io_load(const uint16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void io_store(float* p, float x) { *p = x; }
+__device__ __forceinline__ void io_store(uint16_t* p, float x) { *p = f32_to_bf16_rne(x); }
+
+// A staged row segment of EPT consecutive elements, held in its raw (packed) form until it is used.
+template <typename IO, int EPT> struct RawRow;
+template <int EPT> struct RawRow<float, EPT> {
+  float4 v[EPT / 4];
+  __device__ __forceinline__ void load(const float* p) {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const float4*>(p + 4 * e);
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) v[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) {
+      x[4 * e] = v[e].x; x[4 * e + 1] = v[e].y; x[4 * e + 2] = v[e].z; x[4 * e + 3] = v[e].w;
+    }
+  }
+};
+template <int EPT> struct RawRow<uint16_t, EPT> {
+  uint4 v[EPT / 8];
+  __device__ __forceinline__ void load(const uint16_t* p) {
+#pragma unroll
+    for (int e = 0; e < EPT / 8; ++e) v[e] = *reinterpret_cast<const uint4*>(p + 8 * e);
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int e = 0; e < EPT / 8; ++e) v[e] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
+#pragma unroll
+    for (int e = 0; e < EPT / 8; ++e) {
+      const uint32_t u[4] = {v[e].x, v[e].y, v[e].z, v[e].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[8 * e + 2 * i] = __uint_as_float(u[i] << 16);
+        x[8 * e + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+      }
+    }
+  }
+};
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t x) { return bf16_to_f32(x); }
+
+template <int D, int NW, typename IO>
+__global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
+  constexpr int SL = D / NW;       // columns of A (rows of S) owned by one wave
+  constexpr int NJ = SL / 16;      // 16-wide tiles in a slab
+  constexpr int NB = D / 16;       // 16-row blocks over the whole head dimension
+  constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
+  constexpr int NT = 64 * NW;
+  constexpr int EPT = C * D / NT;  // staged elements per thread per tensor
+  constexpr int TPR = D / EPT;     // threads per token row
+  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
+
+  __shared__ __align__(16) float Ks[C * LD];          // K^  [t][j]
+  __shared__ __align__(16) float Qs[C * LD];          // Q   [t][j]
+  __shared__ __align__(16) float Ys[C * LD];          // Y^T [t][j] (each wave touches only its columns)
+  __shared__ __align__(16) float Wb[D * LT];          // W   [j][t]
+  __shared__ __align__(16) float Gp[NW][2][C * LT];   // per-wave partial Gram matrices G, GQ  [s][t]
+  __shared__ __align__(16) float Lis[C * LT];         // L^{-1} [t][s]
+  __shared__ __align__(16) float Zs[C * LT];          // Z   [t][s]
+  __shared__ __align__(16) float NQs[C * LT];         // NQ^T [t][s]
+  __shared__ __align__(16) float wn2p[NW][C];         // per-wave partial ||w_t||^2
+  __shared__ __align__(16) float cvec[C];             // c_t
+
+  const int head = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int w = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int T = a.T;
+  const float eps = a.eps;
+  const int col0 = SL * w;  // first column of this wave's slab
+
+  // ---- resident state: accumulator tiles
+  // At[b][jn][r] = A[16b + 4g + r][col0 + 16jn + c]
+  // St[b][jn][r] = S[col0 + 16jn + c][16b + 4g + r]      (i.e. tiles of S^T)
+  f4 At[NB][NJ], St[NB][NJ];
+  {
+    const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float diag = 1.0f / a.lambda0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = 16 * b + 4 * g + r, col = col0 + 16 * jn + c;
+          At[b][jn][r] = A0 ? A0[static_cast<size_t>(row) * D + col] : (row == col ? diag : 0.0f);
+          St[b][jn][r] = S0 ? S0[static_cast<size_t>(col) * D + row] : 0.0f;
+        }
+  }
+
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+
+  // staging role of this thread: token row and column segment
+  const int srow = tid / TPR;
+  const int sseg = (tid % TPR) * EPT;
+
+  RawRow<IO, EPT> kpre, qpre;
+  IO vpre[NJ][4];  // V^T in accumulator layout: V[t0 + 4g + r][col0 + 16jn + c]
+
+  auto prefetch = [&](int t0) {
+    if (t0 + srow < T) {
+      kpre.load(kh + static_cast<size_t>(t0 + srow) * D + sseg);
+      qpre.load(qh + static_cast<size_t>(t0 + srow) * D + sseg);
+    } else {
+      kpre.zero();
+      qpre.zero();
+    }
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = t0 + 4 * g + r;
+        vpre[jn][r] = t < T ? vh[static_cast<size_t>(t) * D + col0 + 16 * jn + c] : IO(0);
+      }
+  };
+
+  if (T > 0) prefetch(0);
+
+  int blk = 0;
+  for (int t0 = 0; t0 < T; t0 += C, ++blk) {
+    // ================= stage K^ (normalised) and Q into LDS
+    {
+      float kx[EPT];
+      kpre.unpack(kx);
+      float ss = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
+#pragma unroll
+      for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
+#pragma unroll
+      for (int e = 0; e < EPT; e += 4) {
+        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) =
+            f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+      }
+      qpre.unpack(kx);
+#pragma unroll
+      for (int e = 0; e < EPT; e += 4) {
+        *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
+      }
+    }
+    f4 ft[NJ];  // starts as V^T, becomes F^T = V^T - P^T
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn)
+      ft[jn] = f4{widen(vpre[jn][0]), widen(vpre[jn][1]), widen(vpre[jn][2]), widen(vpre[jn][3])};
+    __syncthreads();  // (1) K^, Q visible
+    if (t0 + C < T) prefetch(t0 + C);
+
+    // ================= Y^T = K^ A0, P^T = K^ S0^T, R^T = Q S0^T  (this wave's columns)
+    f4 yt[NJ], pt[NJ], rt[NJ];
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn) { yt[jn] = f4{0, 0, 0, 0}; pt[jn] = f4{0, 0, 0, 0}; rt[jn] = f4{0, 0, 0, 0}; }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
+      const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int jn = 0; jn < NJ; ++jn) {
+          yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
+          pt[jn] = mfma16(ka[r], St[b][jn][r], pt[jn]);
+          rt[jn] = mfma16(qa[r], St[b][jn][r], rt[jn]);
+        }
+    }
+
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn) ft[jn] -= pt[jn];
+
+    // ================= partial Gram matrices over this wave's columns
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Ys[(4 * g + r) * LD + col0 + 16 * jn + c] = yt[jn][r];
+    {
+      f4 gg = f4{0, 0, 0, 0}, gq = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+        const int o4 = c * LD + col0 + 16 * jn + 4 * g;
+        const f4 ya = lds4(&Ys[o4]);  // same-wave write -> read: LDS operations of one wave are ordered
+        const f4 kb = lds4(&Ks[o4]);
+        const f4 qb = lds4(&Qs[o4]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          gg = mfma16(ya[r], kb[r], gg);
+          gq = mfma16(ya[r], qb[r], gq);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        Gp[w][0][(4 * g + r) * LT + c] = gg[r];
+        Gp[w][1][(4 * g + r) * LT + c] = gq[r];
+      }
+    }
+    __syncthreads();  // (2) partial Grams visible
+
+    // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
+    const int sw = (blk + head) % NW;  // rotate the serial role over the waves (and SIMDs)
+    float m[C];        // lane c: row c of I + G, overwritten by row c of L
+    float rinv[C];     // uniform: 1 / L_tt
+    float dl = 1.0f;   // lane c: L_cc
+    if (w == sw) {
+#pragma unroll
+      for (int s4 = 0; s4 < C; s4 += 4) {
+        f4 acc = lds4(&Gp[0][0][c * LT + s4]);
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) acc += lds4(&Gp[ww][0][c * LT + s4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == c ? 1.0f : 0.0f);
+      }
+#pragma unroll
+      for (int t = 0; t < C; ++t) {
+        const float p = readlane(m[t], t);
+        const float ri = 1.0f / sqrtf(p);
+        rinv[t] = ri;
+        const float li = m[t] * ri;  // column t of L (meaningful for rows >= t)
+        m[t] = li;
+        dl = (c == t) ? li : dl;
+#pragma unroll
+        for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
+      }
+      // X = L^{-1}: lane c holds column c, X[t] = L^{-1}[t][c]
+      float X[C];
+#pragma unroll
+      for (int t = 0; t < C; ++t) {
+        float acc = (c == t) ? 1.0f : 0.0f;
+#pragma unroll
+        for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), X[s], acc);
+        X[t] = acc * rinv[t];
+      }
+      if (g == 0) {
+#pragma unroll
+        for (int t = 0; t < C; ++t) Lis[t * LT + c] = X[t];
+      }
+    }
+    __syncthreads();  // (3) L^{-1} visible
+
+    // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
+    const f4 la = lds4(&Lis[c * LT + 4 * g]);
+    f4 wt[NJ];
+    {
+      f4 n2 = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+        f4 acc = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc = mfma16(la[r], yt[jn][r], acc);
+        wt[jn] = acc;
+        n2 += acc * acc;
+        *reinterpret_cast<f4*>(&Wb[(col0 + 16 * jn + c) * LT + 4 * g]) = acc;
+      }
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) n2[r] += __shfl_xor(n2[r], off);
+      }
+      if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
+    }
+    __syncthreads();  // (4) W and the norm partials visible
+
+    // ================= phase 2 (same wave): c_t, Z, NQ
+    if (w == sw) {
+      float wn2 = 0.0f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
+      const float an = sqrtf(wn2) / dl;               // ||A_t k^_t|| = ||w_t|| / L_tt
+      const float cs = (1.0f / dl) / fmaxf(an, eps);  // alpha^_t = c_t w_t
+      if (g == 0) cvec[c] = cs;
+      // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c
+      float Zr[C];
+#pragma unroll
+      for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);  // lane t: L[t][s] c_s
+#pragma unroll
+      for (int t = 0; t < C; ++t) {
+        float acc = (c == t) ? 1.0f : 0.0f;
+#pragma unroll
+        for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), Zr[s], acc);
+        Zr[t] = acc;
+      }
+      if (g == 0) {
+#pragma unroll
+        for (int t = 0; t < C; ++t) Zs[t * LT + c] = Zr[t];
+      }
+      // H = L^{-1} GQ (one MFMA tile), NQ[s][t] = c_s H[s][t] for s <= t
+      f4 hq = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float gqv = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) gqv += Gp[ww][1][(4 * g + r) * LT + c];
+        hq = mfma16(la[r], gqv, hq);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int s = 4 * g + r;
+        const float csr = __shfl(cs, s);
+        NQs[c * LT + s] = (s <= c) ? csr * hq[r] : 0.0f;
+      }
+    }
+    __syncthreads();  // (5) Z, NQ, c visible
+
+    // ================= E^T = Z F^T, O^T = R^T + NQ^T E^T, store o
+    const f4 za = lds4(&Zs[c * LT + 4 * g]);
+    const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
+    const f4 cg = lds4(&cvec[4 * g]);
+    f4 ce[NJ], nwt[NJ];
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn) {
+      f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[jn][r], et);
+      f4 ot = rt[jn];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = t0 + 4 * g + r;
+        if (t < T) io_store(oh + static_cast<size_t>(t) * D + col0 + 16 * jn + c, ot[r]);
+      }
+      ce[jn] = et * cg;
+      nwt[jn] = -wt[jn];
+    }
+
+    // ================= A -= W W^T ,  S^T += W diag(c) E^T
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 wa = lds4(&Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int jn = 0; jn < NJ; ++jn) {
+          At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
+          St[b][jn] = mfma16(wa[r], ce[jn][r], St[b][jn]);
+        }
+    }
+  }
+
+  // ---- final state
+  {
+    float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
+    float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = 16 * b + 4 * g + r, col = col0 + 16 * jn + c;
+          if (AT) AT[static_cast<size_t>(row) * D + col] = At[b][jn][r];
+          if (ST) ST[static_cast<size_t>(col) * D + row] = St[b][jn][r];
+        }
+  }
+}
+
+template <int D, int NW, typename IO>
+hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO>), dim3(a.n_heads),
+                         dim3(64 * NW), params, 0, stream);
+}
+
+}  // namespace
+
+bool chunk_supported(int d) { return d == 64 || d == 128; }
+
+hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
+    case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace vla

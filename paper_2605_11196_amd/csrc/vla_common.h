@@ -35,4 +35,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // Token-by-token scan, one workgroup per head (vla_scan.hip).
 hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
+
+// Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 64 and 128.
+bool chunk_supported(int d);
+hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+
 }  // namespace vla
