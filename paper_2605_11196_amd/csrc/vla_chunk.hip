@@ -134,16 +134,27 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
     const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
     const float diag = 1.0f / a.lambda0;
+    const int arc = (4 * g) * D + col0 + c;  // A[4g][col0 + c]
+    const int src = (col0 + c) * D + 4 * g;  // S[col0 + c][4g]
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn)
+      for (int jn = 0; jn < NJ; ++jn) {
+        if (A0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = 16 * b + 4 * g + r, col = col0 + 16 * jn + c;
-          At[b][jn][r] = A0 ? A0[static_cast<size_t>(row) * D + col] : (row == col ? diag : 0.0f);
-          St[b][jn][r] = S0 ? S0[static_cast<size_t>(col) * D + row] : 0.0f;
+          for (int r = 0; r < 4; ++r) At[b][jn][r] = A0[arc + (16 * b + r) * D + 16 * jn];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            At[b][jn][r] = (16 * b + 4 * g + r == col0 + 16 * jn + c) ? diag : 0.0f;
         }
+        if (S0) {
+          const float4 x = *reinterpret_cast<const float4*>(S0 + src + 16 * jn * D + 16 * b);
+          St[b][jn] = f4{x.x, x.y, x.z, x.w};
+        } else {
+          St[b][jn] = f4{0, 0, 0, 0};
+        }
+      }
   }
 
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
@@ -155,25 +166,33 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   // staging role of this thread: token row and column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
+  const int vcol = col0 + c;  // first column this lane touches in accumulator layout
 
   RawRow<IO, EPT> kpre, qpre;
   IO vpre[NJ][4];  // V^T in accumulator layout: V[t0 + 4g + r][col0 + 16jn + c]
 
+  // Loads for the block starting at t0.  Rows past the end are read from the last valid row and
+  // zeroed afterwards, so there is no divergent branch around the loads.
   auto prefetch = [&](int t0) {
-    if (t0 + srow < T) {
-      kpre.load(kh + static_cast<size_t>(t0 + srow) * D + sseg);
-      qpre.load(qh + static_cast<size_t>(t0 + srow) * D + sseg);
-    } else {
+    const int tr = t0 + srow;
+    const int trc = tr < T ? tr : T - 1;
+    kpre.load(kh + static_cast<size_t>(trc) * D + sseg);
+    qpre.load(qh + static_cast<size_t>(trc) * D + sseg);
+    if (tr >= T) {
       kpre.zero();
       qpre.zero();
     }
 #pragma unroll
-    for (int jn = 0; jn < NJ; ++jn)
+    for (int r = 0; r < 4; ++r) {
+      const int t = t0 + 4 * g + r;
+      const int tc = t < T ? t : T - 1;
+      const IO* vp = vh + static_cast<size_t>(tc) * D + vcol;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = t0 + 4 * g + r;
-        vpre[jn][r] = t < T ? vh[static_cast<size_t>(t) * D + col0 + 16 * jn + c] : IO(0);
+      for (int jn = 0; jn < NJ; ++jn) {
+        const IO x = vp[16 * jn];
+        vpre[jn][r] = t < T ? x : IO(0);
       }
+    }
   };
 
   if (T > 0) prefetch(0);
@@ -208,26 +227,22 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     __syncthreads();  // (1) K^, Q visible
     if (t0 + C < T) prefetch(t0 + C);
 
-    // ================= Y^T = K^ A0, P^T = K^ S0^T, R^T = Q S0^T  (this wave's columns)
-    f4 yt[NJ], pt[NJ], rt[NJ];
+    // ================= Y^T = K^ A0 and F^T = V^T - K^ S0^T  (this wave's columns)
+    f4 yt[NJ];
 #pragma unroll
-    for (int jn = 0; jn < NJ; ++jn) { yt[jn] = f4{0, 0, 0, 0}; pt[jn] = f4{0, 0, 0, 0}; rt[jn] = f4{0, 0, 0, 0}; }
+    for (int jn = 0; jn < NJ; ++jn) yt[jn] = f4{0, 0, 0, 0};
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
-      const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
+      const f4 nka = -ka;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int jn = 0; jn < NJ; ++jn) {
           yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
-          pt[jn] = mfma16(ka[r], St[b][jn][r], pt[jn]);
-          rt[jn] = mfma16(qa[r], St[b][jn][r], rt[jn]);
+          ft[jn] = mfma16(nka[r], St[b][jn][r], ft[jn]);
         }
     }
-
-#pragma unroll
-    for (int jn = 0; jn < NJ; ++jn) ft[jn] -= pt[jn];
 
     // ================= partial Gram matrices over this wave's columns
 #pragma unroll
@@ -259,7 +274,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
     const int sw = (blk + head) % NW;  // rotate the serial role over the waves (and SIMDs)
     float m[C];        // lane c: row c of I + G, overwritten by row c of L
-    float rinv[C];     // uniform: 1 / L_tt
     float dl = 1.0f;   // lane c: L_cc
     if (w == sw) {
 #pragma unroll
@@ -270,10 +284,12 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == c ? 1.0f : 0.0f);
       }
+      float rinv[C];  // uniform: 1 / L_tt
 #pragma unroll
       for (int t = 0; t < C; ++t) {
-        const float p = readlane(m[t], t);
-        const float ri = 1.0f / sqrtf(p);
+        const float p = readlane(m[t], t);  // pivot = delta_t >= 1
+        float ri = __builtin_amdgcn_rsqf(p);
+        ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);  // one Newton step on 1/sqrt(p)
         rinv[t] = ri;
         const float li = m[t] * ri;  // column t of L (meaningful for rows >= t)
         m[t] = li;
@@ -299,7 +315,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
     const f4 la = lds4(&Lis[c * LT + 4 * g]);
-    f4 wt[NJ];
+    f4 nwt[NJ];  // -W^T
     {
       f4 n2 = f4{0, 0, 0, 0};
 #pragma unroll
@@ -307,7 +323,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         f4 acc = f4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc = mfma16(la[r], yt[jn][r], acc);
-        wt[jn] = acc;
+        nwt[jn] = -acc;
         n2 += acc * acc;
         *reinterpret_cast<f4*>(&Wb[(col0 + 16 * jn + c) * LT + 4 * g]) = acc;
       }
@@ -325,13 +341,14 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       float wn2 = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
-      const float an = sqrtf(wn2) / dl;               // ||A_t k^_t|| = ||w_t|| / L_tt
-      const float cs = (1.0f / dl) / fmaxf(an, eps);  // alpha^_t = c_t w_t
+      const float rdl = 1.0f / dl;
+      const float an = sqrtf(wn2) * rdl;       // ||A_t k^_t|| = ||w_t|| / L_tt
+      const float cs = rdl / fmaxf(an, eps);   // alpha^_t = c_t w_t
       if (g == 0) cvec[c] = cs;
       // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c
-      float Zr[C];
 #pragma unroll
       for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);  // lane t: L[t][s] c_s
+      float Zr[C];
 #pragma unroll
       for (int t = 0; t < C; ++t) {
         float acc = (c == t) ? 1.0f : 0.0f;
@@ -361,26 +378,45 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     }
     __syncthreads();  // (5) Z, NQ, c visible
 
-    // ================= E^T = Z F^T, O^T = R^T + NQ^T E^T, store o
-    const f4 za = lds4(&Zs[c * LT + 4 * g]);
-    const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
-    const f4 cg = lds4(&cvec[4 * g]);
-    f4 ce[NJ], nwt[NJ];
+    // ================= E^T = Z F^T, R^T = Q S0^T, O^T = R^T + NQ^T E^T, store o
+    f4 ce[NJ];
+    {
+      const f4 za = lds4(&Zs[c * LT + 4 * g]);
 #pragma unroll
-    for (int jn = 0; jn < NJ; ++jn) {
-      f4 et = f4{0, 0, 0, 0};
+      for (int jn = 0; jn < NJ; ++jn) {
+        f4 et = f4{0, 0, 0, 0};
 #pragma unroll
-      for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[jn][r], et);
-      f4 ot = rt[jn];
+        for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[jn][r], et);
+        ft[jn] = et;
+      }
+      f4 ot[NJ];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+      for (int jn = 0; jn < NJ; ++jn) ot[jn] = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int jn = 0; jn < NJ; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
+      }
+      const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
+      const f4 cg = lds4(&cvec[4 * g]);
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ot[jn] = mfma16(nqa[r], ft[jn][r], ot[jn]);
+        ce[jn] = ft[jn] * cg;
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int t = t0 + 4 * g + r;
-        if (t < T) io_store(oh + static_cast<size_t>(t) * D + col0 + 16 * jn + c, ot[r]);
+        if (t < T) {
+          IO* op = oh + static_cast<size_t>(t) * D + vcol;
+#pragma unroll
+          for (int jn = 0; jn < NJ; ++jn) io_store(op + 16 * jn, ot[jn][r]);
+        }
       }
-      ce[jn] = et * cg;
-      nwt[jn] = -wt[jn];
     }
 
     // ================= A -= W W^T ,  S^T += W diag(c) E^T
@@ -401,16 +437,23 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   {
     float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
     float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+    int g2 = g;
+    asm volatile("" : "+v"(g2));  // recompute the addresses here instead of carrying them over the loop
+    const int arc = (4 * g2) * D + col0 + c;
+    const int src = (col0 + c) * D + 4 * g2;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn)
+      for (int jn = 0; jn < NJ; ++jn) {
+        if (AT) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = 16 * b + 4 * g + r, col = col0 + 16 * jn + c;
-          if (AT) AT[static_cast<size_t>(row) * D + col] = At[b][jn][r];
-          if (ST) ST[static_cast<size_t>(col) * D + row] = St[b][jn][r];
+          for (int r = 0; r < 4; ++r) AT[arc + (16 * b + r) * D + 16 * jn] = At[b][jn][r];
         }
+        if (ST) {
+          *reinterpret_cast<float4*>(ST + src + 16 * jn * D + 16 * b) =
+              make_float4(St[b][jn][0], St[b][jn][1], St[b][jn][2], St[b][jn][3]);
+        }
+      }
   }
 }
 
