@@ -35,6 +35,7 @@ def parse_args():
     ap.add_argument("--workload", default="large_batch",
                     choices=["tiny", "norm_growth", "recall", "long_context", "large_batch"])
     ap.add_argument("--T", type=int, default=None, help="sequence length override (long_context)")
+    ap.add_argument("--B", type=int, default=None, help="batch override (experiments only)")
     ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=None, help="heads in the oracle timing sample")
@@ -59,6 +60,8 @@ def main():
         c["T"] = args.T or 65536
     elif args.T:
         c["T"] = args.T
+    if args.B:
+        c["B"] = args.B
     B, H, T, d = c["B"], c["H"], c["T"], c["d"]
     dtype = c["dtype"]
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32

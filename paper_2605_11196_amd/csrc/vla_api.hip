@@ -27,6 +27,8 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   if (o.mode < VLA_MODE_AUTO || o.mode > VLA_MODE_TWO_PHASE) return VLA_ERR_INVALID_ARG;
   if (!(o.lambda0 > 0.0f) || !(o.eps > 0.0f)) return VLA_ERR_INVALID_ARG;
   if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
+  // kernels address one head's [T, d] slab with 32-bit byte offsets
+  if (static_cast<long long>(T) * (d_k > d_v ? d_k : d_v) * 4 >= 0x7fffffffLL) return VLA_ERR_UNSUPPORTED;
   if (d_k != d_v || !supported_head_size(d_k)) return VLA_ERR_UNSUPPORTED;
   return VLA_OK;
 }
@@ -109,6 +111,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   a.T = T;
   a.lambda0 = op.lambda0;
   a.eps = op.eps;
+#ifdef VLA_DEBUG_STAMPS
+  a.dbg = workspace_bytes >= (1u << 20) ? static_cast<long long*>(workspace) : nullptr;
+#endif
 
   hipError_t err = hipSuccess;
   switch (mode) {

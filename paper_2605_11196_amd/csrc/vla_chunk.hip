@@ -112,9 +112,9 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   __shared__ __align__(16) float Gp[NW][2][C * LT];   // per-wave partial Gram matrices G, GQ  [s][t]
   __shared__ __align__(16) float Lis[C * LT];         // L^{-1} [t][s]
   __shared__ __align__(16) float Zs[C * LT];          // Z   [t][s]
-  __shared__ __align__(16) float NQs[C * LT];         // NQ^T [t][s]
+  __shared__ __align__(16) float NQs[C * LT];         // -NQ^T [t][s]
   __shared__ __align__(16) float wn2p[NW][C];         // per-wave partial ||w_t||^2
-  __shared__ __align__(16) float cvec[C];             // c_t
+  __shared__ __align__(16) float cvec[C];             // -c_t
 
   const int head = blockIdx.x;
   const int tid = threadIdx.x;
@@ -171,38 +171,40 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   RawRow<IO, EPT> kpre, qpre;
   IO vpre[NJ][4];  // V^T in accumulator layout: V[t0 + 4g + r][col0 + 16jn + c]
 
-  // Loads for the block starting at t0.  Rows past the end are read from the last valid row and
-  // zeroed afterwards, so there is no divergent branch around the loads.
+  // Loads for the block starting at t0.  Rows past the end are read from the last valid row (their
+  // values are replaced by zeros when the registers are consumed, one block later), so the loads need
+  // neither a branch nor a wait.  Offsets are 32-bit from the uniform per-head base pointers.
   auto prefetch = [&](int t0) {
     const int tr = t0 + srow;
-    const int trc = tr < T ? tr : T - 1;
-    kpre.load(kh + static_cast<size_t>(trc) * D + sseg);
-    qpre.load(qh + static_cast<size_t>(trc) * D + sseg);
-    if (tr >= T) {
-      kpre.zero();
-      qpre.zero();
-    }
+    const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+    kpre.load(kh + koff);
+    qpre.load(qh + koff);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int t = t0 + 4 * g + r;
-      const int tc = t < T ? t : T - 1;
-      const IO* vp = vh + static_cast<size_t>(tc) * D + vcol;
+      const unsigned voff = static_cast<unsigned>((t < T ? t : T - 1) * D + vcol);
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) {
-        const IO x = vp[16 * jn];
-        vpre[jn][r] = t < T ? x : IO(0);
-      }
+      for (int jn = 0; jn < NJ; ++jn) vpre[jn][r] = vh[voff + 16 * jn];
     }
   };
 
   if (T > 0) prefetch(0);
 
   int blk = 0;
+#ifdef VLA_DEBUG_STAMPS
+#define VLA_STAMP(pt) do { if (a.dbg && head == 0 && lane == 0 && blk < 256) a.dbg[(blk * 8 + (pt)) * NW + w] = clock64(); } while (0)
+#else
+#define VLA_STAMP(pt) do { } while (0)
+#endif
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
+    VLA_STAMP(0);
     // ================= stage K^ (normalised) and Q into LDS
     {
       float kx[EPT];
+      const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
       kpre.unpack(kx);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
       float ss = 0.0f;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
@@ -216,31 +218,34 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
       qpre.unpack(kx);
 #pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+#pragma unroll
       for (int e = 0; e < EPT; e += 4) {
         *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
       }
     }
-    f4 ft[NJ];  // starts as V^T, becomes F^T = V^T - P^T
+    f4 ft[NJ];  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn)
-      ft[jn] = f4{widen(vpre[jn][0]), widen(vpre[jn][1]), widen(vpre[jn][2]), widen(vpre[jn][3])};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? -widen(vpre[jn][r]) : 0.0f;
+    VLA_STAMP(1);
     __syncthreads();  // (1) K^, Q visible
     if (t0 + C < T) prefetch(t0 + C);
 
-    // ================= Y^T = K^ A0 and F^T = V^T - K^ S0^T  (this wave's columns)
+    // ================= Y^T = K^ A0 and -F^T = K^ S0^T - V^T  (this wave's columns)
     f4 yt[NJ];
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn) yt[jn] = f4{0, 0, 0, 0};
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
-      const f4 nka = -ka;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int jn = 0; jn < NJ; ++jn) {
           yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
-          ft[jn] = mfma16(nka[r], St[b][jn][r], ft[jn]);
+          ft[jn] = mfma16(ka[r], St[b][jn][r], ft[jn]);
         }
     }
 
@@ -269,12 +274,15 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         Gp[w][1][(4 * g + r) * LT + c] = gq[r];
       }
     }
+    VLA_STAMP(2);
     __syncthreads();  // (2) partial Grams visible
 
     // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
     const int sw = (blk + head) % NW;  // rotate the serial role over the waves (and SIMDs)
     float m[C];        // lane c: row c of I + G, overwritten by row c of L
     float dl = 1.0f;   // lane c: L_cc
+    int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
+    asm volatile("" : "+v"(cc));
     if (w == sw) {
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -282,7 +290,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) acc += lds4(&Gp[ww][0][c * LT + s4]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == c ? 1.0f : 0.0f);
+        for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == cc ? 1.0f : 0.0f);
       }
       float rinv[C];  // uniform: 1 / L_tt
 #pragma unroll
@@ -293,7 +301,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         rinv[t] = ri;
         const float li = m[t] * ri;  // column t of L (meaningful for rows >= t)
         m[t] = li;
-        dl = (c == t) ? li : dl;
+        dl = (cc == t) ? li : dl;
 #pragma unroll
         for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
       }
@@ -301,7 +309,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       float X[C];
 #pragma unroll
       for (int t = 0; t < C; ++t) {
-        float acc = (c == t) ? 1.0f : 0.0f;
+        float acc = (cc == t) ? 1.0f : 0.0f;
 #pragma unroll
         for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), X[s], acc);
         X[t] = acc * rinv[t];
@@ -311,6 +319,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int t = 0; t < C; ++t) Lis[t * LT + c] = X[t];
       }
     }
+    VLA_STAMP(3);
     __syncthreads();  // (3) L^{-1} visible
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
@@ -334,6 +343,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
+    VLA_STAMP(4);
     __syncthreads();  // (4) W and the norm partials visible
 
     // ================= phase 2 (same wave): c_t, Z, NQ
@@ -344,14 +354,14 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       const float rdl = 1.0f / dl;
       const float an = sqrtf(wn2) * rdl;       // ||A_t k^_t|| = ||w_t|| / L_tt
       const float cs = rdl / fmaxf(an, eps);   // alpha^_t = c_t w_t
-      if (g == 0) cvec[c] = cs;
+      if (g == 0) cvec[c] = -cs;  // the residual tiles carry -E, see below
       // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c
 #pragma unroll
       for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);  // lane t: L[t][s] c_s
       float Zr[C];
 #pragma unroll
       for (int t = 0; t < C; ++t) {
-        float acc = (c == t) ? 1.0f : 0.0f;
+        float acc = (cc == t) ? 1.0f : 0.0f;
 #pragma unroll
         for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), Zr[s], acc);
         Zr[t] = acc;
@@ -373,12 +383,15 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) {
         const int s = 4 * g + r;
         const float csr = __shfl(cs, s);
-        NQs[c * LT + s] = (s <= c) ? csr * hq[r] : 0.0f;
+        NQs[c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
       }
     }
+    VLA_STAMP(5);
     __syncthreads();  // (5) Z, NQ, c visible
+    VLA_STAMP(6);
 
-    // ================= E^T = Z F^T, R^T = Q S0^T, O^T = R^T + NQ^T E^T, store o
+    // ================= -E^T = Z (-F^T), R^T = Q S0^T, O^T = R^T + (-NQ^T)(-E^T), store o;
+    // ce = (-c) (-E^T) = diag(c) E^T
     f4 ce[NJ];
     {
       const f4 za = lds4(&Zs[c * LT + 4 * g]);
@@ -412,13 +425,14 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) {
         const int t = t0 + 4 * g + r;
         if (t < T) {
-          IO* op = oh + static_cast<size_t>(t) * D + vcol;
+          const unsigned ooff = static_cast<unsigned>(t * D + vcol);
 #pragma unroll
-          for (int jn = 0; jn < NJ; ++jn) io_store(op + 16 * jn, ot[jn][r]);
+          for (int jn = 0; jn < NJ; ++jn) io_store(oh + ooff + 16 * jn, ot[jn][r]);
         }
       }
     }
 
+    VLA_STAMP(7);
     // ================= A -= W W^T ,  S^T += W diag(c) E^T
 #pragma unroll
     for (int b = 0; b < NB; ++b) {

@@ -19,6 +19,9 @@ struct ForwardArgs {
   int T;
   float lambda0;
   float eps;
+#ifdef VLA_DEBUG_STAMPS
+  long long* dbg = nullptr;  // development builds only: per-phase cycle stamps
+#endif
 };
 
 // bf16 <-> f32 helpers on raw bit patterns (bf16 is the upper half of an IEEE float32).
