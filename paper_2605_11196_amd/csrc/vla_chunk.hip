@@ -279,44 +279,38 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 
     // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
     const int sw = (blk + head) % NW;  // rotate the serial role over the waves (and SIMDs)
-    float m[C];        // lane c: row c of I + G, overwritten by row c of L
-    float dl = 1.0f;   // lane c: L_cc
+    // Lanes 0-31 hold rows of I + G (-> rows of L), lanes 32-63 hold columns of the identity
+    // (-> columns of L^{-1}); both halves are updated by the same instruction stream: one broadcast of
+    // L[j][t] serves the Cholesky trailing update and the forward substitution for L^{-1}.
+    float m[C];        // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
+    float dl = 1.0f;   // lanes <32, lane c: L_cc
     int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
     asm volatile("" : "+v"(cc));
     if (w == sw) {
+      const bool lower = lane < 32;
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
         f4 acc = lds4(&Gp[0][0][c * LT + s4]);
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) acc += lds4(&Gp[ww][0][c * LT + s4]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == cc ? 1.0f : 0.0f);
+        for (int e = 0; e < 4; ++e)
+          m[s4 + e] = (lower ? acc[e] : 0.0f) + ((s4 + e) == cc ? 1.0f : 0.0f);
       }
-      float rinv[C];  // uniform: 1 / L_tt
 #pragma unroll
       for (int t = 0; t < C; ++t) {
         const float p = readlane(m[t], t);  // pivot = delta_t >= 1
         float ri = __builtin_amdgcn_rsqf(p);
         ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);  // one Newton step on 1/sqrt(p)
-        rinv[t] = ri;
-        const float li = m[t] * ri;  // column t of L (meaningful for rows >= t)
+        const float li = m[t] * ri;  // lanes <32: column t of L;  lanes >=32: row t of L^{-1}, final
         m[t] = li;
         dl = (cc == t) ? li : dl;
 #pragma unroll
         for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
       }
-      // X = L^{-1}: lane c holds column c, X[t] = L^{-1}[t][c]
-      float X[C];
+      if (g == 2) {
 #pragma unroll
-      for (int t = 0; t < C; ++t) {
-        float acc = (cc == t) ? 1.0f : 0.0f;
-#pragma unroll
-        for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), X[s], acc);
-        X[t] = acc * rinv[t];
-      }
-      if (g == 0) {
-#pragma unroll
-        for (int t = 0; t < C; ++t) Lis[t * LT + c] = X[t];
+        for (int t = 0; t < C; ++t) Lis[t * LT + c] = m[t];
       }
     }
     VLA_STAMP(3);
