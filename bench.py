@@ -24,7 +24,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by the
 # same counter's reading for a plain copy kernel of known size); see profiles/. None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # (workload, T, resolved mode): bytes per launch -- profiles/chunk_kernel_large_batch_hbm_traffic.txt
+    ("large_batch", 8192, 2): 17049639 * 1024,
+}
 
 
 def parse_args():
@@ -38,6 +41,9 @@ def parse_args():
     ap.add_argument("--B", type=int, default=None, help="batch override (experiments only)")
     ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB -> 1 GiB elementwise copy kernel (calibration of the "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     ap.add_argument("--cpu-heads", type=int, default=None, help="heads in the oracle timing sample")
     return ap.parse_args()
 
@@ -94,6 +100,14 @@ def main():
                                  workspace_bytes=need, stream=stream.cuda_stream)
         if rc != 0:
             raise RuntimeError(vla.status_string(rc))
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)                                 # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
