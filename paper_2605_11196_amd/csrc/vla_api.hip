@@ -40,7 +40,7 @@ int pick_mode(int /*B*/, int /*H*/, int /*T*/, int d, int /*io_dtype*/, const vl
 
 bool mode_available(int mode, int d) {
   if (mode == VLA_MODE_SCAN) return true;
-  if (mode == VLA_MODE_CHUNKED) return vla::chunk_supported(d);
+  if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE) return vla::chunk_supported(d);
   return false;
 }
 
@@ -79,6 +79,10 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
                                    const vla_opts* opts) {
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
+  const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
+  if (mode == VLA_MODE_TWO_PHASE && mode_available(mode, d_k)) {
+    return vla::two_phase_workspace_bytes(B * H, T, d_k);
+  }
   return 0;
 }
 
@@ -111,6 +115,7 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   a.T = T;
   a.lambda0 = op.lambda0;
   a.eps = op.eps;
+  a.ws = static_cast<float*>(workspace);
 #ifdef VLA_DEBUG_STAMPS
   a.dbg = workspace_bytes >= (1u << 20) ? static_cast<long long*>(workspace) : nullptr;
 #endif
@@ -122,6 +127,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
       break;
     case VLA_MODE_CHUNKED:
       err = vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      break;
+    case VLA_MODE_TWO_PHASE:
+      err = vla::launch_two_phase(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
       break;
     default:
       return VLA_ERR_UNSUPPORTED;

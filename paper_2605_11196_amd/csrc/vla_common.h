@@ -19,6 +19,7 @@ struct ForwardArgs {
   int T;
   float lambda0;
   float eps;
+  float* ws;  // device workspace (two-phase mode), else nullptr
 #ifdef VLA_DEBUG_STAMPS
   long long* dbg = nullptr;  // development builds only: per-phase cycle stamps
 #endif
@@ -42,5 +43,10 @@ hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t st
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 64 and 128.
 bool chunk_supported(int d);
 hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+
+
+// Two-phase split (vla_two_phase.hip): A recurrence first, then the rows of S on many workgroups.
+size_t two_phase_workspace_bytes(int n_heads, int T, int d);
+hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 }  // namespace vla

@@ -1,0 +1,501 @@
+// Two-phase split of the VLA forward recurrence for small B*H (paper Section 3.3 / Algorithm 2's
+// premise): the A recurrence never reads S (eq. (sm) uses only u_t), so it can run first and hand the
+// S recurrence everything it needs; the rows of S then evolve independently of each other
+// (S_t[i,:] = S_{t-1}[i,:] + e_t[i] alpha^_t^T) and are spread over many more workgroups than heads.
+//
+// Same block form (16 tokens) and notation as vla_chunk.hip.  Per (head, block) the workspace holds
+//   K^  [16][D]      normalised keys (token-major)
+//   W   [D][16]      w_t = z_t / sqrt(delta_t), tokens contiguous
+//   SM  [784]        phase 1 writes L | L^{-1} | GQ | ||w_t||^2 ; phase 1b turns them in place into
+//                    Z | L^{-1} | -NQ^T | -c_t  (all 16x16 row-major, vectors of 16)
+//
+//   phase 1  (a_scan_kernel):  one workgroup per head, the A chain of the block form
+//   phase 1b (zc_kernel):      one wave per (head, block), the C x C work the S recurrence needs
+//   phase 2  (s_rows_kernel):  one wave per (head, 16-row slab of S); operands come straight from
+//                              global memory in MFMA operand layout, no LDS and no barriers
+#include "vla_mfma_util.h"
+
+namespace vla {
+namespace {
+
+constexpr int SMB = 3 * C * C + C;  // floats of small matrices per (head, block)
+
+// Four consecutive elements of q in raw form.
+template <typename IO> struct Raw4;
+template <> struct Raw4<float> {
+  float4 v;
+  __device__ __forceinline__ void load(const float* p) { v = *reinterpret_cast<const float4*>(p); }
+  __device__ __forceinline__ void unpack(float (&x)[4]) const { x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w; }
+};
+template <> struct Raw4<uint16_t> {
+  uint2 v;
+  __device__ __forceinline__ void load(const uint16_t* p) { v = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void unpack(float (&x)[4]) const {
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+  }
+};
+
+__host__ __device__ constexpr size_t head_stride(int nblk, int D) {
+  return static_cast<size_t>(nblk) * (2 * C * D + SMB);
+}
+// sub-array offsets inside one head's workspace (floats)
+__device__ __forceinline__ size_t off_kh(int /*nblk*/, int /*D*/) { return 0; }
+__device__ __forceinline__ size_t off_wt(int nblk, int D) { return static_cast<size_t>(nblk) * C * D; }
+__device__ __forceinline__ size_t off_sm(int nblk, int D) { return static_cast<size_t>(nblk) * 2 * C * D; }
+
+// ------------------------------------------------------------------------------------------ phase 1
+template <int D, int NW, typename IO>
+__global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
+  constexpr int SL = D / NW;
+  constexpr int NJ = SL / 16;
+  constexpr int NB = D / 16;
+  constexpr int LD = D + 4;
+  constexpr int NT = 64 * NW;
+  constexpr int EPT = C * D / NT;
+  constexpr int TPR = D / EPT;
+  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
+
+  __shared__ __align__(16) float Ks[C * LD];
+  __shared__ __align__(16) float Qs[C * LD];
+  __shared__ __align__(16) float Ys[C * LD];
+  __shared__ __align__(16) float Wb[D * LT];
+  __shared__ __align__(16) float Gp[NW][2][C * LT];
+  __shared__ __align__(16) float Lis[C * LT];
+  __shared__ __align__(16) float wn2p[NW][C];
+
+  const int head = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int w = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int T = a.T;
+  const float eps = a.eps;
+  const int col0 = SL * w;
+  const int nblk = (T + C - 1) / C;
+
+  float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
+  float* KH = wsh + off_kh(nblk, D);
+  float* WT = wsh + off_wt(nblk, D);
+  float* SMp = wsh + off_sm(nblk, D);
+
+  f4 At[NB][NJ];
+  {
+    const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float diag = 1.0f / a.lambda0;
+    const int arc = (4 * g) * D + col0 + c;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+        if (A0) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) At[b][jn][r] = A0[arc + (16 * b + r) * D + 16 * jn];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            At[b][jn][r] = (16 * b + 4 * g + r == col0 + 16 * jn + c) ? diag : 0.0f;
+        }
+      }
+  }
+
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const int srow = tid / TPR;
+  const int sseg = (tid % TPR) * EPT;
+
+  RawRow<IO, EPT> kpre, qpre;
+  auto prefetch = [&](int t0) {
+    const int tr = t0 + srow;
+    const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+    kpre.load(kh + koff);
+    qpre.load(qh + koff);
+  };
+  if (T > 0) prefetch(0);
+
+  int blk = 0;
+  for (int t0 = 0; t0 < T; t0 += C, ++blk) {
+    // ---- stage K^ (LDS and workspace) and Q (LDS)
+    {
+      float kx[EPT];
+      const bool live = t0 + srow < T;
+      kpre.unpack(kx);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+      float ss = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
+#pragma unroll
+      for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
+      float* kg = KH + static_cast<size_t>(t0 + srow) * D + sseg;
+#pragma unroll
+      for (int e = 0; e < EPT; e += 4) {
+        const f4 kv = f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) = kv;
+        *reinterpret_cast<f4*>(kg + e) = kv;
+      }
+      qpre.unpack(kx);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPT; e += 4)
+        *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
+    }
+    __syncthreads();  // (1)
+    if (t0 + C < T) prefetch(t0 + C);
+
+    // ---- Y^T = K^ A0 and the partial Gram matrices
+    f4 yt[NJ];
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn) yt[jn] = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int jn = 0; jn < NJ; ++jn) yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
+    }
+#pragma unroll
+    for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Ys[(4 * g + r) * LD + col0 + 16 * jn + c] = yt[jn][r];
+    {
+      f4 gg = f4{0, 0, 0, 0}, gq = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+        const int o4 = c * LD + col0 + 16 * jn + 4 * g;
+        const f4 ya = lds4(&Ys[o4]);
+        const f4 kb = lds4(&Ks[o4]);
+        const f4 qb = lds4(&Qs[o4]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          gg = mfma16(ya[r], kb[r], gg);
+          gq = mfma16(ya[r], qb[r], gq);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        Gp[w][0][(4 * g + r) * LT + c] = gg[r];
+        Gp[w][1][(4 * g + r) * LT + c] = gq[r];
+      }
+    }
+    __syncthreads();  // (2)
+
+    // ---- Cholesky of I + G and L^{-1} (lanes <32 rows of L, lanes >=32 columns of L^{-1})
+    float* smb = SMp + static_cast<size_t>(blk) * SMB;
+    const int sw = blk % NW;
+    if (w == sw) {
+      int cc = c;
+      asm volatile("" : "+v"(cc));
+      const bool lower = lane < 32;
+      float m[C];
+#pragma unroll
+      for (int s4 = 0; s4 < C; s4 += 4) {
+        f4 acc = lds4(&Gp[0][0][c * LT + s4]);
+        f4 acq = lds4(&Gp[0][1][c * LT + s4]);
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) {
+          acc += lds4(&Gp[ww][0][c * LT + s4]);
+          acq += lds4(&Gp[ww][1][c * LT + s4]);
+        }
+        if (g == 1) *reinterpret_cast<f4*>(smb + 2 * C * C + c * C + s4) = acq;  // GQ
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          m[s4 + e] = (lower ? acc[e] : 0.0f) + ((s4 + e) == cc ? 1.0f : 0.0f);
+      }
+#pragma unroll
+      for (int t = 0; t < C; ++t) {
+        const float p = readlane(m[t], t);
+        float ri = __builtin_amdgcn_rsqf(p);
+        ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);
+        const float li = m[t] * ri;
+        m[t] = li;
+#pragma unroll
+        for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
+      }
+      if (g == 0) {  // rows of L
+#pragma unroll
+        for (int s4 = 0; s4 < C; s4 += 4)
+          *reinterpret_cast<f4*>(smb + c * C + s4) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
+      }
+      if (g == 2) {  // columns of L^{-1}
+#pragma unroll
+        for (int t = 0; t < C; ++t) {
+          Lis[t * LT + c] = m[t];
+          smb[C * C + t * C + c] = m[t];
+        }
+      }
+    }
+    __syncthreads();  // (3)
+
+    // ---- W^T = L^{-1} Y^T -> LDS and workspace; partial norms
+    const f4 la = lds4(&Lis[c * LT + 4 * g]);
+    f4 nwt[NJ];
+    {
+      f4 n2 = f4{0, 0, 0, 0};
+      float* wg = WT + static_cast<size_t>(blk) * D * C;
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) {
+        f4 acc = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc = mfma16(la[r], yt[jn][r], acc);
+        nwt[jn] = -acc;
+        n2 += acc * acc;
+        *reinterpret_cast<f4*>(&Wb[(col0 + 16 * jn + c) * LT + 4 * g]) = acc;
+        *reinterpret_cast<f4*>(wg + (col0 + 16 * jn + c) * C + 4 * g) = acc;
+      }
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) n2[r] += __shfl_xor(n2[r], off);
+      }
+      if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
+    }
+    __syncthreads();  // (4)
+
+    if (w == sw && g == 0) {
+      float wn2 = 0.0f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
+      smb[3 * C * C + c] = wn2;
+    }
+    // ---- A -= W W^T
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 wa = lds4(&Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int jn = 0; jn < NJ; ++jn) At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
+    }
+  }
+
+  if (a.A_T) {
+    float* AT = a.A_T + static_cast<size_t>(head) * D * D;
+    int g2 = g;
+    asm volatile("" : "+v"(g2));
+    const int arc = (4 * g2) * D + col0 + c;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) AT[arc + (16 * b + r) * D + 16 * jn] = At[b][jn][r];
+  }
+}
+
+// ------------------------------------------------------------------------------------------ phase 1b
+// One wave per (head, block): c_t, Z = (I + strict_lower(L) diag(c))^{-1}, -NQ^T, in place.
+__global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nblk, int D, float eps) {
+  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
+  if (wave >= n_heads * nblk) return;
+  const int head = wave / nblk, blk = wave - head * nblk;
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  float* smb = ws + static_cast<size_t>(head) * head_stride(nblk, D) +
+               static_cast<size_t>(nblk) * 2 * C * D + static_cast<size_t>(blk) * SMB;
+
+  float m[C];  // lane c: row c of L
+#pragma unroll
+  for (int s4 = 0; s4 < C; s4 += 4) {
+    const f4 lr = *reinterpret_cast<const f4*>(smb + c * C + s4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) m[s4 + e] = lr[e];
+  }
+  const f4 la = *reinterpret_cast<const f4*>(smb + C * C + c * C + 4 * g);  // L^{-1}[c][4g..]
+  float gqv[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) gqv[r] = smb[2 * C * C + (4 * g + r) * C + c];
+  const float wn2 = smb[3 * C * C + c];
+  float dl = m[0];
+#pragma unroll
+  for (int s = 1; s < C; ++s) dl = (c == s) ? m[s] : dl;
+  const float rdl = 1.0f / dl;
+  const float an = sqrtf(wn2) * rdl;
+  const float cs = rdl / fmaxf(an, eps);
+
+#pragma unroll
+  for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);
+  float Zr[C];
+#pragma unroll
+  for (int t = 0; t < C; ++t) {
+    float acc = (c == t) ? 1.0f : 0.0f;
+#pragma unroll
+    for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), Zr[s], acc);
+    Zr[t] = acc;
+  }
+  f4 hq = f4{0, 0, 0, 0};
+#pragma unroll
+  for (int r = 0; r < 4; ++r) hq = mfma16(la[r], gqv[r], hq);
+  f4 nq;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int s = 4 * g + r;
+    const float csr = __shfl(cs, s);
+    nq[r] = (s <= c) ? -(csr * hq[r]) : 0.0f;
+  }
+  // every value read above is in registers; now overwrite in place
+  if (g == 0) {
+#pragma unroll
+    for (int t = 0; t < C; ++t) smb[t * C + c] = Zr[t];
+    smb[3 * C * C + c] = -cs;
+  }
+  *reinterpret_cast<f4*>(smb + 2 * C * C + c * C + 4 * g) = nq;  // -NQ^T[t = c][s = 4g + r]
+}
+
+// ------------------------------------------------------------------------------------------ phase 2
+// One wave per (head, 16-row slab of S).  st[b][r] = S[row0 + c][16b + 4g + r].
+template <int D, typename IO>
+__global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
+  constexpr int NB = D / 16;
+  constexpr int NSLAB = D / 16;
+  const int head = blockIdx.x / NSLAB;
+  const int row0 = (blockIdx.x % NSLAB) * 16;
+  const int lane = threadIdx.x;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int T = a.T;
+  const int nblk = (T + C - 1) / C;
+
+  const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
+  const float* KH = wsh;
+  const float* WT = wsh + static_cast<size_t>(nblk) * C * D;
+  const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+
+  f4 st[NB];
+  {
+    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      if (S0) {
+        const float4 x = *reinterpret_cast<const float4*>(S0 + (row0 + c) * D + 16 * b + 4 * g);
+        st[b] = f4{x.x, x.y, x.z, x.w};
+      } else {
+        st[b] = f4{0, 0, 0, 0};
+      }
+    }
+  }
+
+  // operands of one block, in MFMA operand layout, straight from global memory
+  struct Ops {
+    f4 ka[NB], wa[NB];
+    Raw4<IO> qa[NB];
+    f4 za, nqa, ncg;
+    IO v[4];
+  };
+  auto load_ops = [&](int blk, Ops& o) {
+    const int t = blk * C + c;
+    const unsigned qrow = static_cast<unsigned>((t < T ? t : T - 1) * D);
+    const float* kp = KH + static_cast<size_t>(blk * C + c) * D + 4 * g;
+    const float* wp = WT + static_cast<size_t>(blk) * D * C + c * C + 4 * g;
+    const float* sp = SMp + static_cast<size_t>(blk) * SMB;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      o.ka[b] = *reinterpret_cast<const f4*>(kp + 16 * b);
+      o.wa[b] = *reinterpret_cast<const f4*>(wp + 16 * b * C);
+      o.qa[b].load(qh + qrow + 16 * b + 4 * g);
+    }
+    o.za = *reinterpret_cast<const f4*>(sp + c * C + 4 * g);
+    o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + c * C + 4 * g);
+    o.ncg = *reinterpret_cast<const f4*>(sp + 3 * C * C + 4 * g);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tv = blk * C + 4 * g + r;
+      o.v[r] = vh[static_cast<unsigned>((tv < T ? tv : T - 1) * D + row0 + c)];
+    }
+  };
+
+  Ops cur, nxt;
+  if (nblk > 0) load_ops(0, cur);
+  for (int blk = 0; blk < nblk; ++blk) {
+    if (blk + 1 < nblk) load_ops(blk + 1, nxt);
+    const int t0 = blk * C;
+    const bool qlive = t0 + c < T;
+    f4 ft, ot = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ft[r] = (t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      float qx[4];
+      cur.qa[b].unpack(qx);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        ft = mfma16(cur.ka[b][r], st[b][r], ft);
+        ot = mfma16(qlive ? qx[r] : 0.0f, st[b][r], ot);
+      }
+    }
+    f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int t = t0 + 4 * g + r;
+      if (t < T) io_store(oh + static_cast<unsigned>(t * D + row0 + c), ot[r]);
+    }
+    const f4 ce = et * cur.ncg;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st[b] = mfma16(cur.wa[b][r], ce[r], st[b]);
+    cur = nxt;
+  }
+
+  if (a.S_T) {
+    float* ST = a.S_T + static_cast<size_t>(head) * D * D;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+      *reinterpret_cast<float4*>(ST + (row0 + c) * D + 16 * b + 4 * g) =
+          make_float4(st[b][0], st[b][1], st[b][2], st[b][3]);
+  }
+}
+
+template <int D, int NW, typename IO>
+hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
+                                   dim3(a.n_heads), dim3(64 * NW), params, 0, stream);
+  if (err != hipSuccess) return err;
+  const int nblk = (a.T + C - 1) / C;
+  const long long waves = static_cast<long long>(a.n_heads) * nblk;
+  if (waves > 0) {
+    float* ws = a.ws;
+    int nh = a.n_heads, nb = nblk, d = D;
+    float eps = a.eps;
+    void* p2[] = {&ws, &nh, &nb, &d, &eps};
+    err = hipLaunchKernel(reinterpret_cast<const void*>(&zc_kernel),
+                          dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), p2, 0, stream);
+    if (err != hipSuccess) return err;
+  }
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, IO>),
+                         dim3(a.n_heads * (D / 16)), dim3(64), params, 0, stream);
+}
+
+}  // namespace
+
+size_t two_phase_workspace_bytes(int n_heads, int T, int d) {
+  const int nblk = (T + C - 1) / C;
+  return static_cast<size_t>(n_heads) * head_stride(nblk, d) * sizeof(float);
+}
+
+hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
+    case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace vla
