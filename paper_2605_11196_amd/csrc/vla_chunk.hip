@@ -287,17 +287,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       const float an = sqrtf(wn2) * rdl;       // ||A_t k^_t|| = ||w_t|| / L_tt
       const float cs = rdl / fmaxf(an, eps);   // alpha^_t = c_t w_t
       if (g == 0) cvec[c] = -cs;  // the residual tiles carry -E, see below
-      // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c
-#pragma unroll
-      for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);  // lane t: L[t][s] c_s
-      float Zr[C];
-#pragma unroll
-      for (int t = 0; t < C; ++t) {
-        float acc = (cc == t) ? 1.0f : 0.0f;
-#pragma unroll
-        for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), Zr[s], acc);
-        Zr[t] = acc;
-      }
+      // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c (rows of L live in lanes 0-31)
+      float nm[C], Zr[C];
+      float ncs = -cs;
+      asm volatile("s_nop 1" : "+v"(ncs));   // a DPP read of a VGPR needs 2 wait states after its write
+      scale_cols<0>(m, nm, ncs);             // lane t: -L[t][s] c_s
+      asm volatile("s_nop 1" : "+v"(nm[0]));
+      z_rows<0>(nm, Zr, cc);
       if (g == 0) {
 #pragma unroll
         for (int t = 0; t < C; ++t) Zs[t * LT + c] = Zr[t];

@@ -18,6 +18,53 @@ __device__ __forceinline__ float readlane(float x, int lane) {
 }
 __device__ __forceinline__ f4 lds4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 
+// acc += x[lane L of this 16-lane row] * y   -- one VALU instruction (DPP row broadcast folded into the FMA)
+template <int L>
+__device__ __forceinline__ void fmac_row_bcast(float& acc, float x, float y) {
+  asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+               : "+v"(acc)
+               : "v"(x), "v"(y), "n"(L));
+}
+// x[lane L of this 16-lane row] * y
+template <int L>
+__device__ __forceinline__ float mul_row_bcast(float x, float y) {
+  float r;
+  asm volatile("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+               : "=v"(r)
+               : "v"(x), "v"(y), "n"(L));
+  return r;
+}
+
+// Forward substitution for Z = (I + N)^{-1}, N strictly lower triangular, columns on lanes:
+// on entry nm[s] holds, in lane t of every 16-lane row, -N[t][s]; on exit Z[t] = Z[t][c] in lane c.
+// Row t needs N[t][s] in every lane: that is lane t's own register, broadcast by DPP inside the FMA.
+template <int T_, int S_>
+struct ZRow {
+  static __device__ __forceinline__ void run(const float (&nm)[C], const float (&Z)[C], float& acc) {
+    if constexpr (S_ < T_) {
+      fmac_row_bcast<T_>(acc, nm[S_], Z[S_]);
+      ZRow<T_, S_ + 1>::run(nm, Z, acc);
+    }
+  }
+};
+template <int T_>
+__device__ __forceinline__ void z_rows(const float (&nm)[C], float (&Z)[C], int c) {
+  if constexpr (T_ < C) {
+    float acc = (c == T_) ? 1.0f : 0.0f;
+    ZRow<T_, 0>::run(nm, Z, acc);
+    Z[T_] = acc;
+    z_rows<T_ + 1>(nm, Z, c);
+  }
+}
+// nm[s] = m[s] * ncs[lane s of the row]  for s = 0..C-1   (ncs = -c_s, lane-distributed)
+template <int S_>
+__device__ __forceinline__ void scale_cols(const float (&m)[C], float (&nm)[C], float ncs) {
+  if constexpr (S_ < C) {
+    nm[S_] = mul_row_bcast<S_>(ncs, m[S_]);
+    scale_cols<S_ + 1>(m, nm, ncs);
+  }
+}
+
 __device__ __forceinline__ float io_load(const float* p) { return *p; }
 __device__ __forceinline__ float io_load(const uint16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void io_store(float* p, float x) { *p = x; }

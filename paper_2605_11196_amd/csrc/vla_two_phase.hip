@@ -319,16 +319,12 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
   const float an = sqrtf(wn2) * rdl;
   const float cs = rdl / fmaxf(an, eps);
 
-#pragma unroll
-  for (int s = 0; s < C; ++s) m[s] *= readlane(cs, s);
-  float Zr[C];
-#pragma unroll
-  for (int t = 0; t < C; ++t) {
-    float acc = (c == t) ? 1.0f : 0.0f;
-#pragma unroll
-    for (int s = 0; s < t; ++s) acc = fmaf(-readlane(m[s], t), Zr[s], acc);
-    Zr[t] = acc;
-  }
+  float nm[C], Zr[C];
+  float ncs = -cs;
+  asm volatile("s_nop 1" : "+v"(ncs));   // a DPP read of a VGPR needs 2 wait states after its write
+  scale_cols<0>(m, nm, ncs);             // lane t: -L[t][s] c_s
+  asm volatile("s_nop 1" : "+v"(nm[0]));
+  z_rows<0>(nm, Zr, c);
   f4 hq = f4{0, 0, 0, 0};
 #pragma unroll
   for (int r = 0; r < 4; ++r) hq = mfma16(la[r], gqv[r], hq);
