@@ -49,6 +49,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   __shared__ __align__(16) float Wb[D * LT];          // W   [j][t]
   __shared__ __align__(16) float Gp[NW][2][C * LT];   // per-wave partial Gram matrices G, GQ  [s][t]
   __shared__ __align__(16) float Lis[C * LT];         // L^{-1} [t][s]
+  __shared__ __align__(16) float Lrs[C * LT];         // L [t][s] (rows), for the wave that forms Z
   __shared__ __align__(16) float Zs[C * LT];          // Z   [t][s]
   __shared__ __align__(16) float NQs[C * LT];         // -NQ^T [t][s]
   __shared__ __align__(16) float wn2p[NW][C];         // per-wave partial ||w_t||^2
@@ -216,15 +217,15 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     __syncthreads();  // (2) partial Grams visible
 
     // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
-    const int sw = (blk + head) % NW;  // rotate the serial role over the waves (and SIMDs)
+    const int sw = (blk + head) % NW;   // wave factorising I + G this block (rotates over waves/SIMDs)
+    const int sw2 = (sw + NW / 2) % NW;  // a different wave forms c, Z, NQ
     // Lanes 0-31 hold rows of I + G (-> rows of L), lanes 32-63 hold columns of the identity
     // (-> columns of L^{-1}); both halves are updated by the same instruction stream: one broadcast of
     // L[j][t] serves the Cholesky trailing update and the forward substitution for L^{-1}.
-    float m[C];        // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
-    float dl = 1.0f;   // lanes <32, lane c: L_cc
     int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
     asm volatile("" : "+v"(cc));
     if (w == sw) {
+      float m[C];  // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
       const bool lower = lane < 32;
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -242,13 +243,17 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);  // one Newton step on 1/sqrt(p)
         const float li = m[t] * ri;  // lanes <32: column t of L;  lanes >=32: row t of L^{-1}, final
         m[t] = li;
-        dl = (cc == t) ? li : dl;
 #pragma unroll
         for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
       }
       if (g == 2) {
 #pragma unroll
         for (int t = 0; t < C; ++t) Lis[t * LT + c] = m[t];
+      }
+      if (g == 0) {
+#pragma unroll
+        for (int s4 = 0; s4 < C; s4 += 4)
+          *reinterpret_cast<f4*>(&Lrs[c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
     }
     VLA_STAMP(3);
@@ -278,8 +283,29 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     VLA_STAMP(4);
     __syncthreads();  // (4) W and the norm partials visible
 
-    // ================= phase 2 (same wave): c_t, Z, NQ
-    if (w == sw) {
+    // ================= phase 2 (wave sw2): c_t, Z, NQ -- the other waves update A meanwhile
+    auto update_A = [&]() {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 wa = lds4(&Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int jn = 0; jn < NJ; ++jn) At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
+      }
+    };
+    if (w != sw2) update_A();
+    if (w == sw2) {
+      float m[C];  // lane c: row c of L
+#pragma unroll
+      for (int s4 = 0; s4 < C; s4 += 4) {
+        const f4 lr = lds4(&Lrs[c * LT + s4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m[s4 + e] = lr[e];
+      }
+      float dl = m[0];
+#pragma unroll
+      for (int s = 1; s < C; ++s) dl = (cc == s) ? m[s] : dl;  // L_cc
       float wn2 = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
@@ -361,18 +387,16 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     }
 
     VLA_STAMP(7);
-    // ================= A -= W W^T ,  S^T += W diag(c) E^T
+    // ================= S^T += W diag(c) E^T  (and A -= W W^T on the wave that formed Z)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const f4 wa = lds4(&Wb[(16 * b + c) * LT + 4 * g]);
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int jn = 0; jn < NJ; ++jn) {
-          At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
-          St[b][jn] = mfma16(wa[r], ce[jn][r], St[b][jn]);
-        }
+        for (int jn = 0; jn < NJ; ++jn) St[b][jn] = mfma16(wa[r], ce[jn][r], St[b][jn]);
     }
+    if (w == sw2) update_A();
   }
 
   // ---- final state
