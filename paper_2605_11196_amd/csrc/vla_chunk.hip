@@ -224,6 +224,20 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     // L[j][t] serves the Cholesky trailing update and the forward substitution for L^{-1}.
     int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
     asm volatile("" : "+v"(cc));
+    f4 ot[NJ];  // R^T = Q S0^T, later O^T
+    auto r_pass = [&]() {
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn) ot[jn] = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int jn = 0; jn < NJ; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
+      }
+    };
+    if (w != sw) r_pass();  // the other waves use the matrix pipes while wave sw factorises
     if (w == sw) {
       float m[C];  // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
       const bool lower = lane < 32;
@@ -356,17 +370,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[jn][r], et);
         ft[jn] = et;
       }
-      f4 ot[NJ];
-#pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) ot[jn] = f4{0, 0, 0, 0};
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int jn = 0; jn < NJ; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
-      }
+      if (w == sw) r_pass();
       const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
       const f4 cg = lds4(&cvec[4 * g]);
 #pragma unroll
