@@ -43,8 +43,8 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   constexpr int TPR = D / EPT;     // threads per token row
   static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
 
-  __shared__ __align__(16) float Ks[C * LD];          // K^  [t][j]
-  __shared__ __align__(16) float Qs[C * LD];          // Q   [t][j]
+  __shared__ __align__(16) float Ksb[2][C * LD];      // K^  [t][j], double-buffered over blocks
+  __shared__ __align__(16) float Qsb[2][C * LD];      // Q   [t][j]
   __shared__ __align__(16) float Ys[C * LD];          // Y^T [t][j] (each wave touches only its columns)
   __shared__ __align__(16) float Wb[D * LT];          // W   [j][t]
   __shared__ __align__(16) float Gp[NW][2][C * LT];   // per-wave partial Gram matrices G, GQ  [s][t]
@@ -110,14 +110,15 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   RawRow<IO, EPT> kpre, qpre;
   IO vpre[NJ][4];  // V^T in accumulator layout: V[t0 + 4g + r][col0 + 16jn + c]
 
-  // Loads for the block starting at t0.  Rows past the end are read from the last valid row (their
-  // values are replaced by zeros when the registers are consumed, one block later), so the loads need
-  // neither a branch nor a wait.  Offsets are 32-bit from the uniform per-head base pointers.
-  auto prefetch = [&](int t0) {
+  // Loads never branch or wait: rows past the end are read from the last valid row and replaced by
+  // zeros when the registers are consumed (later).  Offsets are 32-bit from the per-head base pointers.
+  auto load_kq = [&](int t0) {
     const int tr = t0 + srow;
     const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
     kpre.load(kh + koff);
     qpre.load(qh + koff);
+  };
+  auto load_v = [&](int t0) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int t = t0 + 4 * g + r;
@@ -126,8 +127,40 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int jn = 0; jn < NJ; ++jn) vpre[jn][r] = vh[voff + 16 * jn];
     }
   };
+  // normalise this thread's share of the keys of the block starting at t0 and put K^, Q into LDS half `buf`
+  auto stage = [&](int t0, int buf) {
+    float kx[EPT];
+    const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
+    kpre.unpack(kx);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+    float ss = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
+#pragma unroll
+    for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
+#pragma unroll
+    for (int e = 0; e < EPT; e += 4) {
+      *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg + e]) =
+          f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+    }
+    qpre.unpack(kx);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPT; e += 4) {
+      *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
+    }
+  };
 
-  if (T > 0) prefetch(0);
+  if (T > 0) {
+    load_kq(0);
+    load_v(0);
+    stage(0, 0);
+    if (C < T) load_kq(C);
+  }
+  __syncthreads();  // block 0 staged
 
   int blk = 0;
 #ifdef VLA_DEBUG_STAMPS
@@ -137,42 +170,24 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #endif
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
     VLA_STAMP(0);
-    // ================= stage K^ (normalised) and Q into LDS
-    {
-      float kx[EPT];
-      const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
-      kpre.unpack(kx);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
-      float ss = 0.0f;
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
-#pragma unroll
-      for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
-#pragma unroll
-      for (int e = 0; e < EPT; e += 4) {
-        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) =
-            f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+    const float* Ks = Ksb[blk & 1];
+    const float* Qs = Qsb[blk & 1];
+    // staging of the next block (this thread's share): done where this wave is not on the critical path
+    auto stage_next = [&]() {
+      if (t0 + C < T) {
+        stage(t0 + C, (blk + 1) & 1);
+        if (t0 + 2 * C < T) load_kq(t0 + 2 * C);
       }
-      qpre.unpack(kx);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
-#pragma unroll
-      for (int e = 0; e < EPT; e += 4) {
-        *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
-      }
-    }
+    };
     f4 ft[NJ];  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn)
 #pragma unroll
       for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? -widen(vpre[jn][r]) : 0.0f;
+    if (t0 + C < T) load_v(t0 + C);
     VLA_STAMP(1);
-    __syncthreads();  // (1) K^, Q visible
-    if (t0 + C < T) prefetch(t0 + C);
 
-    // ================= Y^T = K^ A0 and -F^T = K^ S0^T - V^T  (this wave's columns)
+    // ================= Y^T = K^ A0 (this wave's columns); Y^T goes to LDS for the Gram products
     f4 yt[NJ];
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn) yt[jn] = f4{0, 0, 0, 0};
@@ -182,35 +197,44 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int jn = 0; jn < NJ; ++jn) {
-          yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
-          ft[jn] = mfma16(ka[r], St[b][jn][r], ft[jn]);
-        }
+        for (int jn = 0; jn < NJ; ++jn) yt[jn] = mfma16(ka[r], At[b][jn][r], yt[jn]);
     }
-
-    // ================= partial Gram matrices over this wave's columns
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn)
 #pragma unroll
       for (int r = 0; r < 4; ++r) Ys[(4 * g + r) * LD + col0 + 16 * jn + c] = yt[jn][r];
+    // ================= -F^T = K^ S0^T - V^T  (covers the LDS round trip of Y^T)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int jn = 0; jn < NJ; ++jn) ft[jn] = mfma16(ka[r], St[b][jn][r], ft[jn]);
+    }
+    // ================= partial Gram matrices over this wave's columns (independent accumulators)
     {
-      f4 gg = f4{0, 0, 0, 0}, gq = f4{0, 0, 0, 0};
+      f4 gg[NJ], gq[NJ];
 #pragma unroll
       for (int jn = 0; jn < NJ; ++jn) {
         const int o4 = c * LD + col0 + 16 * jn + 4 * g;
         const f4 ya = lds4(&Ys[o4]);  // same-wave write -> read: LDS operations of one wave are ordered
         const f4 kb = lds4(&Ks[o4]);
         const f4 qb = lds4(&Qs[o4]);
+        gg[jn] = f4{0, 0, 0, 0};
+        gq[jn] = f4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          gg = mfma16(ya[r], kb[r], gg);
-          gq = mfma16(ya[r], qb[r], gq);
+          gg[jn] = mfma16(ya[r], kb[r], gg[jn]);
+          gq[jn] = mfma16(ya[r], qb[r], gq[jn]);
         }
       }
 #pragma unroll
+      for (int jn = 1; jn < NJ; ++jn) { gg[0] += gg[jn]; gq[0] += gq[jn]; }
+#pragma unroll
       for (int r = 0; r < 4; ++r) {
-        Gp[w][0][(4 * g + r) * LT + c] = gg[r];
-        Gp[w][1][(4 * g + r) * LT + c] = gq[r];
+        Gp[w][0][(4 * g + r) * LT + c] = gg[0][r];
+        Gp[w][1][(4 * g + r) * LT + c] = gq[0][r];
       }
     }
     VLA_STAMP(2);
@@ -237,7 +261,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           for (int jn = 0; jn < NJ; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
       }
     };
-    if (w != sw) r_pass();  // the other waves use the matrix pipes while wave sw factorises
+    if (w != sw) {  // the other waves use the matrix pipes while wave sw factorises
+      r_pass();
+      stage_next();
+    }
     if (w == sw) {
       float m[C];  // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
       const bool lower = lane < 32;
@@ -288,10 +315,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         *reinterpret_cast<f4*>(&Wb[(col0 + 16 * jn + c) * LT + 4 * g]) = acc;
       }
 #pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) n2[r] += __shfl_xor(n2[r], off);
-      }
+      for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
     VLA_STAMP(4);
@@ -309,6 +333,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
     };
     if (w != sw2) update_A();
+    if (w == sw) stage_next();  // (sw != sw2 when NW > 1)
     if (w == sw2) {
       float m[C];  // lane c: row c of L
 #pragma unroll
