@@ -16,7 +16,10 @@ _lib = None
 
 class _Opts(ctypes.Structure):
     _fields_ = [("lambda0", ctypes.c_double), ("eps", ctypes.c_double),
-                ("u", ctypes.c_void_p), ("u_scale", ctypes.c_double)]
+                ("u", ctypes.c_void_p), ("u_scale", ctypes.c_double),
+                ("refresh_period", ctypes.c_int), ("refresh_eta", ctypes.c_double),
+                ("normalise_output", ctypes.c_int), ("feature_map", ctypes.c_int),
+                ("zkey0", ctypes.c_void_p), ("zkey_T", ctypes.c_void_p)]
 
 
 def load():
@@ -52,10 +55,11 @@ def num_threads() -> int:
 
 
 def forward(q, k, v, S0=None, A0=None, *, lambda0=0.1, eps=1e-4, u=None, u_scale=1.0,
-            trace=False):
+            refresh_period=0, refresh_eta=1e-3, normalise_output=False, feature_map=False,
+            zkey0=None, trace=False):
     """q,k [B,H,T,d_k], v [B,H,T,d_v] -> dict(o, S_T, A_T[, trace]) in float64."""
     lib = load()
-    q, k, v, S0, A0, u = map(_f64, (q, k, v, S0, A0, u))
+    q, k, v, S0, A0, u, zkey0 = map(_f64, (q, k, v, S0, A0, u, zkey0))
     B, H, T, dk = q.shape
     dv = v.shape[-1]
     assert k.shape == (B, H, T, dk) and v.shape == (B, H, T, dv)
@@ -69,13 +73,18 @@ def forward(q, k, v, S0=None, A0=None, *, lambda0=0.1, eps=1e-4, u=None, u_scale
     S_T = np.empty((B, H, dv, dk), dtype=np.float64)
     A_T = np.empty((B, H, dk, dk), dtype=np.float64)
     tr = np.empty((B, H, T, TRACE_WIDTH), dtype=np.float64) if trace else None
-    opts = _Opts(float(lambda0), float(eps), _ptr(u), float(u_scale))
+    if zkey0 is not None:
+        assert zkey0.shape == (B, H, dk)
+    zkey_T = np.empty((B, H, dk), dtype=np.float64)
+    opts = _Opts(float(lambda0), float(eps), _ptr(u), float(u_scale), int(refresh_period),
+                 float(refresh_eta), int(bool(normalise_output)), int(bool(feature_map)),
+                 _ptr(zkey0), _ptr(zkey_T))
     rc = lib.vla_oracle_forward_f64(_ptr(q), _ptr(k), _ptr(v), _ptr(S0), _ptr(A0), _ptr(o),
                                     _ptr(S_T), _ptr(A_T), _ptr(tr), B, H, T, dk, dv,
                                     ctypes.byref(opts))
     if rc != 0:
         raise ValueError(f"vla_oracle_forward_f64 returned {rc}")
-    out = {"o": o, "S_T": S_T, "A_T": A_T}
+    out = {"o": o, "S_T": S_T, "A_T": A_T, "zkey_T": zkey_T}
     if trace:
         out["trace"] = tr
     return out

@@ -33,8 +33,12 @@
  *   - the clamp is x / max(||x||, eps), not x / (||x|| + eps); the paper only
  *     says eps = 1e-4 is used "for all denominators" (Section 5.4) and writes
  *     the max() form out for delta (Algorithm 1) and the output denominator.
- *   - the identity refresh of Algorithm 1 is off (it would break
- *     A_t = M_t^{-1}); the output denominator of eq. (output) is not applied.
+ *   - by default the identity refresh of Algorithm 1 is off (it would break
+ *     A_t = M_t^{-1}), the denominator of eq. (output) is not applied and no
+ *     feature map is applied; each of these lines of Algorithm 1 can be
+ *     switched on through vla_oracle_opts (refresh after the rank-1 update and
+ *     before alpha; phi(x) = ELU(x)+1 on q and k before everything else; the
+ *     accumulator of eq. (output) sums the keys as used, before L2 normalisation).
  *   - S is d_v x d_k and o = S q as in eq. (s-update)/(output).
  *
  * Layouts: q,k,u [B,H,T,d_k]; v,o [B,H,T,d_v]; S [B,H,d_v,d_k] row-major;
@@ -63,6 +67,15 @@ typedef struct {
   double eps;       /* stability floor (paper: 1e-4) */
   const double* u;  /* optional raw penalty directions [B,H,T,d_k]; NULL => u_t = k^_t */
   double u_scale;   /* multiplies a supplied, unit-normalised u (1.0 = eq. (penalty)) */
+  /* The remaining switches reproduce the other lines of Algorithm 1; all default to off. */
+  int refresh_period;      /* > 0: A += refresh_eta * I after the rank-1 update of every step t (1-based)
+                              with t mod period == 0 */
+  double refresh_eta;
+  int normalise_output;    /* 1: o_t = S_t q_t / max(q_t . zkey_t, eps), zkey_t = zkey_0 + sum_{s<=t} k_s
+                              (eq. (output); k_s is the key as used, i.e. after the feature map) */
+  int feature_map;         /* 1: q and k are replaced by ELU(x) + 1 elementwise before anything else */
+  const double* zkey0;     /* [B,H,d_k] initial key accumulator, NULL => 0 */
+  double* zkey_T;          /* [B,H,d_k] final key accumulator, NULL => not wanted */
 } vla_oracle_opts;
 
 /* Per-step diagnostics written to trace[((b*H+h)*T + t)*8 + i]:
@@ -90,7 +103,8 @@ static void matvec(const double* M, const double* x, double* y, int rows, int co
 static void one_head(const double* q, const double* k, const double* v, const double* u_raw,
                      const double* S0, const double* A0, double* o, double* S_T, double* A_T,
                      double* trace, int T, int dk, int dv, double lambda0, double eps,
-                     double u_scale) {
+                     double u_scale, int refresh_period, double refresh_eta, int normalise_output,
+                     int feature_map, const double* zkey0, double* zkey_T) {
   double* S = (double*)malloc(sizeof(double) * (size_t)dv * dk);
   double* A = (double*)malloc(sizeof(double) * (size_t)dk * dk);
   double* kh = (double*)malloc(sizeof(double) * dk);
@@ -98,6 +112,10 @@ static void one_head(const double* q, const double* k, const double* v, const do
   double* z = (double*)malloc(sizeof(double) * dk);
   double* a = (double*)malloc(sizeof(double) * dk);
   double* e = (double*)malloc(sizeof(double) * dv);
+  double* kf = (double*)malloc(sizeof(double) * dk);   /* key after the feature map */
+  double* qf = (double*)malloc(sizeof(double) * dk);   /* query after the feature map */
+  double* zkey = (double*)calloc(dk, sizeof(double));  /* running key accumulator (eq. (output)) */
+  if (zkey0) memcpy(zkey, zkey0, sizeof(double) * dk);
 
   if (S0) memcpy(S, S0, sizeof(double) * (size_t)dv * dk);
   else memset(S, 0, sizeof(double) * (size_t)dv * dk);           /* S_0 = 0 (Algorithm 1) */
@@ -108,9 +126,16 @@ static void one_head(const double* q, const double* k, const double* v, const do
   }
 
   for (int t = 0; t < T; ++t) {
-    const double* kt = k + (size_t)t * dk;
-    const double* qt = q + (size_t)t * dk;
+    const double* kt = kf;
+    const double* qt = qf;
     const double* vt = v + (size_t)t * dv;
+
+    /* feature map phi(x) = ELU(x) + 1 (Section 3.3): x + 1 for x > 0, exp(x) otherwise */
+    for (int j = 0; j < dk; ++j) {
+      double kr = k[(size_t)t * dk + j], qr = q[(size_t)t * dk + j];
+      kf[j] = feature_map ? (kr > 0.0 ? kr + 1.0 : exp(kr)) : kr;
+      qf[j] = feature_map ? (qr > 0.0 ? qr + 1.0 : exp(qr)) : qr;
+    }
 
     /* key normalisation */
     double kn = sqrt(dot(kt, kt, dk));
@@ -134,6 +159,10 @@ static void one_head(const double* q, const double* k, const double* v, const do
     for (int i = 0; i < dk; ++i)
       for (int j = 0; j < dk; ++j) A[(size_t)i * dk + j] -= z[i] * z[j] / delta;
 
+    /* periodic identity refresh (Algorithm 1), steps counted from 1 */
+    if (refresh_period > 0 && (t + 1) % refresh_period == 0)
+      for (int i = 0; i < dk; ++i) A[(size_t)i * dk + i] += refresh_eta;
+
     /* write direction from the post-update A */
     matvec(A, kh, a, dk, dk);
     double an = sqrt(dot(a, a, dk));
@@ -147,6 +176,12 @@ static void one_head(const double* q, const double* k, const double* v, const do
 
     /* read-out from the post-update S */
     matvec(S, qt, o + (size_t)t * dv, dv, dk);
+    for (int j = 0; j < dk; ++j) zkey[j] += kt[j];
+    if (normalise_output) {
+      double den = dot(zkey, qt, dk);
+      den = den > eps ? den : eps;
+      for (int i = 0; i < dv; ++i) o[(size_t)t * dv + i] /= den;
+    }
 
     if (trace) {
       double* tr = trace + (size_t)t * VLA_ORACLE_TRACE_WIDTH;
@@ -163,7 +198,8 @@ static void one_head(const double* q, const double* k, const double* v, const do
 
   if (S_T) memcpy(S_T, S, sizeof(double) * (size_t)dv * dk);
   if (A_T) memcpy(A_T, A, sizeof(double) * (size_t)dk * dk);
-  free(S); free(A); free(kh); free(u); free(z); free(a); free(e);
+  if (zkey_T) memcpy(zkey_T, zkey, sizeof(double) * dk);
+  free(S); free(A); free(kh); free(u); free(z); free(a); free(e); free(kf); free(qf); free(zkey);
 }
 
 /* Returns 0 on success, 1 on an invalid argument. S0/A0/S_T/A_T/trace/opts may be NULL. */
@@ -178,6 +214,12 @@ int vla_oracle_forward_f64(const double* q, const double* k, const double* v,
   double eps = opts ? opts->eps : 1e-4;
   const double* u = opts ? opts->u : NULL;
   double u_scale = opts ? opts->u_scale : 1.0;
+  int refresh_period = opts ? opts->refresh_period : 0;
+  double refresh_eta = opts ? opts->refresh_eta : 1e-3;
+  int normalise_output = opts ? opts->normalise_output : 0;
+  int feature_map = opts ? opts->feature_map : 0;
+  const double* zkey0 = opts ? opts->zkey0 : NULL;
+  double* zkey_T = opts ? opts->zkey_T : NULL;
   if (!(lambda0 > 0.0) || !(eps > 0.0)) return 1;
 
   long nh = (long)B * H;
@@ -189,7 +231,8 @@ int vla_oracle_forward_f64(const double* q, const double* k, const double* v,
              S0 ? S0 + n * sS : NULL, A0 ? A0 + n * sA : NULL,
              o + n * sv, S_T ? S_T + n * sS : NULL, A_T ? A_T + n * sA : NULL,
              trace ? trace + (size_t)n * T * VLA_ORACLE_TRACE_WIDTH : NULL,
-             T, d_k, d_v, lambda0, eps, u_scale);
+             T, d_k, d_v, lambda0, eps, u_scale, refresh_period, refresh_eta, normalise_output,
+             feature_map, zkey0 ? zkey0 + n * d_k : NULL, zkey_T ? zkey_T + n * d_k : NULL);
   }
   return 0;
 }

@@ -412,3 +412,98 @@ def test_synthetic_recall_retrieves_stored_values():
     # filler tokens (all-zero) read nothing and write nothing
     filler = (np.abs(q).sum(-1) == 0) & (np.abs(k).sum(-1) == 0)
     assert np.count_nonzero(r["o"][filler]) == 0
+
+
+# ---------------------------------------------------------------- the other lines of Algorithm 1 (switches)
+def test_identity_refresh_against_explicit_inverses():
+    """Algorithm 1's periodic refresh: A <- A + eta I after the rank-1 update of every `period`-th step.
+    A_t is recomputed here from scratch with matrix inverses (no rank-1 recursion)."""
+    d, T, lam, period, eta = 5, 23, 0.2, 4, 1e-2
+    rng = RNG(40)
+    q = rng.standard_normal((T, d)); k = rng.standard_normal((T, d)); v = rng.standard_normal((T, d))
+    r = oracle.forward(q[None, None], k[None, None], v[None, None], lambda0=lam,
+                       refresh_period=period, refresh_eta=eta)
+    A = np.eye(d) / lam; S = np.zeros((d, d))
+    for t in range(T):
+        kh = k[t] / np.linalg.norm(k[t])
+        A = np.linalg.inv(np.linalg.inv(A) + np.outer(kh, kh))
+        if (t + 1) % period == 0:
+            A = A + eta * np.eye(d)
+        a = A @ kh; a /= np.linalg.norm(a)
+        S = S + np.outer(v[t] - S @ kh, a)
+        assert np.abs(r["o"][0, 0, t] - S @ q[t]).max() < 1e-11
+    assert np.abs(r["A_T"][0, 0] - A).max() < 1e-11
+    # and it really differs from the run without refresh
+    r0 = oracle.forward(q[None, None], k[None, None], v[None, None], lambda0=lam)
+    assert np.abs(r0["A_T"] - r["A_T"]).max() > 1e-3
+
+
+def test_output_normaliser_and_key_accumulator():
+    """eq. (output): o_t = S_t q_t / max(q_t . zkey_t, eps), zkey_t = sum_{s<=t} k_s; the denominator
+    here comes from numpy's cumsum, the numerator from the un-normalised run."""
+    d, T = 6, 40
+    rng = RNG(41)
+    q = np.abs(rng.standard_normal((1, 2, T, d))) + 0.1
+    k = np.abs(rng.standard_normal((1, 2, T, d))) + 0.1
+    v = rng.standard_normal((1, 2, T, d))
+    z0 = np.abs(rng.standard_normal((1, 2, d)))
+    plain = oracle.forward(q, k, v)
+    norm = oracle.forward(q, k, v, normalise_output=True, zkey0=z0)
+    zk = z0[:, :, None, :] + np.cumsum(k, axis=2)
+    den = np.maximum(np.einsum("bhtd,bhtd->bht", zk, q), 1e-4)
+    assert np.abs(norm["o"] - plain["o"] / den[..., None]).max() < 1e-12
+    assert np.abs(norm["zkey_T"] - zk[:, :, -1]).max() < 1e-12
+    assert np.array_equal(norm["S_T"], plain["S_T"]) and np.array_equal(norm["A_T"], plain["A_T"])
+    # the floor: a query orthogonal to every key gives den = eps
+    q2 = q.copy(); q2[0, 0, 5] = 0.0
+    n2 = oracle.forward(q2, k, v, normalise_output=True)
+    assert np.count_nonzero(n2["o"][0, 0, 5]) == 0
+    # carry of the accumulator across calls
+    a = oracle.forward(q[:, :, :15], k[:, :, :15], v[:, :, :15], normalise_output=True, zkey0=z0)
+    b = oracle.forward(q[:, :, 15:], k[:, :, 15:], v[:, :, 15:], a["S_T"], a["A_T"],
+                       normalise_output=True, zkey0=a["zkey_T"])
+    assert np.array_equal(np.concatenate([a["o"], b["o"]], axis=2), norm["o"])
+
+
+def test_elu_plus_one_feature_map():
+    """phi(x) = ELU(x) + 1 (Section 3.3): printed values phi(0) = 1, phi(1) = 2, phi(-1) = 1/e, positivity,
+    and equivalence with transforming q and k beforehand."""
+    d, T = 4, 12
+    rng = RNG(42)
+    q = rng.standard_normal((1, 1, T, d)); k = rng.standard_normal((1, 1, T, d)); v = rng.standard_normal((1, 1, T, d))
+    phi = lambda x: np.where(x > 0, x + 1.0, np.exp(np.minimum(x, 0.0)))
+    assert phi(np.array([0.0, 1.0, -1.0])).tolist() == [1.0, 2.0, float(np.exp(-1.0))]
+    r = oracle.forward(q, k, v, feature_map=True, normalise_output=True)
+    ref = oracle.forward(phi(q), phi(k), v, normalise_output=True)
+    for name in ("o", "S_T", "A_T", "zkey_T"):
+        assert np.abs(r[name] - ref[name]).max() < 1e-14
+    # probe phi itself through the accumulator: one token, k = (0, 1, -1, 5)
+    kk = np.array([0.0, 1.0, -1.0, 5.0]).reshape(1, 1, 1, 4)
+    z = oracle.forward(np.ones((1, 1, 1, 4)), kk, np.zeros((1, 1, 1, 4)), feature_map=True)["zkey_T"][0, 0]
+    assert np.abs(z - np.array([1.0, 2.0, np.exp(-1.0), 6.0])).max() < 1e-15
+
+
+def test_full_algorithm1_tiny_with_every_switch():
+    """All lines of Algorithm 1 together (feature map, supplied u scaled by 1/sqrt(d_h), refresh every 3
+    steps, normalised read-out), re-derived with fresh inverses at d_k != d_v."""
+    d_k, d_v, T, lam, eta, period = 4, 3, 10, 0.1, 1e-3, 3
+    rng = RNG(43)
+    q = rng.standard_normal((T, d_k)); k = rng.standard_normal((T, d_k)); v = rng.standard_normal((T, d_v))
+    u = rng.standard_normal((T, d_k))
+    r = oracle.forward(q[None, None], k[None, None], v[None, None], lambda0=lam, u=u[None, None],
+                       u_scale=d_k ** -0.5, refresh_period=period, refresh_eta=eta,
+                       normalise_output=True, feature_map=True)
+    phi = lambda x: np.where(x > 0, x + 1.0, np.exp(np.minimum(x, 0.0)))
+    A = np.eye(d_k) / lam; S = np.zeros((d_v, d_k)); z = np.zeros(d_k)
+    for t in range(T):
+        kf, qf = phi(k[t]), phi(q[t])
+        kh = kf / np.linalg.norm(kf)
+        uu = u[t] / np.linalg.norm(u[t]) / np.sqrt(d_k)
+        A = np.linalg.inv(np.linalg.inv(A) + np.outer(uu, uu))
+        if (t + 1) % period == 0:
+            A = A + eta * np.eye(d_k)
+        a = A @ kh; a /= np.linalg.norm(a)
+        S = S + np.outer(v[t] - S @ kh, a)
+        z = z + kf
+        assert np.abs(r["o"][0, 0, t] - S @ qf / max(z @ qf, 1e-4)).max() < 1e-11
+    assert np.abs(r["A_T"][0, 0] - A).max() < 1e-10 and np.abs(r["S_T"][0, 0] - S).max() < 1e-11
