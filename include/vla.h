@@ -15,8 +15,9 @@
  *     S_t      = S_{t-1} + e_t alpha^_t^T                      (eq. (s-update))
  *     o_t      = S_t q_t                                       (post-update S)
  *
- * and finally S_T, A_T are written out.  The identity refresh of Algorithm 1 and
- * the denominator of eq. (output) are not applied.
+ * and finally S_T, A_T are written out.  The other lines of Algorithm 1 (a separate
+ * penalty direction u, the periodic identity refresh, the denominator of eq. (output)
+ * and the ELU+1 feature map) are off by default and switched on through vla_opts.
  *
  * Every pointer is a DEVICE pointer unless stated otherwise.  The library never
  * allocates, frees or retains memory: the caller owns every buffer for the
@@ -66,11 +67,34 @@ typedef enum {
   VLA_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
 } vla_status;
 
-/* Options; pass NULL for the defaults in brackets. */
+/* Options; pass NULL for the defaults in brackets.  Always initialise the struct with
+ * vla_default_opts() and then change fields: later library versions may append fields.
+ *
+ * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
+ * With any of them set only the SCAN kernel family applies (AUTO selects it; asking for CHUNKED or
+ * TWO_PHASE returns VLA_ERR_UNSUPPORTED). */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
-  float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^|| (Section 5.4) */
+  float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the
+                    read-out denominator (Section 5.4) */
   int mode;      /* [VLA_MODE_AUTO] a vla_mode */
+  const void* u; /* [NULL] device, [B, H, T, d_k], io_dtype: raw penalty directions u~_t of
+                    eq. (penalty); the recurrence uses u_t = u_scale * u~_t / max(||u~_t||, eps).
+                    NULL: u_t = k^_t (Section 7.1) */
+  float u_scale; /* [1.0]  1/sqrt(d_h) reproduces the scaling in Algorithm 1 */
+  int refresh_period;   /* [0 = off] > 0: A += refresh_eta * I after the rank-1 update (and before the
+                           write direction is formed) at every step whose 1-based index
+                           step_offset + t is a multiple of refresh_period (Algorithm 1 uses 20) */
+  float refresh_eta;    /* [1e-3] */
+  int step_offset;      /* [0] tokens already processed by earlier calls of a split sequence; only
+                           the refresh schedule depends on it */
+  int normalise_output; /* [0] 1: o_t = S_t q_t / max(q_t . zkey_t, eps) with the running key sum
+                           zkey_t = zkey_0 + sum_{s<=t} k_s of eq. (output); k_s is the key as used
+                           (after feature_map, before L2 normalisation) */
+  int feature_map;      /* [0] 1: q and k are replaced by ELU(x) + 1 elementwise on load (Section 3.3) */
+  const float* zkey0;   /* [NULL = 0] device, [B, H, d_k] float32: key sum carried in from earlier calls */
+  float* zkey_T;        /* [NULL = not wanted] device, [B, H, d_k] float32: key sum after the last token;
+                           may alias zkey0 */
 } vla_opts;
 
 /* Fills *opts with the defaults above. */

@@ -18,7 +18,7 @@ class _Opts(ctypes.Structure):
     _fields_ = [("lambda0", ctypes.c_double), ("eps", ctypes.c_double),
                 ("u", ctypes.c_void_p), ("u_scale", ctypes.c_double),
                 ("refresh_period", ctypes.c_int), ("refresh_eta", ctypes.c_double),
-                ("normalise_output", ctypes.c_int), ("feature_map", ctypes.c_int),
+                ("step_offset", ctypes.c_int), ("normalise_output", ctypes.c_int), ("feature_map", ctypes.c_int),
                 ("zkey0", ctypes.c_void_p), ("zkey_T", ctypes.c_void_p)]
 
 
@@ -55,7 +55,7 @@ def num_threads() -> int:
 
 
 def forward(q, k, v, S0=None, A0=None, *, lambda0=0.1, eps=1e-4, u=None, u_scale=1.0,
-            refresh_period=0, refresh_eta=1e-3, normalise_output=False, feature_map=False,
+            refresh_period=0, refresh_eta=1e-3, step_offset=0, normalise_output=False, feature_map=False,
             zkey0=None, trace=False):
     """q,k [B,H,T,d_k], v [B,H,T,d_v] -> dict(o, S_T, A_T[, trace]) in float64."""
     lib = load()
@@ -77,7 +77,7 @@ def forward(q, k, v, S0=None, A0=None, *, lambda0=0.1, eps=1e-4, u=None, u_scale
         assert zkey0.shape == (B, H, dk)
     zkey_T = np.empty((B, H, dk), dtype=np.float64)
     opts = _Opts(float(lambda0), float(eps), _ptr(u), float(u_scale), int(refresh_period),
-                 float(refresh_eta), int(bool(normalise_output)), int(bool(feature_map)),
+                 float(refresh_eta), int(step_offset), int(bool(normalise_output)), int(bool(feature_map)),
                  _ptr(zkey0), _ptr(zkey_T))
     rc = lib.vla_oracle_forward_f64(_ptr(q), _ptr(k), _ptr(v), _ptr(S0), _ptr(A0), _ptr(o),
                                     _ptr(S_T), _ptr(A_T), _ptr(tr), B, H, T, dk, dv,

@@ -71,6 +71,7 @@ typedef struct {
   int refresh_period;      /* > 0: A += refresh_eta * I after the rank-1 update of every step t (1-based)
                               with t mod period == 0 */
   double refresh_eta;
+  int step_offset;         /* tokens processed by earlier calls (only shifts the refresh schedule) */
   int normalise_output;    /* 1: o_t = S_t q_t / max(q_t . zkey_t, eps), zkey_t = zkey_0 + sum_{s<=t} k_s
                               (eq. (output); k_s is the key as used, i.e. after the feature map) */
   int feature_map;         /* 1: q and k are replaced by ELU(x) + 1 elementwise before anything else */
@@ -103,7 +104,7 @@ static void matvec(const double* M, const double* x, double* y, int rows, int co
 static void one_head(const double* q, const double* k, const double* v, const double* u_raw,
                      const double* S0, const double* A0, double* o, double* S_T, double* A_T,
                      double* trace, int T, int dk, int dv, double lambda0, double eps,
-                     double u_scale, int refresh_period, double refresh_eta, int normalise_output,
+                     double u_scale, int refresh_period, double refresh_eta, int step_offset, int normalise_output,
                      int feature_map, const double* zkey0, double* zkey_T) {
   double* S = (double*)malloc(sizeof(double) * (size_t)dv * dk);
   double* A = (double*)malloc(sizeof(double) * (size_t)dk * dk);
@@ -160,7 +161,7 @@ static void one_head(const double* q, const double* k, const double* v, const do
       for (int j = 0; j < dk; ++j) A[(size_t)i * dk + j] -= z[i] * z[j] / delta;
 
     /* periodic identity refresh (Algorithm 1), steps counted from 1 */
-    if (refresh_period > 0 && (t + 1) % refresh_period == 0)
+    if (refresh_period > 0 && (step_offset + t + 1) % refresh_period == 0)
       for (int i = 0; i < dk; ++i) A[(size_t)i * dk + i] += refresh_eta;
 
     /* write direction from the post-update A */
@@ -216,6 +217,7 @@ int vla_oracle_forward_f64(const double* q, const double* k, const double* v,
   double u_scale = opts ? opts->u_scale : 1.0;
   int refresh_period = opts ? opts->refresh_period : 0;
   double refresh_eta = opts ? opts->refresh_eta : 1e-3;
+  int step_offset = opts ? opts->step_offset : 0;
   int normalise_output = opts ? opts->normalise_output : 0;
   int feature_map = opts ? opts->feature_map : 0;
   const double* zkey0 = opts ? opts->zkey0 : NULL;
@@ -231,7 +233,7 @@ int vla_oracle_forward_f64(const double* q, const double* k, const double* v,
              S0 ? S0 + n * sS : NULL, A0 ? A0 + n * sA : NULL,
              o + n * sv, S_T ? S_T + n * sS : NULL, A_T ? A_T + n * sA : NULL,
              trace ? trace + (size_t)n * T * VLA_ORACLE_TRACE_WIDTH : NULL,
-             T, d_k, d_v, lambda0, eps, u_scale, refresh_period, refresh_eta, normalise_output,
+             T, d_k, d_v, lambda0, eps, u_scale, refresh_period, refresh_eta, step_offset, normalise_output,
              feature_map, zkey0 ? zkey0 + n * d_k : NULL, zkey_T ? zkey_T + n * d_k : NULL);
   }
   return 0;

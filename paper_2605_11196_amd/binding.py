@@ -24,7 +24,11 @@ class VlaError(RuntimeError):
 
 
 class VlaOpts(ctypes.Structure):
-    _fields_ = [("lambda0", ctypes.c_float), ("eps", ctypes.c_float), ("mode", ctypes.c_int)]
+    _fields_ = [("lambda0", ctypes.c_float), ("eps", ctypes.c_float), ("mode", ctypes.c_int),
+                ("u", ctypes.c_void_p), ("u_scale", ctypes.c_float), ("refresh_period", ctypes.c_int),
+                ("refresh_eta", ctypes.c_float), ("step_offset", ctypes.c_int),
+                ("normalise_output", ctypes.c_int), ("feature_map", ctypes.c_int),
+                ("zkey0", ctypes.c_void_p), ("zkey_T", ctypes.c_void_p)]
 
 
 _lib = None
@@ -76,7 +80,7 @@ def status_string(status: int) -> str:
     return load_library().vla_status_string(int(status)).decode()
 
 
-def _opts(lambda0, eps, mode):
+def _opts(lambda0, eps, mode, extra=None):
     o = VlaOpts()
     load_library().vla_default_opts(ctypes.byref(o))
     if lambda0 is not None:
@@ -85,6 +89,9 @@ def _opts(lambda0, eps, mode):
         o.eps = float(eps)
     if mode is not None:
         o.mode = int(mode)
+    for key, val in (extra or {}).items():   # u, u_scale, refresh_period, ... (addresses as int)
+        if val is not None:
+            setattr(o, key, val)
     return o
 
 
@@ -101,9 +108,10 @@ def resolve_mode(B, H, T, d_k, d_v, io_dtype, *, mode=None) -> int:
 
 
 def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *, lambda0=None,
-                    eps=None, mode=None, workspace=0, workspace_bytes=0, stream=0) -> int:
-    """Direct call with integer device addresses (0 = NULL); returns the vla_status."""
-    op = _opts(lambda0, eps, mode)
+                    eps=None, mode=None, workspace=0, workspace_bytes=0, stream=0, **extra) -> int:
+    """Direct call with integer device addresses (0 = NULL); returns the vla_status.
+    `extra`: further vla_opts fields by name (u, zkey0, zkey_T as integer addresses)."""
+    op = _opts(lambda0, eps, mode, extra)
     n = lambda x: ctypes.c_void_p(int(x) if x else None)
     return int(load_library().vla_forward(n(q), n(k), n(v), n(S0), n(A0), n(o), n(S_T), n(A_T),
                                           B, H, T, d_k, d_v, io_dtype, ctypes.byref(op),
@@ -111,7 +119,9 @@ def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *
 
 
 def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None, stream=None,
-                return_state=True):
+                return_state=True, u=None, u_scale=None, refresh_period=None, refresh_eta=None,
+                step_offset=None, normalise_output=None, feature_map=None, zkey0=None,
+                return_zkey=False):
     """Torch-tensor front end: q,k [B,H,T,d_k], v [B,H,T,d_v] on the GPU (float32 or bfloat16).
 
     Allocates o (and S_T, A_T, workspace) with torch, enqueues the kernels on `stream`
@@ -148,9 +158,24 @@ def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None,
         st = stream if stream is not None else torch.cuda.current_stream(dev)
         handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
         p = lambda x: 0 if x is None else x.data_ptr()
+        if u is not None:
+            if u.dtype != q.dtype or tuple(u.shape) != tuple(q.shape) or u.device != dev:
+                raise ValueError("u must match q in dtype, shape and device")
+            u = u.contiguous()
+        if zkey0 is not None and (zkey0.dtype != torch.float32 or tuple(zkey0.shape) != (B, H, dk)
+                                  or not zkey0.is_contiguous() or zkey0.device != dev):
+            raise ValueError(f"zkey0 must be a contiguous float32 tensor of shape {(B, H, dk)} on {dev}")
+        zkey_T = torch.empty((B, H, dk), dtype=torch.float32, device=dev) if return_zkey else None
+        extra = dict(u=p(u) or None, u_scale=u_scale, refresh_period=refresh_period,
+                     refresh_eta=refresh_eta, step_offset=step_offset,
+                     normalise_output=None if normalise_output is None else int(bool(normalise_output)),
+                     feature_map=None if feature_map is None else int(bool(feature_map)),
+                     zkey0=p(zkey0) or None, zkey_T=p(zkey_T) or None)
         rc = vla_forward_raw(p(q), p(k), p(v), p(S0), p(A0), p(o), p(S_T), p(A_T), B, H, T, dk, dv,
                              io, lambda0=lambda0, eps=eps, mode=mode, workspace=p(ws),
-                             workspace_bytes=need, stream=handle)
+                             workspace_bytes=need, stream=handle, **extra)
     if rc != 0:
         raise VlaError(rc, status_string(rc))
+    if return_zkey:
+        return o, S_T, A_T, zkey_T
     return o, S_T, A_T

@@ -26,6 +26,7 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   if (io_dtype != VLA_F32 && io_dtype != VLA_BF16) return VLA_ERR_INVALID_ARG;
   if (o.mode < VLA_MODE_AUTO || o.mode > VLA_MODE_TWO_PHASE) return VLA_ERR_INVALID_ARG;
   if (!(o.lambda0 > 0.0f) || !(o.eps > 0.0f)) return VLA_ERR_INVALID_ARG;
+  if (o.refresh_period < 0 || o.step_offset < 0 || !(o.u_scale == o.u_scale)) return VLA_ERR_INVALID_ARG;
   if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
   // kernels address one head's [T, d] slab with 32-bit byte offsets
   if (static_cast<long long>(T) * (d_k > d_v ? d_k : d_v) * 4 >= 0x7fffffffLL) return VLA_ERR_UNSUPPORTED;
@@ -33,13 +34,21 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   return VLA_OK;
 }
 
+// true when any of the optional lines of Algorithm 1 is switched on
+bool general_path(const vla_opts& o) {
+  return o.u != nullptr || o.refresh_period > 0 || o.normalise_output != 0 || o.feature_map != 0 ||
+         o.zkey0 != nullptr || o.zkey_T != nullptr;
+}
+
 int pick_mode(int /*B*/, int /*H*/, int /*T*/, int d, int /*io_dtype*/, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
+  if (general_path(o)) return VLA_MODE_SCAN;
   return vla::chunk_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
 }
 
-bool mode_available(int mode, int d) {
+bool mode_available(int mode, int d, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return true;
+  if (general_path(o)) return false;
   if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE) return vla::chunk_supported(d);
   return false;
 }
@@ -53,6 +62,15 @@ void vla_default_opts(vla_opts* opts) {
   opts->lambda0 = 0.1f;
   opts->eps = 1e-4f;
   opts->mode = VLA_MODE_AUTO;
+  opts->u = nullptr;
+  opts->u_scale = 1.0f;
+  opts->refresh_period = 0;
+  opts->refresh_eta = 1e-3f;
+  opts->step_offset = 0;
+  opts->normalise_output = 0;
+  opts->feature_map = 0;
+  opts->zkey0 = nullptr;
+  opts->zkey_T = nullptr;
 }
 
 int vla_version(void) { return kVersion; }
@@ -72,7 +90,7 @@ int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const 
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return -1;
   const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  return mode_available(mode, d_k) ? mode : -1;
+  return mode_available(mode, d_k, o) ? mode : -1;
 }
 
 size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
@@ -80,7 +98,7 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
   const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  if (mode == VLA_MODE_TWO_PHASE && mode_available(mode, d_k)) {
+  if (mode == VLA_MODE_TWO_PHASE && mode_available(mode, d_k, o)) {
     return vla::two_phase_workspace_bytes(B * H, T, d_k);
   }
   return 0;
@@ -96,17 +114,17 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   if (T > 0 && (q == nullptr || k == nullptr || v == nullptr || o == nullptr)) {
     return VLA_ERR_INVALID_ARG;
   }
-  const void* ptrs[] = {q, k, v, S0, A0, o, S_T, A_T, workspace};
+  const void* ptrs[] = {q, k, v, S0, A0, o, S_T, A_T, workspace, op.u, op.zkey0, op.zkey_T};
   for (const void* p : ptrs) {
     if (p != nullptr && !aligned16(p)) return VLA_ERR_INVALID_ARG;
   }
   if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
 
   const int mode = pick_mode(B, H, T, d_k, io_dtype, op);
-  if (!mode_available(mode, d_k)) return VLA_ERR_UNSUPPORTED;
+  if (!mode_available(mode, d_k, op)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return VLA_ERR_WORKSPACE;
-  if (T == 0 && S_T == nullptr && A_T == nullptr) return VLA_OK;  // nothing to compute or copy
+  if (T == 0 && S_T == nullptr && A_T == nullptr && op.zkey_T == nullptr) return VLA_OK;  // nothing to do
 
   vla::ForwardArgs a;
   a.q = q; a.k = k; a.v = v; a.S0 = S0; a.A0 = A0;
@@ -116,6 +134,10 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   a.lambda0 = op.lambda0;
   a.eps = op.eps;
   a.ws = static_cast<float*>(workspace);
+  a.u = op.u; a.u_scale = op.u_scale;
+  a.refresh_period = op.refresh_period; a.refresh_eta = op.refresh_eta; a.step_offset = op.step_offset;
+  a.normalise_output = op.normalise_output; a.feature_map = op.feature_map;
+  a.zkey0 = op.zkey0; a.zkey_T = op.zkey_T;
 #ifdef VLA_DEBUG_STAMPS
   a.dbg = workspace_bytes >= (1u << 20) ? static_cast<long long*>(workspace) : nullptr;
 #endif
@@ -123,7 +145,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   hipError_t err = hipSuccess;
   switch (mode) {
     case VLA_MODE_SCAN:
-      err = vla::launch_scan(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      err = general_path(op)
+                ? vla::launch_scan_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
+                : vla::launch_scan(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_CHUNKED:
       err = vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));

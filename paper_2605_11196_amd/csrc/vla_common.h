@@ -20,6 +20,16 @@ struct ForwardArgs {
   float lambda0;
   float eps;
   float* ws;  // device workspace (two-phase mode), else nullptr
+  // the remaining lines of Algorithm 1 (general scan kernel only)
+  const void* u;
+  float u_scale;
+  int refresh_period;
+  float refresh_eta;
+  int step_offset;
+  int normalise_output;
+  int feature_map;
+  const float* zkey0;
+  float* zkey_T;
 #ifdef VLA_DEBUG_STAMPS
   long long* dbg = nullptr;  // development builds only: per-phase cycle stamps
 #endif
@@ -38,6 +48,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 
 // Token-by-token scan, one workgroup per head (vla_scan.hip).
 hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+// Same, with the optional lines of Algorithm 1 (separate u, refresh, normalised read-out, ELU+1).
+hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 64 and 128.

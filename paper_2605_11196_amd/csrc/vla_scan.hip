@@ -197,6 +197,226 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// General variant: all lines of Algorithm 1.  Same thread layout as scan_kernel.  Per token, with
+// u~ the raw penalty direction (the key itself when none is supplied), k the key after the optional
+// feature map, n_k = max(||k||, eps), n_u = max(||u~||, eps), su = u_scale / n_u:
+//   z' = A u~, y' = A k               (one sweep of A_{t-1}, two accumulators)
+//   delta = max(1 + su^2 (u~ . z'), eps);   A -= su^2 z' z'^T / delta;   A += eta I on refresh steps
+//   a = A_t k^ = y'/n_k - z' su^2 (u~ . y') / (n_k delta)  (+ eta k^)       (A symmetric)
+//   alpha^ = a / max(||a||, eps);  e = v - (S k)/n_k;  S += e alpha^^T;  o = S_{t-1} q + e (alpha^ . q)
+//   zkey += k;  o /= max(q . zkey, eps)  when the read-out is normalised (eq. (output))
+// Two reduction rounds per token (a needs delta and u~ . y' first), hence two barriers per token.
+constexpr int kTileG = 16;
+
+__device__ __forceinline__ float elu1(float x) { return x > 0.0f ? x + 1.0f : expf(x); }
+
+template <int D, typename IO>
+__global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
+  constexpr int NT = 2 * D;
+  constexpr int RED_LANES = D < 64 ? D : 64;
+  constexpr int NWA = (D + 63) / 64;
+
+  __shared__ __align__(16) float qs[kTileG * D];
+  __shared__ __align__(16) float ks[kTileG * D];
+  __shared__ __align__(16) float vs[kTileG * D];
+  __shared__ __align__(16) float us[kTileG * D];
+  __shared__ __align__(16) float zb[2][D];   // z' (raw)
+  __shared__ __align__(16) float ab[2][D];   // a = A_t k^
+  __shared__ __align__(16) float red1[2][NWA][8];
+  __shared__ __align__(16) float red2[2][NWA][2];
+
+  const int head = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int role = tid / D;
+  const int i = tid - role * D;
+  const int T = a.T;
+  const bool has_u = a.u != nullptr;
+
+  float row[D];
+  {
+    const float* src = role == 0 ? a.A0 : a.S0;
+    if (src != nullptr) {
+      const float* p = src + (static_cast<size_t>(head) * D + i) * D;
+#pragma unroll
+      for (int j = 0; j < D; j += 4) load4(p + j, &row[j]);
+    } else {
+      const float diag = role == 0 ? 1.0f / a.lambda0 : 0.0f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) row[j] = (j == i) ? diag : 0.0f;
+    }
+  }
+  float zkey = (role == 0 && a.zkey0 != nullptr) ? a.zkey0[static_cast<size_t>(head) * D + i] : 0.0f;
+
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  const IO* uh = has_u ? static_cast<const IO*>(a.u) + slab : kh;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+  const float eps = a.eps;
+
+  for (int t0 = 0; t0 < T; t0 += kTileG) {
+    const int nt = (T - t0) < kTileG ? (T - t0) : kTileG;
+    __syncthreads();
+    for (int idx = tid; idx < nt * (D / 4); idx += NT) {
+      const size_t off = static_cast<size_t>(t0) * D + static_cast<size_t>(idx) * 4;
+      float x[4];
+      load4(qh + off, x);
+      if (a.feature_map) { x[0] = elu1(x[0]); x[1] = elu1(x[1]); x[2] = elu1(x[2]); x[3] = elu1(x[3]); }
+      *reinterpret_cast<float4*>(&qs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+      load4(kh + off, x);
+      if (a.feature_map) { x[0] = elu1(x[0]); x[1] = elu1(x[1]); x[2] = elu1(x[2]); x[3] = elu1(x[3]); }
+      *reinterpret_cast<float4*>(&ks[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+      if (has_u) load4(uh + off, x);  // without a supplied u the penalty direction is the key as used
+      *reinterpret_cast<float4*>(&us[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+      load4(vh + off, x);
+      *reinterpret_cast<float4*>(&vs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
+    }
+    __syncthreads();
+
+    for (int tt = 0; tt < nt; ++tt) {
+      const int par = tt & 1;
+      const float4* k4 = reinterpret_cast<const float4*>(&ks[tt * D]);
+      const float4* q4 = reinterpret_cast<const float4*>(&qs[tt * D]);
+      const float4* u4 = reinterpret_cast<const float4*>(&us[tt * D]);
+
+      // role 0: m = z' = A u~, r = y' = A k ; role 1: m = S k, r = S q
+      float m0 = 0.f, m1 = 0.f, r0 = 0.f, r1 = 0.f;
+      {
+        const float4* x4 = role == 0 ? u4 : k4;
+        const float4* y4 = role == 0 ? k4 : q4;
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 xx = x4[j / 4];
+          const float4 yy = y4[j / 4];
+          m0 = fmaf(row[j + 0], xx.x, m0);
+          m1 = fmaf(row[j + 1], xx.y, m1);
+          m0 = fmaf(row[j + 2], xx.z, m0);
+          m1 = fmaf(row[j + 3], xx.w, m1);
+          r0 = fmaf(row[j + 0], yy.x, r0);
+          r1 = fmaf(row[j + 1], yy.y, r1);
+          r0 = fmaf(row[j + 2], yy.z, r0);
+          r1 = fmaf(row[j + 3], yy.w, r1);
+        }
+      }
+      const float mv = m0 + m1;
+      const float rv = r0 + r1;
+
+      // ---- round 1: k.k, u~.u~, u~.z', u~.y', q.zkey
+      float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+      float ki = 0.f;
+      if (role == 0) {
+        ki = ks[tt * D + i];
+        const float ui = us[tt * D + i];
+        zkey += ki;
+        s[0] = ki * ki;
+        s[1] = ui * ui;
+        s[2] = ui * mv;
+        s[3] = ui * rv;
+        s[4] = qs[tt * D + i] * zkey;
+        zb[par][i] = mv;
+      }
+#pragma unroll
+      for (int off = RED_LANES / 2; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int e = 0; e < 5; ++e) s[e] += __shfl_xor(s[e], off);
+      }
+      if (role == 0 && (i % RED_LANES) == 0) {
+#pragma unroll
+        for (int e = 0; e < 5; ++e) red1[par][i / RED_LANES][e] = s[e];
+      }
+      __syncthreads();
+
+      float kk = 0.f, uu = 0.f, uz = 0.f, uy = 0.f, qz = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWA; ++w) {
+        kk += red1[par][w][0]; uu += red1[par][w][1]; uz += red1[par][w][2];
+        uy += red1[par][w][3]; qz += red1[par][w][4];
+      }
+      const float inv_nk = 1.0f / fmaxf(sqrtf(kk), eps);
+      const float su = (has_u ? a.u_scale : 1.0f) / fmaxf(sqrtf(uu), eps);  // u = k^ carries no scale
+      const float su2 = su * su;
+      const float delta = fmaxf(1.0f + su2 * uz, eps);
+      const float cz = su2 / delta;  // A -= cz z' z'^T ;  a = y' inv_nk - z' cz (u~ . y') inv_nk
+      const bool refresh = a.refresh_period > 0 && ((a.step_offset + t0 + tt + 1) % a.refresh_period) == 0;
+      const float eta = refresh ? a.refresh_eta : 0.0f;
+      const float4* z4 = reinterpret_cast<const float4*>(&zb[par][0]);
+
+      // ---- round 2: a = A_t k^ on the A threads; ||a||^2, a.q
+      float t2[2] = {0.f, 0.f};
+      if (role == 0) {
+        const float ai = (rv - mv * cz * uy) * inv_nk + eta * ki * inv_nk;
+        ab[par][i] = ai;
+        t2[0] = ai * ai;
+        t2[1] = ai * qs[tt * D + i];
+        const float f = -mv * cz;
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 zj = z4[j / 4];
+          row[j + 0] = fmaf(f, zj.x, row[j + 0]);
+          row[j + 1] = fmaf(f, zj.y, row[j + 1]);
+          row[j + 2] = fmaf(f, zj.z, row[j + 2]);
+          row[j + 3] = fmaf(f, zj.w, row[j + 3]);
+        }
+        if (refresh) {
+#pragma unroll
+          for (int j = 0; j < D; ++j) row[j] += (j == i) ? eta : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int off = RED_LANES / 2; off >= 1; off >>= 1) {
+        t2[0] += __shfl_xor(t2[0], off);
+        t2[1] += __shfl_xor(t2[1], off);
+      }
+      if (role == 0 && (i % RED_LANES) == 0) {
+        red2[par][i / RED_LANES][0] = t2[0];
+        red2[par][i / RED_LANES][1] = t2[1];
+      }
+      __syncthreads();
+
+      if (role == 1) {
+        float aa = 0.f, aq = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWA; ++w) { aa += red2[par][w][0]; aq += red2[par][w][1]; }
+        const float inv_an = 1.0f / fmaxf(sqrtf(aa), eps);
+        const float e = vs[tt * D + i] - mv * inv_nk;
+        const float gcoef = e * inv_an;
+        const float4* a4 = reinterpret_cast<const float4*>(&ab[par][0]);
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+          const float4 aj = a4[j / 4];
+          row[j + 0] = fmaf(gcoef, aj.x, row[j + 0]);
+          row[j + 1] = fmaf(gcoef, aj.y, row[j + 1]);
+          row[j + 2] = fmaf(gcoef, aj.z, row[j + 2]);
+          row[j + 3] = fmaf(gcoef, aj.w, row[j + 3]);
+        }
+        float ov = fmaf(gcoef, aq, rv);
+        if (a.normalise_output) ov /= fmaxf(qz, eps);
+        store1(oh + static_cast<size_t>(t0 + tt) * D + i, ov);
+      }
+    }
+  }
+
+  float* dst = role == 0 ? a.A_T : a.S_T;
+  if (dst != nullptr) {
+    float* p = dst + (static_cast<size_t>(head) * D + i) * D;
+#pragma unroll
+    for (int j = 0; j < D; j += 4) {
+      *reinterpret_cast<float4*>(p + j) = make_float4(row[j], row[j + 1], row[j + 2], row[j + 3]);
+    }
+  }
+  if (role == 0 && a.zkey_T != nullptr) a.zkey_T[static_cast<size_t>(head) * D + i] = zkey;
+}
+
+template <int D, typename IO>
+hipError_t launch_general(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_general_kernel<D, IO>), dim3(a.n_heads),
+                         dim3(2 * D), params, 0, stream);
+}
+
 template <int D, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   // hipLaunchKernel reports this launch's own status; the sticky hipGetLastError() value may
@@ -216,6 +436,17 @@ hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t st
     case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
     case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
     case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 16: return bf ? launch_general<16, uint16_t>(a, stream) : launch_general<16, float>(a, stream);
+    case 32: return bf ? launch_general<32, uint16_t>(a, stream) : launch_general<32, float>(a, stream);
+    case 64: return bf ? launch_general<64, uint16_t>(a, stream) : launch_general<64, float>(a, stream);
+    case 128: return bf ? launch_general<128, uint16_t>(a, stream) : launch_general<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -40,6 +40,27 @@ def test_default_opts():
     o = binding.VlaOpts()
     vla.load_library().vla_default_opts(ctypes.byref(o))
     assert abs(o.lambda0 - 0.1) < 1e-7 and abs(o.eps - 1e-4) < 1e-10 and o.mode == vla.MODE_AUTO
+    assert o.u is None and o.u_scale == 1.0 and o.refresh_period == 0 and abs(o.refresh_eta - 1e-3) < 1e-9
+    assert o.step_offset == 0 and o.normalise_output == 0 and o.feature_map == 0
+    assert o.zkey0 is None and o.zkey_T is None
+
+
+def test_opts_struct_layout_matches_the_header():
+    """ctypes mirror of vla_opts: field order and count as declared in include/vla.h."""
+    text = open(os.path.join(ROOT, "include", "vla.h")).read()
+    body = re.search(r"typedef struct vla_opts \{(.*?)\} vla_opts;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = re.findall(r"(\w+)\s*;", body)
+    assert names == [f[0] for f in binding.VlaOpts._fields_]
+
+
+def test_options_force_the_scan_family():
+    assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
+    o = binding._opts(None, None, None, dict(refresh_period=20))
+    lib = vla.load_library()
+    assert lib.vla_resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, ctypes.byref(o)) == vla.MODE_SCAN
+    o = binding._opts(None, None, vla.MODE_CHUNKED, dict(normalise_output=1))
+    assert lib.vla_resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, ctypes.byref(o)) == -1
 
 
 FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on these paths
@@ -58,6 +79,8 @@ def call(**kw):
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), 1), (dict(H=-1), 1), (dict(T=-1), 1), (dict(d_k=0, d_v=0), 1),
     (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
+    (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
+    (dict(mode=2, d_k=64, d_v=64, refresh_period=3), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=32), 2), (dict(d_k=256, d_v=256), 2),

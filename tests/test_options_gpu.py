@@ -1,0 +1,103 @@
+"""GPU parity for the optional lines of Algorithm 1 (separate penalty direction u, periodic identity
+refresh, normalised read-out with the running key sum, ELU+1 feature map): general scan kernel through
+the C ABI against the fp64 oracle, same error metric and tolerances as the main parity tests."""
+import numpy as np
+import pytest
+
+import oracle
+import vla_inputs
+from parity_utils import TOL, slab_rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, **opt):
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    if dtype == "bf16":
+        q, k, v = (vla_inputs.round_to_bf16(x) for x in (q, k, v))
+        u = None if u is None else vla_inputs.round_to_bf16(u)
+    ref = oracle.forward(q, k, v, S0, A0, u=u, zkey0=zkey0, **opt)
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    t = lambda x, dt=tdt: None if x is None else torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(dt)
+    o, S_T, A_T, zk = vla.vla_forward(t(q), t(k), t(v), t(S0, torch.float32), t(A0, torch.float32),
+                                       u=t(u), zkey0=t(zkey0, torch.float32), return_zkey=True,
+                                       lambda0=opt.get("lambda0"), eps=opt.get("eps"),
+                                       u_scale=opt.get("u_scale"), refresh_period=opt.get("refresh_period"),
+                                       refresh_eta=opt.get("refresh_eta"), step_offset=opt.get("step_offset"),
+                                       normalise_output=opt.get("normalise_output"),
+                                       feature_map=opt.get("feature_map"))
+    torch.cuda.synchronize()
+    got = dict(o=to_np(o), S_T=to_np(S_T), A_T=to_np(A_T), zkey_T=to_np(zk))
+    return got, ref
+
+
+def assert_close(got, ref, tol):
+    errs = dict(o=slab_rel_err(got["o"], ref["o"], 2), S=slab_rel_err(got["S_T"], ref["S_T"], 2),
+                A=slab_rel_err(got["A_T"], ref["A_T"], 2), z=slab_rel_err(got["zkey_T"], ref["zkey_T"], 1))
+    assert all(np.isfinite(x).all() for x in got.values())
+    assert max(errs.values()) <= tol, errs
+    return errs
+
+
+OPTION_SETS = {
+    "supplied_u": dict(with_u=True),
+    "supplied_u_scaled": dict(with_u=True, u_scale=0.125),
+    "refresh": dict(refresh_period=20, refresh_eta=1e-3),
+    "normalised": dict(normalise_output=True, positive=True),
+    "feature_map": dict(feature_map=True),
+    "algorithm1": dict(with_u=True, u_scale=0.125, refresh_period=20, refresh_eta=1e-3,
+                       normalise_output=True, feature_map=True),
+    "only_key_sum": dict(want_zkey_only=True),
+}
+
+
+@pytest.mark.parametrize("name", list(OPTION_SETS))
+@pytest.mark.parametrize("d,T,dtype", [(16, 70, "f32"), (64, 130, "f32"), (128, 45, "f32"), (32, 97, "bf16"),
+                                       (128, 64, "bf16")])
+def test_option_parity(name, d, T, dtype):
+    cfg = dict(OPTION_SETS[name])
+    rng = np.random.default_rng(900 + d + T)
+    q, k, v = vla_inputs.gaussian_qkv(2, 2, T, d, seed=700 + d + T)
+    if cfg.pop("positive", False):      # a meaningful denominator needs non-negative features
+        q, k = np.abs(q) + 0.05, np.abs(k) + 0.05
+    u = rng.standard_normal(q.shape).astype(np.float32) if cfg.pop("with_u", False) else None
+    cfg.pop("want_zkey_only", None)
+    got, ref = run_both(q, k, v, dtype=dtype, u=u, lambda0=0.1, **cfg)
+    print(name, d, T, dtype, assert_close(got, ref, TOL[dtype]))
+
+
+def test_split_sequence_with_every_option_carries_state():
+    """[0,T1) then [T1,T) with S, A, the key sum and the refresh phase carried == one call."""
+    d, T, T1 = 64, 101, 37
+    rng = np.random.default_rng(5)
+    q, k, v = vla_inputs.gaussian_qkv(1, 3, T, d, seed=55)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    opt = dict(lambda0=0.1, u_scale=0.125, refresh_period=8, refresh_eta=1e-2, normalise_output=True,
+               feature_map=True)
+    full, ref = run_both(q, k, v, u=u, **opt)
+    assert_close(full, ref, 1e-4)
+    a, _ = run_both(q[:, :, :T1], k[:, :, :T1], v[:, :, :T1], u=u[:, :, :T1], **opt)
+    b, _ = run_both(q[:, :, T1:], k[:, :, T1:], v[:, :, T1:], u=u[:, :, T1:], S0=a["S_T"], A0=a["A_T"],
+                    zkey0=a["zkey_T"], step_offset=T1, **opt)
+    joined = dict(o=np.concatenate([a["o"], b["o"]], axis=2), S_T=b["S_T"], A_T=b["A_T"], zkey_T=b["zkey_T"])
+    assert_close(joined, ref, 1e-4)
+
+
+def test_options_are_refused_by_the_block_kernels():
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    dev = torch.device("cuda:0")
+    x = torch.randn(1, 1, 32, 64, device=dev)
+    for mode in (vla.MODE_CHUNKED, vla.MODE_TWO_PHASE):
+        with pytest.raises(vla.VlaError) as e:
+            vla.vla_forward(x, x, x, mode=mode, refresh_period=4)
+        assert e.value.status == 2
+    o, _, _ = vla.vla_forward(x, x, x, refresh_period=4)     # AUTO falls back to the scan family
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
