@@ -9,7 +9,7 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
-bool supported_head_size(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+bool supported_head_size(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

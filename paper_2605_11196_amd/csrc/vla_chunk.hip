@@ -462,11 +462,12 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-bool chunk_supported(int d) { return d == 64 || d == 128; }
+bool chunk_supported(int d) { return d == 32 || d == 64 || d == 128; }
 
 hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
   const bool bf = io_dtype == 1;
   switch (d) {
+    case 32: return bf ? launch<32, 1, uint16_t>(a, stream) : launch<32, 1, float>(a, stream);
     case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
     case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;

@@ -435,6 +435,7 @@ hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t st
     case 16: return bf ? launch<16, uint16_t>(a, stream) : launch<16, float>(a, stream);
     case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
     case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
+    case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);
     case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }
@@ -446,6 +447,7 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
     case 16: return bf ? launch_general<16, uint16_t>(a, stream) : launch_general<16, float>(a, stream);
     case 32: return bf ? launch_general<32, uint16_t>(a, stream) : launch_general<32, float>(a, stream);
     case 64: return bf ? launch_general<64, uint16_t>(a, stream) : launch_general<64, float>(a, stream);
+    case 96: return bf ? launch_general<96, uint16_t>(a, stream) : launch_general<96, float>(a, stream);
     case 128: return bf ? launch_general<128, uint16_t>(a, stream) : launch_general<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }

@@ -488,6 +488,7 @@ size_t two_phase_workspace_bytes(int n_heads, int T, int d) {
 hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
   const bool bf = io_dtype == 1;
   switch (d) {
+    case 32: return bf ? launch<32, 1, uint16_t>(a, stream) : launch<32, 1, float>(a, stream);
     case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
     case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;

@@ -56,7 +56,7 @@ OPTION_SETS = {
 
 
 @pytest.mark.parametrize("name", list(OPTION_SETS))
-@pytest.mark.parametrize("d,T,dtype", [(16, 70, "f32"), (64, 130, "f32"), (128, 45, "f32"), (32, 97, "bf16"),
+@pytest.mark.parametrize("d,T,dtype", [(16, 70, "f32"), (64, 130, "f32"), (128, 45, "f32"), (96, 58, "f32"), (32, 97, "bf16"),
                                        (128, 64, "bf16")])
 def test_option_parity(name, d, T, dtype):
     cfg = dict(OPTION_SETS[name])

@@ -137,7 +137,7 @@ def test_config5_large_batch_bf16_sampled_heads():
 @pytest.mark.parametrize("mode", ALL_MODES)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("d,T", [(16, 37), (32, 131), (64, 257), (128, 193), (64, 1), (128, 2),
-                                 (32, 32), (128, 64), (64, 63), (16, 65)])
+                                 (32, 32), (128, 64), (64, 63), (16, 65), (96, 77), (96, 16), (32, 500)])
 def test_head_sizes_dtypes_and_ragged_lengths(d, T, dtype, mode):
     skip_unless_mode(d, mode, dtype)
     q, k, v = vla_inputs.gaussian_qkv(2, 3, T, d, seed=100 + d + T)
@@ -146,7 +146,7 @@ def test_head_sizes_dtypes_and_ragged_lengths(d, T, dtype, mode):
 
 
 @pytest.mark.parametrize("mode", ALL_MODES)
-@pytest.mark.parametrize("d", [16, 64, 128])
+@pytest.mark.parametrize("d", [16, 32, 64, 96, 128])
 def test_given_initial_state_and_state_carry(d, mode):
     skip_unless_mode(d, mode)
     rng = np.random.default_rng(7)
