@@ -39,6 +39,7 @@ def parse_args():
                     choices=["tiny", "norm_growth", "recall", "long_context", "large_batch"])
     ap.add_argument("--T", type=int, default=None, help="sequence length override (long_context)")
     ap.add_argument("--B", type=int, default=None, help="batch override (experiments only)")
+    ap.add_argument("--d", type=int, default=None, help="head size override (experiments only)")
     ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -68,6 +69,10 @@ def main():
         c["T"] = args.T
     if args.B:
         c["B"] = args.B
+    if args.d:
+        c["d"] = args.d
+        if "std" in c and args.workload == "large_batch":
+            c["std"] = args.d ** -0.5
     B, H, T, d = c["B"], c["H"], c["T"], c["d"]
     dtype = c["dtype"]
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
