@@ -157,7 +157,7 @@ def main():
         "config": {"workload": workload, "io_dtype": dtype, "kernel_mode": mode_names.get(resolved, str(resolved)),
                    "global_batch": B, "heads": H, "seq_len": T, "d_h": d, "parallelism": "single-gpu"},
         "roofline": {
-            "bound": "mfma" if resolved == 2 else "alu",
+            "bound": "mfma" if resolved in (2, 3) else "alu",
             "achieved": achieved_tflops,
             "peak": PEAK_FP32_TFLOPS,
             "unit": "TFLOP/s",

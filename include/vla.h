@@ -41,7 +41,10 @@ extern "C" {
 typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
- *   AUTO     : the library picks (currently by head size, dtype and B*H).
+ *   AUTO     : the library picks: SCAN when an option of Algorithm 1 is switched on or the head
+ *              size has no block kernel; TWO_PHASE for B*H <= 64 and T >= 1024 if the caller
+ *              passed the workspace vla_forward_workspace_bytes() asks for (else CHUNKED);
+ *              CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
  *              resident in registers (FP32 vector ALU).
  *   CHUNKED  : tokens are processed in blocks; the block form of the same
@@ -139,8 +142,9 @@ const char* vla_status_string(int status);
 /* Library version: major*10000 + minor*100 + patch. */
 int vla_version(void);
 
-/* Which concrete mode AUTO resolves to for these arguments (a vla_mode, never AUTO),
- * or -1 if the arguments are invalid/unsupported.  Host-only, launches nothing. */
+/* Which concrete mode AUTO resolves to for these arguments when the workspace asked for by
+ * vla_forward_workspace_bytes() is passed (a vla_mode, never AUTO), or -1 if the arguments are
+ * invalid/unsupported.  Host-only, launches nothing. */
 int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts* opts);
 
 #ifdef __cplusplus

@@ -40,10 +40,14 @@ bool general_path(const vla_opts& o) {
          o.zkey0 != nullptr || o.zkey_T != nullptr;
 }
 
-int pick_mode(int /*B*/, int /*H*/, int /*T*/, int d, int /*io_dtype*/, const vla_opts& o) {
+// AUTO: options -> scan family; few heads on a long sequence -> two-phase (the S rows then spread over
+// d/16 times more workgroups than there are heads); otherwise the fused block kernel.
+int pick_mode(int B, int H, int T, int d, int /*io_dtype*/, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (general_path(o)) return VLA_MODE_SCAN;
-  return vla::chunk_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
+  if (!vla::chunk_supported(d)) return VLA_MODE_SCAN;
+  const long long heads = static_cast<long long>(B) * H;
+  return (heads <= 64 && T >= 1024) ? VLA_MODE_TWO_PHASE : VLA_MODE_CHUNKED;
 }
 
 bool mode_available(int mode, int d, const vla_opts& o) {
@@ -120,10 +124,14 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   }
   if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
 
-  const int mode = pick_mode(B, H, T, d_k, io_dtype, op);
+  int mode = pick_mode(B, H, T, d_k, io_dtype, op);
   if (!mode_available(mode, d_k, op)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
-  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return VLA_ERR_WORKSPACE;
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
+    // AUTO never fails for want of a workspace: it falls back to the fused block kernel
+    if (op.mode != VLA_MODE_AUTO) return VLA_ERR_WORKSPACE;
+    mode = VLA_MODE_CHUNKED;
+  }
   if (T == 0 && S_T == nullptr && A_T == nullptr && op.zkey_T == nullptr) return VLA_OK;  // nothing to do
 
   vla::ForwardArgs a;

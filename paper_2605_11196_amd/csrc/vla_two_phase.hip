@@ -346,7 +346,7 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
 
 // ------------------------------------------------------------------------------------------ phase 2
 // One wave per (head, 16-row slab of S).  st[b][r] = S[row0 + c][16b + 4g + r].
-template <int D, typename IO>
+template <int D, int DEPTH, typename IO>
 __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   constexpr int NB = D / 16;
   constexpr int NSLAB = D / 16;
@@ -410,10 +410,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     }
   };
 
-  Ops cur, nxt;
-  if (nblk > 0) load_ops(0, cur);
-  for (int blk = 0; blk < nblk; ++blk) {
-    if (blk + 1 < nblk) load_ops(blk + 1, nxt);
+  auto compute = [&](int blk, const Ops& cur) {
     const int t0 = blk * C;
     const bool qlive = t0 + c < T;
     f4 ft, ot = f4{0, 0, 0, 0};
@@ -444,7 +441,31 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int r = 0; r < 4; ++r) st[b] = mfma16(cur.wa[b][r], ce[r], st[b]);
-    cur = nxt;
+  };
+
+  // The wave is alone on its SIMD slot and bound by memory latency, so operands are fetched DEPTH
+  // blocks ahead into rotating register sets (the loop is unrolled by DEPTH + 1 to keep them static).
+  if constexpr (DEPTH == 2) {
+    Ops o0, o1, o2;
+    if (nblk > 0) load_ops(0, o0);
+    if (nblk > 1) load_ops(1, o1);
+    for (int blk = 0; blk < nblk; blk += 3) {
+      if (blk + 2 < nblk) load_ops(blk + 2, o2);
+      compute(blk, o0);
+      if (blk + 3 < nblk) load_ops(blk + 3, o0);
+      if (blk + 1 < nblk) compute(blk + 1, o1);
+      if (blk + 4 < nblk) load_ops(blk + 4, o1);
+      if (blk + 2 < nblk) compute(blk + 2, o2);
+    }
+  } else {
+    Ops o0, o1;
+    if (nblk > 0) load_ops(0, o0);
+    for (int blk = 0; blk < nblk; blk += 2) {
+      if (blk + 1 < nblk) load_ops(blk + 1, o1);
+      compute(blk, o0);
+      if (blk + 2 < nblk) load_ops(blk + 2, o0);
+      if (blk + 1 < nblk) compute(blk + 1, o1);
+    }
   }
 
   if (a.S_T) {
@@ -474,7 +495,8 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
                           dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), p2, 0, stream);
     if (err != hipSuccess) return err;
   }
-  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, IO>),
+  constexpr int kDepth = D <= 64 ? 2 : 1;  // register budget: three operand sets only fit up to d = 64
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO>),
                          dim3(a.n_heads * (D / 16)), dim3(64), params, 0, stream);
 }
 
