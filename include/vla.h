@@ -42,7 +42,7 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
  *   AUTO     : the library picks: SCAN when an option of Algorithm 1 is switched on or the head
- *              size has no block kernel; TWO_PHASE for B*H <= 64 and T >= 1024 if the caller
+ *              size has no block kernel; TIME_PARALLEL for B*H <= 64 and T >= 1024 if the caller
  *              passed the workspace vla_forward_workspace_bytes() asks for (else CHUNKED);
  *              CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
@@ -54,12 +54,19 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
  *              workspace; phase 2 runs the S recurrence with the rows of S spread
  *              over several workgroups (for small B*H).  Allowed because A never
  *              reads S (eq. (sm)); Algorithm 2 takes k^, alpha^ as given inputs.
+ *   TIME_PARALLEL: TWO_PHASE with the sequence cut into segments that run concurrently (for small
+ *              B*H and long T).  With u = k^ and no refresh, A at a segment boundary is the explicit
+ *              inverse (A_0^{-1} + sum of k^ k^T up to there)^{-1} of Section 3.2, computed in float64
+ *              from one Gram matrix per segment; S at a boundary follows by composing the per-segment
+ *              affine maps S -> S P + Q of eq. (s-update).  Inside a segment the recurrence is the
+ *              same exact block form.  Same result up to float32 rounding.
  */
 typedef enum {
   VLA_MODE_AUTO = 0,
   VLA_MODE_SCAN = 1,
   VLA_MODE_CHUNKED = 2,
-  VLA_MODE_TWO_PHASE = 3
+  VLA_MODE_TWO_PHASE = 3,
+  VLA_MODE_TIME_PARALLEL = 4
 } vla_mode;
 
 typedef enum {
@@ -74,8 +81,8 @@ typedef enum {
  * vla_default_opts() and then change fields: later library versions may append fields.
  *
  * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
- * With any of them set only the SCAN kernel family applies (AUTO selects it; asking for CHUNKED or
- * TWO_PHASE returns VLA_ERR_UNSUPPORTED). */
+ * With any of them set only the SCAN kernel family applies (AUTO selects it; asking for CHUNKED,
+ * TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED). */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
   float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the
@@ -98,6 +105,9 @@ typedef struct vla_opts {
   const float* zkey0;   /* [NULL = 0] device, [B, H, d_k] float32: key sum carried in from earlier calls */
   float* zkey_T;        /* [NULL = not wanted] device, [B, H, d_k] float32: key sum after the last token;
                            may alias zkey0 */
+  int segments;         /* [0 = the library chooses] TIME_PARALLEL only: number of time segments (at most
+                           256; capped at one per 16 tokens).  Sizes the workspace, so pass the same
+                           value to vla_forward_workspace_bytes() and vla_forward() */
 } vla_opts;
 
 /* Fills *opts with the defaults above. */

@@ -5,6 +5,7 @@ from .binding import (  # noqa: F401
     MODE_AUTO,
     MODE_CHUNKED,
     MODE_SCAN,
+    MODE_TIME_PARALLEL,
     MODE_TWO_PHASE,
     VlaError,
     lib_path,

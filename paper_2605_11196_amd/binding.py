@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libvla.so"
 
 VLA_F32, VLA_BF16 = 0, 1
-MODE_AUTO, MODE_SCAN, MODE_CHUNKED, MODE_TWO_PHASE = 0, 1, 2, 3
+MODE_AUTO, MODE_SCAN, MODE_CHUNKED, MODE_TWO_PHASE, MODE_TIME_PARALLEL = 0, 1, 2, 3, 4
 
 EXPORTS = ("vla_default_opts", "vla_forward_workspace_bytes", "vla_forward",
            "vla_status_string", "vla_version", "vla_resolve_mode")
@@ -28,7 +28,7 @@ class VlaOpts(ctypes.Structure):
                 ("u", ctypes.c_void_p), ("u_scale", ctypes.c_float), ("refresh_period", ctypes.c_int),
                 ("refresh_eta", ctypes.c_float), ("step_offset", ctypes.c_int),
                 ("normalise_output", ctypes.c_int), ("feature_map", ctypes.c_int),
-                ("zkey0", ctypes.c_void_p), ("zkey_T", ctypes.c_void_p)]
+                ("zkey0", ctypes.c_void_p), ("zkey_T", ctypes.c_void_p), ("segments", ctypes.c_int)]
 
 
 _lib = None
@@ -96,8 +96,8 @@ def _opts(lambda0, eps, mode, extra=None):
 
 
 def vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, *, lambda0=None, eps=None,
-                                mode=None) -> int:
-    o = _opts(lambda0, eps, mode)
+                                mode=None, segments=None) -> int:
+    o = _opts(lambda0, eps, mode, dict(segments=segments))
     return int(load_library().vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype,
                                                           ctypes.byref(o)))
 
@@ -121,7 +121,7 @@ def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *
 def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None, stream=None,
                 return_state=True, u=None, u_scale=None, refresh_period=None, refresh_eta=None,
                 step_offset=None, normalise_output=None, feature_map=None, zkey0=None,
-                return_zkey=False):
+                return_zkey=False, segments=None):
     """Torch-tensor front end: q,k [B,H,T,d_k], v [B,H,T,d_v] on the GPU (float32 or bfloat16).
 
     Allocates o (and S_T, A_T, workspace) with torch, enqueues the kernels on `stream`
@@ -153,7 +153,8 @@ def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None,
         o = torch.empty((B, H, T, dv), dtype=q.dtype, device=dev)
         S_T = torch.empty((B, H, dv, dk), dtype=torch.float32, device=dev) if return_state else None
         A_T = torch.empty((B, H, dk, dk), dtype=torch.float32, device=dev) if return_state else None
-        need = vla_forward_workspace_bytes(B, H, T, dk, dv, io, lambda0=lambda0, eps=eps, mode=mode)
+        need = vla_forward_workspace_bytes(B, H, T, dk, dv, io, lambda0=lambda0, eps=eps, mode=mode,
+                                           segments=segments)
         ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev) if need else None
         st = stream if stream is not None else torch.cuda.current_stream(dev)
         handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
@@ -170,7 +171,7 @@ def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None,
                      refresh_eta=refresh_eta, step_offset=step_offset,
                      normalise_output=None if normalise_output is None else int(bool(normalise_output)),
                      feature_map=None if feature_map is None else int(bool(feature_map)),
-                     zkey0=p(zkey0) or None, zkey_T=p(zkey_T) or None)
+                     zkey0=p(zkey0) or None, zkey_T=p(zkey_T) or None, segments=segments)
         rc = vla_forward_raw(p(q), p(k), p(v), p(S0), p(A0), p(o), p(S_T), p(A_T), B, H, T, dk, dv,
                              io, lambda0=lambda0, eps=eps, mode=mode, workspace=p(ws),
                              workspace_bytes=need, stream=handle, **extra)

@@ -24,7 +24,8 @@ vla_opts resolve_opts(const vla_opts* o) {
 int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts& o) {
   if (B <= 0 || H <= 0 || T < 0 || d_k <= 0 || d_v <= 0) return VLA_ERR_INVALID_ARG;
   if (io_dtype != VLA_F32 && io_dtype != VLA_BF16) return VLA_ERR_INVALID_ARG;
-  if (o.mode < VLA_MODE_AUTO || o.mode > VLA_MODE_TWO_PHASE) return VLA_ERR_INVALID_ARG;
+  if (o.mode < VLA_MODE_AUTO || o.mode > VLA_MODE_TIME_PARALLEL) return VLA_ERR_INVALID_ARG;
+  if (o.segments < 0) return VLA_ERR_INVALID_ARG;
   if (!(o.lambda0 > 0.0f) || !(o.eps > 0.0f)) return VLA_ERR_INVALID_ARG;
   if (o.refresh_period < 0 || o.step_offset < 0 || !(o.u_scale == o.u_scale)) return VLA_ERR_INVALID_ARG;
   if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
@@ -40,20 +41,23 @@ bool general_path(const vla_opts& o) {
          o.zkey0 != nullptr || o.zkey_T != nullptr;
 }
 
-// AUTO: options -> scan family; few heads on a long sequence -> two-phase (the S rows then spread over
-// d/16 times more workgroups than there are heads); otherwise the fused block kernel.
+// AUTO: options -> scan family; few heads on a long sequence -> time-parallel (segments of the sequence run
+// concurrently and the S rows spread over d/16 times more workgroups than there are heads); otherwise the
+// fused block kernel.
 int pick_mode(int B, int H, int T, int d, int /*io_dtype*/, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (general_path(o)) return VLA_MODE_SCAN;
   if (!vla::chunk_supported(d)) return VLA_MODE_SCAN;
   const long long heads = static_cast<long long>(B) * H;
-  return (heads <= 64 && T >= 1024) ? VLA_MODE_TWO_PHASE : VLA_MODE_CHUNKED;
+  return (heads <= 64 && T >= 1024) ? VLA_MODE_TIME_PARALLEL : VLA_MODE_CHUNKED;
 }
 
 bool mode_available(int mode, int d, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return true;
   if (general_path(o)) return false;
-  if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE) return vla::chunk_supported(d);
+  if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
+    return vla::chunk_supported(d);
+  }
   return false;
 }
 
@@ -75,6 +79,7 @@ void vla_default_opts(vla_opts* opts) {
   opts->feature_map = 0;
   opts->zkey0 = nullptr;
   opts->zkey_T = nullptr;
+  opts->segments = 0;
 }
 
 int vla_version(void) { return kVersion; }
@@ -102,9 +107,9 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
   const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  if (mode == VLA_MODE_TWO_PHASE && mode_available(mode, d_k, o)) {
-    return vla::two_phase_workspace_bytes(B * H, T, d_k);
-  }
+  if (!mode_available(mode, d_k, o)) return 0;
+  if (mode == VLA_MODE_TWO_PHASE) return vla::two_phase_workspace_bytes(B * H, T, d_k);
+  if (mode == VLA_MODE_TIME_PARALLEL) return vla::time_parallel_workspace_bytes(B * H, T, d_k, o.segments);
   return 0;
 }
 
@@ -162,6 +167,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
       break;
     case VLA_MODE_TWO_PHASE:
       err = vla::launch_two_phase(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      break;
+    case VLA_MODE_TIME_PARALLEL:
+      err = vla::launch_time_parallel(a, d_k, io_dtype, op.segments, static_cast<hipStream_t>(stream));
       break;
     default:
       return VLA_ERR_UNSUPPORTED;

@@ -30,6 +30,12 @@ struct ForwardArgs {
   int feature_map;
   const float* zkey0;
   float* zkey_T;
+  // time segments (time-parallel mode; n_seg == 1 everywhere else)
+  int n_seg = 1;                  // segments per head
+  int seg_blocks = 0;             // 16-token blocks per segment (the last one may hold fewer)
+  const float* seg_A = nullptr;   // [n_heads][n_seg][d][d]  A at the start of every segment
+  const float* seg_S = nullptr;   // [n_heads][n_seg][d][d]  S at the start of every segment
+  float* seg_PQ = nullptr;        // [n_heads][n_seg][2][d][d]  per-segment affine map of the S recurrence
 #ifdef VLA_DEBUG_STAMPS
   long long* dbg = nullptr;  // development builds only: per-phase cycle stamps
 #endif
@@ -60,5 +66,23 @@ hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t s
 // Two-phase split (vla_two_phase.hip): A recurrence first, then the rows of S on many workgroups.
 size_t two_phase_workspace_bytes(int n_heads, int T, int d);
 hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+
+// Time-parallel mode: the sequence is cut into segments that run concurrently (vla_two_phase.hip drives it,
+// vla_segments.hip holds the kernels that compute the state at the segment boundaries).
+struct SegmentPlan {
+  int n_seg;       // >= 1
+  int seg_blocks;  // 16-token blocks per segment
+};
+SegmentPlan plan_segments(int n_heads, int T, int requested);
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments);
+hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
+                                hipStream_t stream);
+// Boundary kernels (vla_segments.hip).  All buffers are device memory inside the caller's workspace.
+//   gram:      G[h][s] = sum over the tokens of segment s of k^ k^T, float64 [d][d]
+//   boundary:  seg_A[h][s] = inverse(inverse(A0[h]) + sum_{j<s} G[h][j]) rounded to float32
+//   combine:   seg_S[h][0] = S0[h];  seg_S[h][s+1] = seg_S[h][s] P[h][s] + Q[h][s]
+hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hipStream_t stream);
+hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* seg_A, hipStream_t stream);
+hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t stream);
 
 }  // namespace vla

@@ -64,16 +64,19 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   __shared__ __align__(16) float Lis[C * LT];
   __shared__ __align__(16) float wn2p[NW][C];
 
-  const int head = blockIdx.x;
+  // One workgroup per (head, time segment); with a single segment it walks the whole sequence.
+  const int head = blockIdx.x / a.n_seg;
+  const int seg = blockIdx.x - head * a.n_seg;
   const int tid = threadIdx.x;
   const int w = tid >> 6;
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
-  const int T = a.T;
+  const int tb = seg * a.seg_blocks * C;                                   // first token of the segment
+  const int T = min(a.T, tb + a.seg_blocks * C);                           // one past its last token
   const float eps = a.eps;
   const int col0 = SL * w;
-  const int nblk = (T + C - 1) / C;
+  const int nblk = (a.T + C - 1) / C;                                      // blocks of the whole sequence
 
   float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
   float* KH = wsh + off_kh(nblk, D);
@@ -82,7 +85,8 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
 
   f4 At[NB][NJ];
   {
-    const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* A0 = a.seg_A ? a.seg_A + static_cast<size_t>(blockIdx.x) * D * D
+                              : (a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr);
     const float diag = 1.0f / a.lambda0;
     const int arc = (4 * g) * D + col0 + c;
 #pragma unroll
@@ -100,7 +104,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
       }
   }
 
-  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const int srow = tid / TPR;
@@ -113,10 +117,10 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
     kpre.load(kh + koff);
     qpre.load(qh + koff);
   };
-  if (T > 0) prefetch(0);
+  if (tb < T) prefetch(tb);
 
-  int blk = 0;
-  for (int t0 = 0; t0 < T; t0 += C, ++blk) {
+  int blk = seg * a.seg_blocks;
+  for (int t0 = tb; t0 < T; t0 += C, ++blk) {
     // ---- stage K^ (LDS and workspace) and Q (LDS)
     {
       float kx[EPT];
@@ -274,7 +278,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
     }
   }
 
-  if (a.A_T) {
+  if (a.A_T && seg == a.n_seg - 1) {
     float* AT = a.A_T + static_cast<size_t>(head) * D * D;
     int g2 = g;
     asm volatile("" : "+v"(g2));
@@ -346,30 +350,50 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
 
 // ------------------------------------------------------------------------------------------ phase 2
 // One wave per (head, 16-row slab of S).  st[b][r] = S[row0 + c][16b + 4g + r].
-template <int D, int DEPTH, typename IO>
+//
+// MAP = false: the recurrence proper for one (head, time segment, slab): reads q, writes o.
+// MAP = true:  the affine map S_end = S_start P + Q of one segment, for the time-parallel mode.  Rows of S
+//              are independent, so row i of P is what row i of the identity evolves into with v = 0, and Q is
+//              what a zero state evolves into with the real v: 2 d/16 slabs per (head, segment), nothing
+//              read from q and nothing written to o; the end states go to seg_PQ.
+template <int D, int DEPTH, typename IO, bool MAP>
 __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   constexpr int NB = D / 16;
   constexpr int NSLAB = D / 16;
-  const int head = blockIdx.x / NSLAB;
-  const int row0 = (blockIdx.x % NSLAB) * 16;
+  constexpr int SLABS = MAP ? 2 * NSLAB : NSLAB;
+  const int hs = blockIdx.x / SLABS;                 // head * n_seg + seg
+  const int slab_id = blockIdx.x - hs * SLABS;
+  const int head = hs / a.n_seg;
+  const int seg = hs - head * a.n_seg;
+  const bool p_run = MAP && slab_id >= NSLAB;        // identity rows, v = 0
+  const int row0 = (slab_id % NSLAB) * 16;
   const int lane = threadIdx.x;
   const int c = lane & 15;
   const int g = lane >> 4;
-  const int T = a.T;
-  const int nblk = (T + C - 1) / C;
+  const int nblk = (a.T + C - 1) / C;
+  const int bb = seg * a.seg_blocks;                 // block range of the segment
+  const int be = min(nblk, bb + a.seg_blocks);
+  const int T = min(a.T, be * C);
+  if (MAP && seg == a.n_seg - 1) return;                // nothing follows the last segment
 
   const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
   const float* KH = wsh;
   const float* WT = wsh + static_cast<size_t>(nblk) * C * D;
   const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
-  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
   f4 st[NB];
-  {
-    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+  if constexpr (MAP) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st[b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+  } else {
+    const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * D * D
+                              : (a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (S0) {
@@ -398,10 +422,10 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     for (int b = 0; b < NB; ++b) {
       o.ka[b] = *reinterpret_cast<const f4*>(kp + 16 * b);
       o.wa[b] = *reinterpret_cast<const f4*>(wp + 16 * b * C);
-      o.qa[b].load(qh + qrow + 16 * b + 4 * g);
+      if constexpr (!MAP) o.qa[b].load(qh + qrow + 16 * b + 4 * g);
     }
     o.za = *reinterpret_cast<const f4*>(sp + c * C + 4 * g);
-    o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + c * C + 4 * g);
+    if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + c * C + 4 * g);
     o.ncg = *reinterpret_cast<const f4*>(sp + 3 * C * C + 4 * g);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -415,26 +439,28 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     const bool qlive = t0 + c < T;
     f4 ft, ot = f4{0, 0, 0, 0};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) ft[r] = (t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
+    for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       float qx[4];
-      cur.qa[b].unpack(qx);
+      if constexpr (!MAP) cur.qa[b].unpack(qx);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         ft = mfma16(cur.ka[b][r], st[b][r], ft);
-        ot = mfma16(qlive ? qx[r] : 0.0f, st[b][r], ot);
+        if constexpr (!MAP) ot = mfma16(qlive ? qx[r] : 0.0f, st[b][r], ot);
       }
     }
     f4 et = f4{0, 0, 0, 0};
 #pragma unroll
     for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
+    if constexpr (!MAP) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
+      for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int t = t0 + 4 * g + r;
-      if (t < T) io_store(oh + static_cast<unsigned>(t * D + row0 + c), ot[r]);
+      for (int r = 0; r < 4; ++r) {
+        const int t = t0 + 4 * g + r;
+        if (t < T) io_store(oh + static_cast<unsigned>(t * D + row0 + c), ot[r]);
+      }
     }
     const f4 ce = et * cur.ncg;
 #pragma unroll
@@ -447,29 +473,35 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   // blocks ahead into rotating register sets (the loop is unrolled by DEPTH + 1 to keep them static).
   if constexpr (DEPTH == 2) {
     Ops o0, o1, o2;
-    if (nblk > 0) load_ops(0, o0);
-    if (nblk > 1) load_ops(1, o1);
-    for (int blk = 0; blk < nblk; blk += 3) {
-      if (blk + 2 < nblk) load_ops(blk + 2, o2);
+    if (bb < be) load_ops(bb, o0);
+    if (bb + 1 < be) load_ops(bb + 1, o1);
+    for (int blk = bb; blk < be; blk += 3) {
+      if (blk + 2 < be) load_ops(blk + 2, o2);
       compute(blk, o0);
-      if (blk + 3 < nblk) load_ops(blk + 3, o0);
-      if (blk + 1 < nblk) compute(blk + 1, o1);
-      if (blk + 4 < nblk) load_ops(blk + 4, o1);
-      if (blk + 2 < nblk) compute(blk + 2, o2);
+      if (blk + 3 < be) load_ops(blk + 3, o0);
+      if (blk + 1 < be) compute(blk + 1, o1);
+      if (blk + 4 < be) load_ops(blk + 4, o1);
+      if (blk + 2 < be) compute(blk + 2, o2);
     }
   } else {
     Ops o0, o1;
-    if (nblk > 0) load_ops(0, o0);
-    for (int blk = 0; blk < nblk; blk += 2) {
-      if (blk + 1 < nblk) load_ops(blk + 1, o1);
+    if (bb < be) load_ops(bb, o0);
+    for (int blk = bb; blk < be; blk += 2) {
+      if (blk + 1 < be) load_ops(blk + 1, o1);
       compute(blk, o0);
-      if (blk + 2 < nblk) load_ops(blk + 2, o0);
-      if (blk + 1 < nblk) compute(blk + 1, o1);
+      if (blk + 2 < be) load_ops(blk + 2, o0);
+      if (blk + 1 < be) compute(blk + 1, o1);
     }
   }
 
-  if (a.S_T) {
-    float* ST = a.S_T + static_cast<size_t>(head) * D * D;
+  float* out = nullptr;
+  if constexpr (MAP) {
+    out = a.seg_PQ + (static_cast<size_t>(hs) * 2 + (p_run ? 0 : 1)) * D * D;
+  } else if (a.S_T && seg == a.n_seg - 1) {
+    out = a.S_T + static_cast<size_t>(head) * D * D;
+  }
+  if (out) {
+    float* ST = out;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
       *reinterpret_cast<float4*>(ST + (row0 + c) * D + 16 * b + 4 * g) =
@@ -477,12 +509,14 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   }
 }
 
+// Phase 1, 1b and 2 over every (head, segment) of `a`.
 template <int D, int NW, typename IO>
-hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
+hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
-                                   dim3(a.n_heads), dim3(64 * NW), params, 0, stream);
+  const int hs = a.n_heads * a.n_seg;
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>), dim3(hs),
+                                   dim3(64 * NW), params, 0, stream);
   if (err != hipSuccess) return err;
   const int nblk = (a.T + C - 1) / C;
   const long long waves = static_cast<long long>(a.n_heads) * nblk;
@@ -496,8 +530,16 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
     if (err != hipSuccess) return err;
   }
   constexpr int kDepth = D <= 64 ? 2 : 1;  // register budget: three operand sets only fit up to d = 64
-  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO>),
-                         dim3(a.n_heads * (D / 16)), dim3(64), params, 0, stream);
+  if (a.n_seg > 1) {
+    // the state of S at the segment boundaries: per-segment affine maps, then their composition
+    err = hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, true>),
+                          dim3(hs * 2 * (D / 16)), dim3(64), params, 0, stream);
+    if (err != hipSuccess) return err;
+    err = launch_combine(a, D, const_cast<float*>(a.seg_S), stream);
+    if (err != hipSuccess) return err;
+  }
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, false>),
+                         dim3(hs * (D / 16)), dim3(64), params, 0, stream);
 }
 
 }  // namespace
@@ -507,14 +549,91 @@ size_t two_phase_workspace_bytes(int n_heads, int T, int d) {
   return static_cast<size_t>(n_heads) * head_stride(nblk, d) * sizeof(float);
 }
 
-hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+namespace {
+hipError_t dispatch_phases(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
   const bool bf = io_dtype == 1;
   switch (d) {
-    case 32: return bf ? launch<32, 1, uint16_t>(a, stream) : launch<32, 1, float>(a, stream);
-    case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
-    case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
+    case 32: return bf ? launch_phases<32, 1, uint16_t>(a, stream) : launch_phases<32, 1, float>(a, stream);
+    case 64: return bf ? launch_phases<64, 2, uint16_t>(a, stream) : launch_phases<64, 2, float>(a, stream);
+    case 128: return bf ? launch_phases<128, 4, uint16_t>(a, stream) : launch_phases<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;
   }
+}
+}  // namespace
+
+hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  ForwardArgs args = a;
+  args.n_seg = 1;
+  args.seg_blocks = (a.T + C - 1) / C;
+  args.seg_A = nullptr;
+  args.seg_S = nullptr;
+  args.seg_PQ = nullptr;
+  return dispatch_phases(args, d, io_dtype, stream);
+}
+
+// ---------------------------------------------------------------------------------- time-parallel mode
+// Segments are sized so that heads x segments fills the chip about twice over, but never shorter than 32
+// blocks (512 tokens): the map pass costs two extra sweeps of S whatever the segment count.
+SegmentPlan plan_segments(int n_heads, int T, int requested) {
+  const int nblk = (T + C - 1) / C;
+  int ns = requested;
+  if (ns <= 0) {
+    const int by_chip = 512 / (n_heads < 1 ? 1 : n_heads);
+    const int by_length = nblk / 32;
+    ns = by_chip < by_length ? by_chip : by_length;
+  }
+  if (ns > 256) ns = 256;
+  if (ns > nblk) ns = nblk;
+  if (ns < 1) ns = 1;
+  SegmentPlan p;
+  p.seg_blocks = nblk > 0 ? (nblk + ns - 1) / ns : 0;
+  p.n_seg = nblk > 0 ? (nblk + p.seg_blocks - 1) / p.seg_blocks : 1;  // no empty segment
+  return p;
+}
+
+namespace {
+// workspace of the time-parallel mode, in floats, after the two-phase region
+struct TpLayout {
+  size_t gram, seg_A, seg_PQ, seg_S, total;
+};
+TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
+  const int nblk = (T + C - 1) / C;
+  const size_t mats = static_cast<size_t>(n_heads) * n_seg * d * d;  // one d x d float matrix per (head, seg)
+  TpLayout l;
+  size_t off = static_cast<size_t>(n_heads) * head_stride(nblk, d);
+  off = (off + 3) & ~static_cast<size_t>(3);  // 16-byte alignment
+  l.gram = off;   off += 2 * mats;            // float64
+  l.seg_A = off;  off += mats;
+  l.seg_PQ = off; off += 2 * mats;
+  l.seg_S = off;  off += mats;
+  l.total = off;
+  return l;
+}
+}  // namespace
+
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments) {
+  const SegmentPlan p = plan_segments(n_heads, T, requested_segments);
+  if (p.n_seg <= 1) return two_phase_workspace_bytes(n_heads, T, d);
+  return tp_layout(n_heads, T, d, p.n_seg).total * sizeof(float);
+}
+
+hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
+                                hipStream_t stream) {
+  const SegmentPlan p = plan_segments(a.n_heads, a.T, requested_segments);
+  if (p.n_seg <= 1) return launch_two_phase(a, d, io_dtype, stream);
+  const TpLayout l = tp_layout(a.n_heads, a.T, d, p.n_seg);
+  ForwardArgs args = a;
+  args.n_seg = p.n_seg;
+  args.seg_blocks = p.seg_blocks;
+  double* G = reinterpret_cast<double*>(a.ws + l.gram);
+  args.seg_A = a.ws + l.seg_A;
+  args.seg_PQ = a.ws + l.seg_PQ;
+  args.seg_S = a.ws + l.seg_S;
+  hipError_t err = launch_gram(args, d, io_dtype, G, stream);
+  if (err != hipSuccess) return err;
+  err = launch_boundary(args, d, G, a.ws + l.seg_A, stream);
+  if (err != hipSuccess) return err;
+  return dispatch_phases(args, d, io_dtype, stream);
 }
 
 }  // namespace vla

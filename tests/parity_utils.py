@@ -29,7 +29,8 @@ def to_np(t):
     return t.detach().cpu().numpy()
 
 
-def gpu_forward(q, k, v, S0=None, A0=None, *, dtype="f32", lambda0=0.1, eps=1e-4, mode=None):
+def gpu_forward(q, k, v, S0=None, A0=None, *, dtype="f32", lambda0=0.1, eps=1e-4, mode=None,
+                segments=None):
     """numpy float32 inputs -> GPU call through the C ABI -> numpy outputs (o widened to f32)."""
     import torch
 
@@ -40,7 +41,8 @@ def gpu_forward(q, k, v, S0=None, A0=None, *, dtype="f32", lambda0=0.1, eps=1e-4
     tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(tdt) for x in (q, k, v))
     tS0 = None if S0 is None else torch.from_numpy(np.ascontiguousarray(S0, dtype=np.float32)).to(dev)
     tA0 = None if A0 is None else torch.from_numpy(np.ascontiguousarray(A0, dtype=np.float32)).to(dev)
-    o, S_T, A_T = vla.vla_forward(tq, tk, tv, tS0, tA0, lambda0=lambda0, eps=eps, mode=mode)
+    o, S_T, A_T = vla.vla_forward(tq, tk, tv, tS0, tA0, lambda0=lambda0, eps=eps, mode=mode,
+                                  segments=segments)
     torch.cuda.synchronize()
     return to_np(o), to_np(S_T), to_np(A_T)
 
@@ -53,12 +55,13 @@ def oracle_inputs(q, k, v, dtype):
 
 
 def check_parity(q, k, v, S0=None, A0=None, *, dtype="f32", lambda0=0.1, eps=1e-4, mode=None,
-                 tol=None):
+                 tol=None, segments=None):
     """Run both sides on the same inputs and assert the three outputs are within tolerance."""
     tol = TOL[dtype] if tol is None else tol
     qo, ko, vo = oracle_inputs(q, k, v, dtype)
     ref = oracle.forward(qo, ko, vo, S0, A0, lambda0=lambda0, eps=eps)
-    o, S_T, A_T = gpu_forward(qo, ko, vo, S0, A0, dtype=dtype, lambda0=lambda0, eps=eps, mode=mode)
+    o, S_T, A_T = gpu_forward(qo, ko, vo, S0, A0, dtype=dtype, lambda0=lambda0, eps=eps, mode=mode,
+                              segments=segments)
     errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(S_T, ref["S_T"], 2),
                 A=slab_rel_err(A_T, ref["A_T"], 2))
     assert np.isfinite(o).all() and np.isfinite(S_T).all() and np.isfinite(A_T).all()

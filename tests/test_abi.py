@@ -98,8 +98,35 @@ def test_workspace_query_and_mode_resolution():
     assert vla.vla_forward_workspace_bytes(0, 1, 8, 16, 16, vla.VLA_F32) == 0
     assert vla.resolve_mode(1, 1, 8, 16, 16, vla.VLA_F32, mode=vla.MODE_SCAN) == vla.MODE_SCAN
     assert vla.resolve_mode(1, 1, 8, 48, 48, vla.VLA_F32) == -1
-    m = vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16)
-    assert m in (vla.MODE_SCAN, vla.MODE_CHUNKED, vla.MODE_TWO_PHASE)
+    assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(1, 16, 512, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_SCAN
+
+
+def test_time_parallel_workspace_follows_the_segment_plan():
+    """Workspace = the two-phase region + per (head, segment) one float64 and four float32 d x d matrices
+    (Gram, A start, P, Q, S start); one segment needs nothing beyond the two-phase region."""
+    B, H, T, d = 1, 16, 8192, 64
+    two = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
+    nblk = T // 16
+    assert two == B * H * nblk * (2 * 16 * d + 784) * 4
+    tp = lambda s: vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16,
+                                                   mode=vla.MODE_TIME_PARALLEL, segments=s)
+    assert tp(1) == two
+    for s in (2, 8, 64):
+        assert tp(s) == two + B * H * s * d * d * 4 * 6
+    # 512 blocks in 100 segments: ceil(512/100) = 6 blocks each -> 86 non-empty segments
+    assert tp(100) == two + B * H * 86 * d * d * 4 * 6
+    # never more segments than blocks, never more than 256
+    assert vla.vla_forward_workspace_bytes(1, 1, 64, d, d, vla.VLA_F32, mode=vla.MODE_TIME_PARALLEL,
+                                           segments=99) == 4 * (2 * 16 * d + 784) * 4 + 4 * d * d * 24
+    big = vla.vla_forward_workspace_bytes(1, 1, 16 * 4096, d, d, vla.VLA_F32,
+                                          mode=vla.MODE_TIME_PARALLEL, segments=100000)
+    assert big == 4096 * (2 * 16 * d + 784) * 4 + 256 * d * d * 24
+    # the library's own choice: about 512 (head, segment) pairs, segments of at least 32 blocks
+    auto = tp(0)
+    assert auto == two + B * H * 16 * d * d * 24          # 512 blocks / 32 = 16 < 512 / 16 heads = 32
 
 
 def test_torch_front_end_refuses_cpu_tensors():

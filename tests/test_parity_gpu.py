@@ -20,13 +20,13 @@ def modes_for(d):
     import paper_2605_11196_amd as vla
 
     out = [vla.MODE_SCAN]
-    for m in (vla.MODE_CHUNKED, vla.MODE_TWO_PHASE):
+    for m in (vla.MODE_CHUNKED, vla.MODE_TWO_PHASE, vla.MODE_TIME_PARALLEL):
         if vla.resolve_mode(2, 2, 64, d, d, vla.VLA_F32, mode=m) == m:
             out.append(m)
     return out
 
 
-ALL_MODES = [1, 2, 3]
+ALL_MODES = [1, 2, 3, 4]
 
 
 def skip_unless_mode(d, mode, dtype="f32"):
@@ -95,13 +95,15 @@ def test_config4_long_context_bf16(T):
 
     c = C["long_context"]
     q, k, v = vla_inputs.device_gaussian(c["B"], c["H"], T, c["d"], c["seed"], c["std"], torch.bfloat16)
-    o, S_T, A_T = vla.vla_forward(q, k, v, lambda0=c["lambda0"])
-    torch.cuda.synchronize()
     ref = oracle.forward(to_np(q), to_np(k), to_np(v), lambda0=c["lambda0"])
-    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
-                A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
-    print("config4", T, errs)
-    assert max(errs.values()) <= TOL["bf16"], errs
+    # AUTO (the time-parallel kernels here) and every block-form mode asked for by name
+    for mode in (None, vla.MODE_TIME_PARALLEL, vla.MODE_TWO_PHASE, vla.MODE_CHUNKED):
+        o, S_T, A_T = vla.vla_forward(q, k, v, lambda0=c["lambda0"], mode=mode)
+        torch.cuda.synchronize()
+        errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                    A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+        print("config4", T, "mode", mode, errs)
+        assert max(errs.values()) <= TOL["bf16"], (mode, errs)
 
 
 def test_config5_large_batch_bf16_sampled_heads():

@@ -1,0 +1,94 @@
+"""GPU parity of the time-parallel mode: segments of the sequence run concurrently from boundary states
+(A from the explicit inverse of Section 3.2 in float64, S from composed per-segment affine maps of
+eq. (s-update)); the result must match the sequential fp64 oracle to the same tolerance as every other mode.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import vla_inputs
+from parity_utils import TOL, check_parity, gpu_forward, slab_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TP = 4  # VLA_MODE_TIME_PARALLEL
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,T,segments", [
+    (64, 1000, 5),      # ragged: 63 blocks in segments of 13, the last one short, last block 8 tokens
+    (32, 200, 256),     # more segments asked for than blocks: one block per segment
+    (128, 513, 2),      # second segment ends in a one-token block
+    (128, 300, 7),
+    (64, 4096, 0),      # the library's own choice (8 segments for 6 heads)
+    (32, 2048, 0),
+    (64, 16, 4),        # a single block: degenerates to one segment
+])
+def test_segments_match_the_sequential_oracle(d, T, segments, dtype):
+    q, k, v = vla_inputs.gaussian_qkv(2, 3, T, d, seed=900 + d + T)
+    errs, _, _ = check_parity(q, k, v, dtype=dtype, lambda0=0.1, mode=TP, segments=segments)
+    print(d, T, segments, dtype, errs)
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_given_initial_state_enters_the_boundary_inverse(d):
+    """A non-trivial symmetric positive definite A0 and a non-zero S0 (the state after T1 tokens, from
+    the oracle) must be carried through the boundary computation: A0 is inverted in float64 there."""
+    T, T1 = 700, 123
+    q, k, v = vla_inputs.gaussian_qkv(1, 4, T, d, seed=77 + d)
+    full = oracle.forward(q, k, v, lambda0=0.1)
+    head = oracle.forward(q[:, :, :T1], k[:, :, :T1], v[:, :, :T1], lambda0=0.1)
+    o, S_T, A_T = gpu_forward(q[:, :, T1:], k[:, :, T1:], v[:, :, T1:], head["S_T"], head["A_T"],
+                              mode=TP, segments=6)
+    errs = dict(o=slab_rel_err(o, full["o"][:, :, T1:], 2), S=slab_rel_err(S_T, full["S_T"], 2),
+                A=slab_rel_err(A_T, full["A_T"], 2))
+    assert max(errs.values()) <= TOL["f32"], errs
+
+
+def test_recall_workload_with_zero_and_repeated_directions():
+    """Mostly all-zero tokens and few distinct keys: the Gram sums are low-rank, so the boundary matrix
+    lambda0 I + G has many eigenvalues equal to lambda0."""
+    c = vla_inputs.CONFIGS["recall"]
+    q, k, v, _ = vla_inputs.recall_task(4, c["H"], c["T"], c["d"], c["seed"], c["n_pairs"])
+    check_parity(q, k, v, lambda0=c["lambda0"], mode=TP, segments=8)
+
+
+def test_segment_count_only_changes_rounding():
+    d, T = 64, 1536
+    q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=31)
+    ref = gpu_forward(q, k, v, mode=3)
+    for segments in (2, 3, 16, 96):
+        got = gpu_forward(q, k, v, mode=TP, segments=segments)
+        for x, y, nd in zip(got, ref, (2, 2, 2)):
+            assert slab_rel_err(x, y, nd) <= 2e-5, segments
+
+
+def test_workspace_and_option_checks():
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, T, d = 1, 2, 2048, 64
+    need_tp = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_F32, mode=TP, segments=4)
+    need_2p = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_F32, mode=vla.MODE_TWO_PHASE)
+    assert need_tp > need_2p > 0
+    # AUTO for few heads and a long sequence is this mode and asks for its workspace
+    assert vla.resolve_mode(B, H, T, d, d, vla.VLA_F32) == TP
+    assert vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_F32) >= need_2p
+    dev = torch.device("cuda:0")
+    q = torch.randn(B, H, T, d, device=dev)
+    o = torch.empty_like(q)
+    ws = torch.empty(need_tp, dtype=torch.uint8, device=dev)
+    args = (q.data_ptr(), q.data_ptr(), q.data_ptr(), 0, 0, o.data_ptr(), 0, 0, B, H, T, d, d, vla.VLA_F32)
+    # too small a workspace for an explicitly requested mode is an error, nothing is launched
+    rc = vla.vla_forward_raw(*args, mode=TP, segments=4, workspace=ws.data_ptr(), workspace_bytes=need_tp - 16)
+    assert vla.status_string(rc) == "VLA_ERR_WORKSPACE"
+    rc = vla.vla_forward_raw(*args, mode=TP, segments=4, workspace=ws.data_ptr(), workspace_bytes=need_tp)
+    assert rc == 0
+    # the options of Algorithm 1 break A_t = M_t^{-1} (refresh) or u = k^: refused
+    rc = vla.vla_forward_raw(*args, mode=TP, segments=4, workspace=ws.data_ptr(), workspace_bytes=need_tp,
+                             refresh_period=20)
+    assert vla.status_string(rc) == "VLA_ERR_UNSUPPORTED"
+    rc = vla.vla_forward_raw(*args, mode=TP, segments=-1, workspace=ws.data_ptr(), workspace_bytes=need_tp)
+    assert vla.status_string(rc) == "VLA_ERR_INVALID_ARG"
+    torch.cuda.synchronize()
