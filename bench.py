@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--B", type=int, default=None, help="batch override (experiments only)")
     ap.add_argument("--d", type=int, default=None, help="head size override (experiments only)")
     ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
+    ap.add_argument("--segments", type=int, default=None,
+                    help="time segments for the time-parallel mode (default: the library chooses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB -> 1 GiB elementwise copy kernel (calibration of the "
@@ -93,7 +95,8 @@ def main():
     S_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
     A_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
     mode = args.mode
-    need = vla.vla_forward_workspace_bytes(B, H, T, d, d, io, lambda0=c["lambda0"], mode=mode)
+    need = vla.vla_forward_workspace_bytes(B, H, T, d, d, io, lambda0=c["lambda0"], mode=mode,
+                                           segments=args.segments)
     ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
     resolved = vla.resolve_mode(B, H, T, d, d, io, mode=mode)
     stream = torch.cuda.current_stream(dev)
@@ -102,7 +105,7 @@ def main():
         rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(),
                                  S_T.data_ptr(), A_T.data_ptr(), B, H, T, d, d, io,
                                  lambda0=c["lambda0"], mode=mode, workspace=ws.data_ptr(),
-                                 workspace_bytes=need, stream=stream.cuda_stream)
+                                 workspace_bytes=need, stream=stream.cuda_stream, segments=args.segments)
         if rc != 0:
             raise RuntimeError(vla.status_string(rc))
 
@@ -138,7 +141,7 @@ def main():
     flops = 10.0 * d * d * head_tokens           # algorithmic flop per launch (5 d^2 FMA per head-token)
     io_bytes = (2 if dtype == "bf16" else 4) * 4 * d * head_tokens   # q,k,v read + o written
     achieved_tflops = flops / avg_launch_s / 1e12
-    mode_names = {1: "scan", 2: "chunked", 3: "two_phase"}
+    mode_names = {1: "scan", 2: "chunked", 3: "two_phase", 4: "time_parallel"}
     workload = (f"{args.workload}: B={B} H={H} T={T} d_h={d} {dtype} q/k/v/o, fp32 A and S, "
                 f"lambda0={c['lambda0']}")
     out = {
@@ -157,7 +160,7 @@ def main():
         "config": {"workload": workload, "io_dtype": dtype, "kernel_mode": mode_names.get(resolved, str(resolved)),
                    "global_batch": B, "heads": H, "seq_len": T, "d_h": d, "parallelism": "single-gpu"},
         "roofline": {
-            "bound": "mfma" if resolved in (2, 3) else "alu",
+            "bound": "mfma" if resolved in (2, 3, 4) else "alu",
             "achieved": achieved_tflops,
             "peak": PEAK_FP32_TFLOPS,
             "unit": "TFLOP/s",

@@ -78,8 +78,8 @@ size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_se
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream);
 // Boundary kernels (vla_segments.hip).  All buffers are device memory inside the caller's workspace.
-//   gram:      G[h][s] = sum over the tokens of segment s of k^ k^T, float64 [d][d]
-//   boundary:  seg_A[h][s] = inverse(inverse(A0[h]) + sum_{j<s} G[h][j]) rounded to float32
+//   gram:      G[h][s] = sum over the tokens of segments 0..s of k^ k^T, float64 [d][d]
+//   boundary:  seg_A[h][s] = inverse(inverse(A0[h]) + G[h][s-1]) rounded to float32
 //   combine:   seg_S[h][0] = S0[h];  seg_S[h][s+1] = seg_S[h][s] P[h][s] + Q[h][s]
 hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hipStream_t stream);
 hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* seg_A, hipStream_t stream);

@@ -17,30 +17,72 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <typename IO> __device__ __forceinline__ double widen64(IO x);
-template <> __device__ __forceinline__ double widen64<float>(float x) { return static_cast<double>(x); }
-template <> __device__ __forceinline__ double widen64<uint16_t>(uint16_t x) {
-  return static_cast<double>(bf16_to_f32(x));
-}
-
 // ------------------------------------------------------------------------------------------ Gram
-// One workgroup per (head, segment); the last segment's matrix is never needed.  Thread (ty, tx) of a 16 x 16
-// grid owns G[ty + 16 a][tx + 16 b]; tokens are normalised in float64 and staged through LDS 16 at a time.
+// Raw row fragment of EPT consecutive elements -> float64.
+template <typename IO, int EPT> struct RawFrag;
+template <int EPT> struct RawFrag<float, EPT> {
+  static_assert(EPT % 4 == 0, "16-byte pieces");
+  float4 v[EPT / 4];
+  __device__ __forceinline__ void load(const float* p) {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const float4*>(p + 4 * e);
+  }
+  __device__ __forceinline__ void widen(double (&x)[EPT]) const {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) {
+      x[4 * e] = v[e].x; x[4 * e + 1] = v[e].y; x[4 * e + 2] = v[e].z; x[4 * e + 3] = v[e].w;
+    }
+  }
+};
+template <int EPT> struct RawFrag<uint16_t, EPT> {
+  static_assert(EPT % 4 == 0, "8-byte pieces");
+  uint2 v[EPT / 4];
+  __device__ __forceinline__ void load(const uint16_t* p) {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const uint2*>(p + 4 * e);
+  }
+  __device__ __forceinline__ void widen(double (&x)[EPT]) const {
+#pragma unroll
+    for (int e = 0; e < EPT / 4; ++e) {
+      x[4 * e] = __uint_as_float(v[e].x << 16);     x[4 * e + 1] = __uint_as_float(v[e].x & 0xffff0000u);
+      x[4 * e + 2] = __uint_as_float(v[e].y << 16); x[4 * e + 3] = __uint_as_float(v[e].y & 0xffff0000u);
+    }
+  }
+};
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+// One workgroup (4 waves) per (head, segment); the last segment's matrix is never needed.  Tokens are
+// normalised in float64 and staged through LDS 32 at a time; the outer products run on the float64 matrix
+// cores (v_mfma_f64_16x16x4_f64: lane l supplies A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16] and
+// receives D[i = l / 16 + 4 r][j = l % 16] in element r), both operands being the same staged tile.  A wave
+// holds at most 16 result tiles: up to D = 64 every wave covers the whole matrix and the waves take the
+// tokens of a tile in turn (summed through LDS at the end); at D = 128 each wave owns two tile rows.
 template <int D, typename IO>
-__global__ void __launch_bounds__(kThreads) gram_kernel(ForwardArgs a, double* G) {
-  constexpr int NA = D / 16;
-  constexpr int TT = 16;          // tokens per tile
-  constexpr int LDK = D + 1;      // odd stride: the 16 partial-norm threads of a token hit different banks
-  constexpr int EPT = TT * D / kThreads;  // elements of the tile each thread stages
-  constexpr int TPR = D / EPT;            // threads per token row
-  static_assert(EPT >= 1 && TPR >= 1 && TPR <= 64 && (TPR & (TPR - 1)) == 0, "staging layout");
-  __shared__ double kt[TT * LDK];
+__global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double* G) {
+  constexpr int NTI = D / 16;                                // tiles per side
+  constexpr int TR = NTI * NTI <= 16 ? NTI : 16 / NTI;       // tile rows per wave
+  constexpr int RGW = NTI / TR;                              // waves across the rows
+  constexpr int NGW = (kThreads / 64) / RGW;                 // waves across the tokens
+  constexpr int TT = 32;                                     // tokens per tile
+  constexpr int KS = TT / 4;                                 // k-steps (4 tokens) per tile
+  constexpr int LDK = D + 16;                                // rows 32 banks apart: conflict-free operand reads
+  constexpr int EPT = TT * D / kThreads;                     // elements of the tile each thread stages
+  constexpr int TPR = D / EPT;                               // threads per token row (8)
+  static_assert(RGW * NGW * 64 == kThreads && KS % NGW == 0 && TPR == 8, "layout");
+  __shared__ double ktb[2][TT * LDK];   // double-buffered: one barrier per tile
+  __shared__ double red[NGW > 1 ? D * D : 1];
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
   if (seg == a.n_seg - 1) return;
   const int tid = threadIdx.x;
-  const int ty = tid >> 4, tx = tid & 15;
+  const int w = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int rgw = w % RGW;      // which tile rows
+  const int tgrp = w / RGW;     // which k-steps
   const int tb = seg * a.seg_blocks * C;
   const int te = min(a.T, tb + a.seg_blocks * C);
   const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
@@ -48,93 +90,172 @@ __global__ void __launch_bounds__(kThreads) gram_kernel(ForwardArgs a, double* G
   const int srow = tid / TPR;
   const int scol = (tid % TPR) * EPT;
 
-  double acc[NA][NA];
+  d4 acc[TR][NTI];
 #pragma unroll
-  for (int i = 0; i < NA; ++i)
+  for (int i = 0; i < TR; ++i)
 #pragma unroll
-    for (int j = 0; j < NA; ++j) acc[i][j] = 0.0;
+    for (int j = 0; j < NTI; ++j) acc[i][j] = d4{0, 0, 0, 0};
 
-  for (int t0 = tb; t0 < te; t0 += TT) {
-    // stage: k^ = k / max(||k||, eps) in float64; rows past the end are zero
-    {
-      const int t = t0 + srow;
-      double x[EPT];
-      double ss = 0.0;
+  // Fragments of the next PF tiles are kept in flight in raw form (a few registers each): with a thousand
+  // workgroups streaming at once the memory latency is several tiles' worth of work.
+  constexpr int PF = D >= 128 ? 2 : 4;   // what the register file allows next to 128 accumulator registers
+  RawFrag<IO, EPT> raw[PF];
+  auto fetch = [&](int t0, RawFrag<IO, EPT>& o) {
+    const int t = t0 + srow;
+    o.load(kh + static_cast<size_t>(t < te ? t : te - 1) * D + scol);
+  };
+  // stage: k^ = k / max(||k||, eps) in float64; rows past the end are zero.  1 / ||k|| is a float32
+  // reciprocal square root refined by one Newton step in float64 (relative error ~1e-14).
+  auto stage = [&](int t0, const RawFrag<IO, EPT>& o, double* kt) {
+    const int t = t0 + srow;
+    double x[EPT];
+    o.widen(x);
+    double ss = 0.0;
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        x[e] = t < te ? widen64<IO>(kh[static_cast<size_t>(t) * D + scol + e]) : 0.0;
-        ss = fma(x[e], x[e], ss);
-      }
-#pragma unroll
-      for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      const double rn = 1.0 / fmax(sqrt(ss), eps);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) kt[srow * LDK + scol + e] = x[e] * rn;
+    for (int e = 0; e < EPT; ++e) {
+      x[e] = t < te ? x[e] : 0.0;
+      ss = fma(x[e], x[e], ss);
     }
-    __syncthreads();
-#pragma unroll 4
-    for (int tt = 0; tt < TT; ++tt) {
-      double ri[NA], cj[NA];
 #pragma unroll
-      for (int i = 0; i < NA; ++i) {
-        ri[i] = kt[tt * LDK + ty + 16 * i];
-        cj[i] = kt[tt * LDK + tx + 16 * i];
+    for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    const double y = static_cast<double>(__builtin_amdgcn_rsqf(static_cast<float>(ss)));
+    const double yn = y * fma(-0.5 * ss * y, y, 1.5);
+    const double rn = ss > eps * eps ? yn : 1.0 / eps;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) kt[srow * LDK + scol + e] = x[e] * rn;
+  };
+  auto products = [&](const double* kt) {
+#pragma unroll
+    for (int kk = tgrp; kk < KS; kk += NGW) {
+      const double* row = &kt[(4 * kk + g) * LDK + c];
+      double bv[NTI];
+#pragma unroll
+      for (int j = 0; j < NTI; ++j) bv[j] = row[16 * j];
+#pragma unroll
+      for (int i = 0; i < TR; ++i) {
+        const double av = RGW == 1 ? bv[i] : row[16 * (rgw * TR + i)];
+#pragma unroll
+        for (int j = 0; j < NTI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[j], acc[i][j], 0, 0, 0);
       }
-#pragma unroll
-      for (int i = 0; i < NA; ++i)
-#pragma unroll
-        for (int j = 0; j < NA; ++j) acc[i][j] = fma(ri[i], cj[j], acc[i][j]);
     }
-    __syncthreads();
+  };
+#pragma unroll
+  for (int u = 0; u < PF; ++u)
+    if (tb + u * TT < te) fetch(tb + u * TT, raw[u]);
+  for (int t0 = tb; t0 < te; t0 += PF * TT) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int tu = t0 + u * TT;
+      if (tu < te) {   // uniform over the workgroup
+        double* kt = ktb[u & 1];
+        stage(tu, raw[u], kt);
+        // the buffer written here was last read two tiles ago, and every wave has passed the barrier of the
+        // tile in between since then
+        __syncthreads();
+        if (tu + PF * TT < te) fetch(tu + PF * TT, raw[u]);
+        products(kt);
+      }
+    }
   }
 
+  // element r of tile (i, j) is G[16 (rgw TR + i) + g + 4 r][16 j + c]
   double* Gh = G + static_cast<size_t>(blockIdx.x) * D * D;
+  if constexpr (NGW == 1) {
 #pragma unroll
-  for (int i = 0; i < NA; ++i)
+    for (int i = 0; i < TR; ++i)
 #pragma unroll
-    for (int j = 0; j < NA; ++j) Gh[(ty + 16 * i) * D + tx + 16 * j] = acc[i][j];
+      for (int j = 0; j < NTI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Gh[(16 * (rgw * TR + i) + g + 4 * r) * D + 16 * j + c] = acc[i][j][r];
+  } else {
+    for (int gi = 0; gi < NGW; ++gi) {
+      if (tgrp == gi) {
+#pragma unroll
+        for (int i = 0; i < TR; ++i)
+#pragma unroll
+          for (int j = 0; j < NTI; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int o = (16 * (rgw * TR + i) + g + 4 * r) * D + 16 * j + c;
+              red[o] = gi == 0 ? acc[i][j][r] : red[o] + acc[i][j][r];
+            }
+      }
+      __syncthreads();
+    }
+    for (int o = tid; o < D * D; o += kThreads) Gh[o] = red[o];
+  }
+}
+
+// In-place inclusive prefix sum of the Gram matrices over the segments of a head, one thread per element:
+// afterwards G[h][s] = sum over segments 0..s.
+__global__ void __launch_bounds__(kThreads) gram_prefix_kernel(double* G, int n_heads, int n_seg, int dd) {
+  const long long e = static_cast<long long>(blockIdx.x) * kThreads + threadIdx.x;
+  if (e >= static_cast<long long>(n_heads) * dd) return;
+  const int head = static_cast<int>(e / dd);
+  double* p = G + (static_cast<size_t>(head) * n_seg) * dd + (e - static_cast<long long>(head) * dd);
+  double run = 0.0;
+#pragma unroll 8
+  for (int s = 0; s + 1 < n_seg; ++s) {
+    run += p[static_cast<size_t>(s) * dd];
+    p[static_cast<size_t>(s) * dd] = run;
+  }
 }
 
 // ------------------------------------------------------------------------------------------ boundary
-// In-place Gauss-Jordan inverse of the symmetric positive definite D x D matrix M held in LDS with row
-// stride LDM (no pivoting needed for such a matrix).  All kThreads threads call it; ends with a barrier.
-template <int D, int LDM>
-__device__ void invert_spd(double* M, double* colp, double* rowp) {
-  constexpr int RG = kThreads / D;   // rows handled concurrently
-  const int j = threadIdx.x % D;
-  const int rg = threadIdx.x / D;
-  for (int p = 0; p < D; ++p) {
-    __syncthreads();
-    const double piv = 1.0 / M[p * LDM + p];
-    if (threadIdx.x < D) {
-      colp[threadIdx.x] = M[threadIdx.x * LDM + p];
-      rowp[threadIdx.x] = M[p * LDM + threadIdx.x] * piv;
-    }
-    __syncthreads();
-    const double rj = rowp[j];
-    for (int i = rg; i < D; i += RG) {
-      double val;
-      if (i == p) {
-        val = (j == p) ? piv : rj;
-      } else if (j == p) {
-        val = -colp[i] * piv;
-      } else {
-        val = fma(-colp[i], rj, M[i * LDM + j]);
+// Gauss-Jordan inverse, in place, of a symmetric positive definite D x D matrix spread over the workgroup's
+// registers (no pivoting needed for such a matrix): thread (rg, j) holds m[n] = M[rg + RG n][j].
+//
+// Step p, with d = M[p][p]: replace column p by the unit vector e_p, then M <- M - c r^T with
+//   c_i = M[i][p] (i != p), c_p = d - 1;   r_j = M[p][j] / d (j != p), r_p = 1 / d
+// which is the usual in-place sweep (M[i][j] - M[i][p] M[p][j] / d off the pivot row and column, -M[i][p] / d in
+// column p, M[p][j] / d in row p, 1 / d at the pivot) written so that every element takes the same fused
+// multiply-add.  The pivot row is not fetched at all: after p steps the not yet eliminated part of M is a
+// Schur complement (symmetric) and the eliminated part of row p is minus the transposed column, so
+// M[p][j] = M[j][p] for j > p and -M[j][p] for j < p.  Only column p goes through LDS, double-buffered: one
+// barrier per step.
+template <int D>
+struct SpdInverse {
+  static constexpr int RG = kThreads / D;  // row groups
+  static constexpr int NR = D / RG;        // rows per thread
+  double* colp;                            // LDS [2][D + 1]: c, a thread's NR rows contiguous; then d
+  __device__ __forceinline__ void run(double (&m)[NR]) const {
+    const int j = threadIdx.x % D;
+    const int rg = threadIdx.x / D;
+    const int jslot = (j % RG) * NR + j / RG;   // where c_j sits
+    for (int p = 0; p < D; ++p) {
+      double* cp = colp + (p & 1) * (D + 1);
+      if (j == p) {
+        const int pn = p / RG;
+        const bool own_row = rg == p % RG;
+#pragma unroll
+        for (int n = 0; n < NR; ++n) {
+          const bool pivot = own_row && n == pn;
+          if (pivot) cp[D] = m[n];
+          cp[rg * NR + n] = pivot ? m[n] - 1.0 : m[n];
+          m[n] = pivot ? 1.0 : 0.0;
+        }
       }
-      M[i * LDM + j] = val;
+      __syncthreads();
+      const double piv = 1.0 / cp[D];
+      const double cj = cp[jslot];
+      const double rj = (j == p) ? piv : (j > p ? cj : -cj) * piv;
+#pragma unroll
+      for (int n = 0; n < NR; ++n) {
+        m[n] = fma(-cp[rg * NR + n], rj, m[n]);
+        if (n % 8 == 7) asm volatile("" ::: "memory");   // keep at most 8 LDS reads in flight (registers)
+      }
     }
   }
-  __syncthreads();
-}
+};
 
-// One workgroup per (head, segment): seg_A = inverse(inverse(A0) + sum of the Gram matrices before it).
+// One workgroup per (head, segment): seg_A = inverse(inverse(A0) + sum of the Gram matrices before it),
+// G holding the prefix sums.
 template <int D>
 __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const double* G, float* seg_A) {
-  constexpr int LDM = D + 1;
   constexpr int RG = kThreads / D;
-  __shared__ double M[D * LDM];
-  __shared__ double colp[D];
-  __shared__ double rowp[D];
+  constexpr int NR = D / RG;
+  __shared__ __align__(16) double colp[2 * (D + 1)];
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
@@ -148,69 +269,109 @@ __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const
     for (int i = rg; i < D; i += RG) out[i * D + j] = A0 ? A0[i * D + j] : (i == j ? diag : 0.0f);
     return;
   }
+  const SpdInverse<D> inv{colp};
+  double m[NR];
   if (A0) {
-    for (int i = rg; i < D; i += RG)
-      M[i * LDM + j] = 0.5 * (static_cast<double>(A0[i * D + j]) + static_cast<double>(A0[j * D + i]));
-    invert_spd<D, LDM>(M, colp, rowp);
+#pragma unroll
+    for (int n = 0; n < NR; ++n) {
+      const int i = rg + RG * n;
+      m[n] = 0.5 * (static_cast<double>(A0[i * D + j]) + static_cast<double>(A0[j * D + i]));
+    }
+    inv.run(m);
+    __syncthreads();   // the pivot buffers are reused by the second inversion
   } else {
-    for (int i = rg; i < D; i += RG) M[i * LDM + j] = (i == j) ? 1.0 / static_cast<double>(diag) : 0.0;
+#pragma unroll
+    for (int n = 0; n < NR; ++n) m[n] = (rg + RG * n == j) ? 1.0 / static_cast<double>(diag) : 0.0;
   }
-  // every thread touches only its own elements here, so no barrier is needed before the sum
-  const double* Gh = G + static_cast<size_t>(head) * a.n_seg * D * D;
-  for (int i = rg; i < D; i += RG) {
-    double sum = M[i * LDM + j];
-    for (int s = 0; s < seg; ++s) sum += Gh[static_cast<size_t>(s) * D * D + i * D + j];
-    M[i * LDM + j] = sum;
+  // G holds inclusive prefix sums: G[head][seg - 1] covers every token before this segment
+  const double* Gh = G + (static_cast<size_t>(blockIdx.x) - 1) * D * D;
+#pragma unroll
+  for (int n = 0; n < NR; ++n) m[n] += Gh[(rg + RG * n) * D + j];
+  inv.run(m);
+  // The inverse of a symmetric matrix is symmetric up to rounding; store the lower triangle's values on both
+  // sides so that the float32 matrix the recurrence starts from is exactly symmetric.
+#pragma unroll
+  for (int n = 0; n < NR; ++n) {
+    const int i = rg + RG * n;
+    const float v = static_cast<float>(m[n]);
+    if (i >= j) {
+      out[i * D + j] = v;
+      out[j * D + i] = v;
+    }
   }
-  invert_spd<D, LDM>(M, colp, rowp);
-  for (int i = rg; i < D; i += RG) out[i * D + j] = static_cast<float>(0.5 * (M[i * LDM + j] + M[j * LDM + i]));
 }
 
 // ------------------------------------------------------------------------------------------ combine
-// One wave per (head, 16-row slab of S): x <- x P_s + Q_s for s = 0 .. n_seg-2, every intermediate written
-// out as the start state of segment s+1.  x is held as accumulator tiles, xt[b][r] = S[row0 + c][16b + 4g + r],
-// the layout the S-rows kernel loads its start state in; the contraction index is taken in the order
-// k = 16b + 4g + r so that a tile feeds straight back as the MFMA B operand.
+// x <- x P_s + Q_s for s = 0 .. n_seg-2, every intermediate written out as the start state of segment s+1.
+// One workgroup per (head, 16-row slab of S), one wave per 16-column slice of the result: each wave keeps the
+// whole slab x as accumulator tiles, xt[b][r] = S[row0 + c][16b + 4g + r] (the layout the S-rows kernel loads
+// its start state in; the contraction index is taken in the order k = 16b + 4g + r so that a tile feeds
+// straight back as the MFMA B operand), computes its own slice of x P + Q and hands it to the other waves
+// through LDS.  The chain is sequential in s and short per step, so the operands of the next three
+// segments are kept in flight in rotating register sets.
 template <int D>
-__global__ void __launch_bounds__(64) combine_kernel(ForwardArgs a, float* seg_S) {
+__global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, float* seg_S) {
   constexpr int NB = D / 16;
+  constexpr int LDX = D + 4;
+  constexpr int LA = 3;   // segments of lookahead
+  __shared__ __align__(16) float xs[2][16 * LDX];
   const int head = blockIdx.x / NB;
   const int row0 = (blockIdx.x - head * NB) * 16;
-  const int lane = threadIdx.x;
+  const int jb = threadIdx.x >> 6;    // column slice of this wave
+  const int lane = threadIdx.x & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
   const size_t hbase = static_cast<size_t>(head) * a.n_seg;
   const int ro = (row0 + c) * D + 4 * g;   // this lane's float4 inside a d x d matrix, plus 16 b
+  const int n = a.n_seg - 1;               // steps
+
+  struct Seg {
+    float pa[NB][4];   // P[16b + 4g + r][16 jb + c]
+    f4 q;              // Q[row0 + c][16 jb + 4g ..]
+  };
+  auto load = [&](int s, Seg& o) {
+    const float* P = a.seg_PQ + (hbase + s) * 2 * D * D;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o.pa[b][r] = P[(16 * b + 4 * g + r) * D + 16 * jb + c];
+    o.q = *reinterpret_cast<const f4*>(P + D * D + ro + 16 * jb);
+  };
 
   f4 xt[NB];
   {
     const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
-    float* dst = seg_S + hbase * D * D;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      xt[b] = S0 ? *reinterpret_cast<const f4*>(S0 + ro + 16 * b) : f4{0, 0, 0, 0};
-      *reinterpret_cast<f4*>(dst + ro + 16 * b) = xt[b];
-    }
+    for (int b = 0; b < NB; ++b) xt[b] = S0 ? *reinterpret_cast<const f4*>(S0 + ro + 16 * b) : f4{0, 0, 0, 0};
+    const f4 mine = S0 ? *reinterpret_cast<const f4*>(S0 + ro + 16 * jb) : f4{0, 0, 0, 0};
+    *reinterpret_cast<f4*>(seg_S + hbase * D * D + ro + 16 * jb) = mine;
   }
-  for (int s = 0; s + 1 < a.n_seg; ++s) {
-    const float* P = a.seg_PQ + (hbase + s) * 2 * D * D;
-    const float* Q = P + D * D;
-    f4 nx[NB];
-#pragma unroll
-    for (int jb = 0; jb < NB; ++jb) nx[jb] = *reinterpret_cast<const f4*>(Q + ro + 16 * jb);
+
+  auto step = [&](int s, const Seg& o) {
+    f4 nx = o.q;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float* prow = P + (16 * b + 4 * g + r) * D + c;   // P[k][16 jb + c]
+      for (int r = 0; r < 4; ++r) nx = mfma16(o.pa[b][r], xt[b][r], nx);
+    *reinterpret_cast<f4*>(seg_S + (hbase + s + 1) * D * D + ro + 16 * jb) = nx;
+    float* x = xs[s & 1];
+    *reinterpret_cast<f4*>(&x[c * LDX + 16 * jb + 4 * g]) = nx;
+    __syncthreads();
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) nx[jb] = mfma16(prow[16 * jb], xt[b][r], nx[jb]);
+    for (int b = 0; b < NB; ++b) xt[b] = lds4(&x[c * LDX + 16 * b + 4 * g]);
+  };
+
+  Seg buf[LA + 1];
+#pragma unroll
+  for (int u = 0; u < LA; ++u)
+    if (u < n) load(u, buf[u]);
+  for (int s = 0; s < n; s += LA + 1) {
+#pragma unroll
+    for (int u = 0; u <= LA; ++u) {
+      if (s + u < n) {   // uniform over the workgroup
+        if (s + u + LA < n) load(s + u + LA, buf[(u + LA) % (LA + 1)]);
+        step(s + u, buf[u]);
       }
-    float* dst = seg_S + (hbase + s + 1) * D * D;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      xt[b] = nx[b];
-      *reinterpret_cast<f4*>(dst + ro + 16 * b) = xt[b];
     }
   }
 }
@@ -226,15 +387,22 @@ template <int D, typename IO>
 hipError_t launch_gram_d(const ForwardArgs& a, double* G, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args, &G};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&gram_kernel<D, IO>), dim3(a.n_heads * a.n_seg),
-                         dim3(kThreads), params, 0, stream);
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&gram_kernel<D, IO>),
+                                   dim3(a.n_heads * a.n_seg), dim3(kThreads), params, 0, stream);
+  if (err != hipSuccess) return err;
+  int nh = a.n_heads, ns = a.n_seg, dd = D * D;
+  void* p2[] = {&G, &nh, &ns, &dd};
+  const long long elems = static_cast<long long>(nh) * dd;
+  return hipLaunchKernel(reinterpret_cast<const void*>(&gram_prefix_kernel),
+                         dim3(static_cast<unsigned>((elems + kThreads - 1) / kThreads)), dim3(kThreads), p2, 0,
+                         stream);
 }
 template <int D>
 hipError_t launch_combine_d(const ForwardArgs& a, float* seg_S, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args, &seg_S};
   return hipLaunchKernel(reinterpret_cast<const void*>(&combine_kernel<D>), dim3(a.n_heads * (D / 16)),
-                         dim3(64), params, 0, stream);
+                         dim3(64 * (D / 16)), params, 0, stream);
 }
 
 }  // namespace

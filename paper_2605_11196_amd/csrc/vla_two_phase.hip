@@ -15,6 +15,8 @@
 //                              global memory in MFMA operand layout, no LDS and no barriers
 #include "vla_mfma_util.h"
 
+#include <type_traits>
+
 namespace vla {
 namespace {
 
@@ -349,24 +351,34 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
 }
 
 // ------------------------------------------------------------------------------------------ phase 2
-// One wave per (head, 16-row slab of S).  st[b][r] = S[row0 + c][16b + 4g + r].
+// One wave per (head, time segment, group of RS 16-row slabs of S).  st[s][b][r] = S[row(s) + c][16b + 4g + r].
+// The operands of a block (K^, W, Z, -NQ^T, -c, q) are the same for every row of S, so a wave that holds
+// RS slabs reads them once for all of them: RS = 1 gives the most waves (few heads, latency bound), larger
+// RS divides the memory traffic when there are enough (head, segment) pairs to fill the chip anyway.
 //
-// MAP = false: the recurrence proper for one (head, time segment, slab): reads q, writes o.
+// MAP = false: the recurrence proper: reads q, writes o.
 // MAP = true:  the affine map S_end = S_start P + Q of one segment, for the time-parallel mode.  Rows of S
 //              are independent, so row i of P is what row i of the identity evolves into with v = 0, and Q is
-//              what a zero state evolves into with the real v: 2 d/16 slabs per (head, segment), nothing
-//              read from q and nothing written to o; the end states go to seg_PQ.
-template <int D, int DEPTH, typename IO, bool MAP>
+//              what a zero state evolves into with the real v: twice the row groups per (head, segment),
+//              nothing read from q and nothing written to o; the end states go to seg_PQ.
+//
+// Workgroup ids are dealt round-robin over the 8 XCDs, each with its own L2; the id is decoded so that all
+// waves of one (head, segment) sit on the same XCD and share the operands they all read through its L2.
+template <int D, int DEPTH, typename IO, bool MAP, int RS>
 __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   constexpr int NB = D / 16;
-  constexpr int NSLAB = D / 16;
-  constexpr int SLABS = MAP ? 2 * NSLAB : NSLAB;
-  const int hs = blockIdx.x / SLABS;                 // head * n_seg + seg
-  const int slab_id = blockIdx.x - hs * SLABS;
+  constexpr int GROUPS = (D / 16) / RS;              // row groups per run
+  constexpr int WPH = MAP ? 2 * GROUPS : GROUPS;     // waves per (head, segment)
+  static_assert((D / 16) % RS == 0, "row groups");
+  const int xcd = blockIdx.x & 7;
+  const int rest = blockIdx.x >> 3;
+  const int hs = (rest / WPH) * 8 + xcd;             // head * n_seg + seg
+  const int grp = rest % WPH;
+  if (hs >= a.n_heads * a.n_seg) return;
   const int head = hs / a.n_seg;
   const int seg = hs - head * a.n_seg;
-  const bool p_run = MAP && slab_id >= NSLAB;        // identity rows, v = 0
-  const int row0 = (slab_id % NSLAB) * 16;
+  const bool p_run = MAP && grp >= GROUPS;           // identity rows, v = 0
+  const int row0 = (grp % GROUPS) * RS * 16;
   const int lane = threadIdx.x;
   const int c = lane & 15;
   const int g = lane >> 4;
@@ -374,7 +386,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   const int bb = seg * a.seg_blocks;                 // block range of the segment
   const int be = min(nblk, bb + a.seg_blocks);
   const int T = min(a.T, be * C);
-  if (MAP && seg == a.n_seg - 1) return;                // nothing follows the last segment
+  if (MAP && seg == a.n_seg - 1) return;             // nothing follows the last segment
 
   const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
   const float* KH = wsh;
@@ -385,24 +397,30 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
-  f4 st[NB];
+  f4 st[RS][NB];
   if constexpr (MAP) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int s = 0; s < RS; ++s)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st[b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          st[s][b][r] = (p_run && row0 + 16 * s + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
   } else {
     const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * D * D
                               : (a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr);
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      if (S0) {
-        const float4 x = *reinterpret_cast<const float4*>(S0 + (row0 + c) * D + 16 * b + 4 * g);
-        st[b] = f4{x.x, x.y, x.z, x.w};
-      } else {
-        st[b] = f4{0, 0, 0, 0};
+    for (int s = 0; s < RS; ++s)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        if (S0) {
+          const float4 x =
+              *reinterpret_cast<const float4*>(S0 + (row0 + 16 * s + c) * D + 16 * b + 4 * g);
+          st[s][b] = f4{x.x, x.y, x.z, x.w};
+        } else {
+          st[s][b] = f4{0, 0, 0, 0};
+        }
       }
-    }
   }
 
   // operands of one block, in MFMA operand layout, straight from global memory
@@ -410,67 +428,88 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     f4 ka[NB], wa[NB];
     Raw4<IO> qa[NB];
     f4 za, nqa, ncg;
-    IO v[4];
+    IO v[RS][4];
   };
+  // Addresses are a per-block uniform base (scalar registers) plus lane-constant 32-bit offsets, so that a
+  // load costs no vector address arithmetic; only the ragged last block clamps its token rows.
+  const unsigned ko = static_cast<unsigned>(c * D + 4 * g);   // K^ row c; also q row c (elements)
+  const unsigned wo = static_cast<unsigned>(c * C + 4 * g);   // W row c of a 16-column slice; Z / NQ row c
+  const unsigned vo = static_cast<unsigned>(4 * g * D + row0 + c);  // v and o: token 4g, column row0 + c
   auto load_ops = [&](int blk, Ops& o) {
-    const int t = blk * C + c;
-    const unsigned qrow = static_cast<unsigned>((t < T ? t : T - 1) * D);
-    const float* kp = KH + static_cast<size_t>(blk * C + c) * D + 4 * g;
-    const float* wp = WT + static_cast<size_t>(blk) * D * C + c * C + 4 * g;
+    const float* kb = KH + static_cast<size_t>(blk) * (C * D);
+    const float* wb = WT + static_cast<size_t>(blk) * (D * C);
     const float* sp = SMp + static_cast<size_t>(blk) * SMB;
+    const IO* qb = qh + static_cast<size_t>(blk) * (C * D);
+    const IO* vb = vh + static_cast<size_t>(blk) * (C * D);
+    const int lim = T - 1 - blk * C;                          // last live token row of this block
+    const unsigned qo = static_cast<unsigned>(min(c, lim) * D + 4 * g);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      o.ka[b] = *reinterpret_cast<const f4*>(kp + 16 * b);
-      o.wa[b] = *reinterpret_cast<const f4*>(wp + 16 * b * C);
-      if constexpr (!MAP) o.qa[b].load(qh + qrow + 16 * b + 4 * g);
+      o.ka[b] = *reinterpret_cast<const f4*>(kb + ko + 16 * b);
+      o.wa[b] = *reinterpret_cast<const f4*>(wb + wo + 16 * b * C);
+      if constexpr (!MAP) o.qa[b].load(qb + qo + 16 * b);
     }
-    o.za = *reinterpret_cast<const f4*>(sp + c * C + 4 * g);
-    if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + c * C + 4 * g);
+    o.za = *reinterpret_cast<const f4*>(sp + wo);
+    if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + wo);
     o.ncg = *reinterpret_cast<const f4*>(sp + 3 * C * C + 4 * g);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int tv = blk * C + 4 * g + r;
-      o.v[r] = vh[static_cast<unsigned>((tv < T ? tv : T - 1) * D + row0 + c)];
+      const unsigned vr = static_cast<unsigned>(min(4 * g + r, lim) * D + row0 + c);
+#pragma unroll
+      for (int s = 0; s < RS; ++s) o.v[s][r] = vb[vr + 16 * s];
     }
   };
 
   auto compute = [&](int blk, const Ops& cur) {
     const int t0 = blk * C;
-    const bool qlive = t0 + c < T;
-    f4 ft, ot = f4{0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float qx[4];
-      if constexpr (!MAP) cur.qa[b].unpack(qx);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        ft = mfma16(cur.ka[b][r], st[b][r], ft);
-        if constexpr (!MAP) ot = mfma16(qlive ? qx[r] : 0.0f, st[b][r], ot);
-      }
-    }
-    f4 et = f4{0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
+    IO* ob = oh + static_cast<size_t>(blk) * (C * D);
+    // Rows of q past the end hold a copy of the last token (clamped loads); row t of the read-out depends on
+    // row t of q only, and those rows are never stored, so they need no masking.
+    float qx[NB][4];
     if constexpr (!MAP) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = t0 + 4 * g + r;
-        if (t < T) io_store(oh + static_cast<unsigned>(t * D + row0 + c), ot[r]);
-      }
+      for (int b = 0; b < NB; ++b) cur.qa[b].unpack(qx[b]);
     }
-    const f4 ce = et * cur.ncg;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int s = 0; s < RS; ++s) {
+      f4 ft, ot = f4{0, 0, 0, 0};
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st[b] = mfma16(cur.wa[b][r], ce[r], st[b]);
+      for (int r = 0; r < 4; ++r)
+        ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[s][r]) : 0.0f;
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          ft = mfma16(cur.ka[b][r], st[s][b][r], ft);
+          if constexpr (!MAP) ot = mfma16(qx[b][r], st[s][b][r], ot);
+        }
+      }
+      f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
+      if constexpr (!MAP) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
+        if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
+#pragma unroll
+          for (int r = 0; r < 4; ++r) io_store(ob + vo + r * D + 16 * s, ot[r]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (t0 + 4 * g + r < T) io_store(ob + vo + r * D + 16 * s, ot[r]);
+          }
+        }
+      }
+      const f4 ce = et * cur.ncg;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) st[s][b] = mfma16(cur.wa[b][r], ce[r], st[s][b]);
+    }
   };
 
-  // The wave is alone on its SIMD slot and bound by memory latency, so operands are fetched DEPTH
-  // blocks ahead into rotating register sets (the loop is unrolled by DEPTH + 1 to keep them static).
+  // Operands are fetched DEPTH blocks ahead into rotating register sets (the loop is unrolled by DEPTH + 1
+  // to keep them static).
   if constexpr (DEPTH == 2) {
     Ops o0, o1, o2;
     if (bb < be) load_ops(bb, o0);
@@ -501,12 +540,26 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     out = a.S_T + static_cast<size_t>(head) * D * D;
   }
   if (out) {
-    float* ST = out;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-      *reinterpret_cast<float4*>(ST + (row0 + c) * D + 16 * b + 4 * g) =
-          make_float4(st[b][0], st[b][1], st[b][2], st[b][3]);
+    for (int s = 0; s < RS; ++s)
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        *reinterpret_cast<float4*>(out + (row0 + 16 * s + c) * D + 16 * b + 4 * g) =
+            make_float4(st[s][b][0], st[s][b][1], st[s][b][2], st[s][b][3]);
   }
+}
+
+template <int D, typename IO, bool MAP, int RS>
+hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  // register budget: three operand sets only fit a single slab per wave up to d = 64
+  constexpr int kDepth = (RS == 1 && D <= 64) ? 2 : 1;
+  constexpr int kWph = (MAP ? 2 : 1) * (D / 16) / RS;
+  const int hs = a.n_heads * a.n_seg;
+  const unsigned grid = static_cast<unsigned>((hs + 7) / 8) * 8u * kWph;
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, MAP, RS>), dim3(grid),
+                         dim3(64), params, 0, stream);
 }
 
 // Phase 1, 1b and 2 over every (head, segment) of `a`.
@@ -529,17 +582,32 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
                           dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), p2, 0, stream);
     if (err != hipSuccess) return err;
   }
-  constexpr int kDepth = D <= 64 ? 2 : 1;  // register budget: three operand sets only fit up to d = 64
+  // Slabs of S per wave: as many as still leave two waves per SIMD (2048 on the chip) and fit the register
+  // file (every slab up to d = 64), else one, for the most waves.
+  constexpr int kSlabs = D / 16;
+  const int waves1 = hs * kSlabs;
+  int rs = 1;
+  if (D <= 64) {
+    while (rs < kSlabs && waves1 / (2 * rs) >= 2048) rs *= 2;
+  }
+  auto rows = [&](auto map_tag) -> hipError_t {
+    constexpr bool kMap = decltype(map_tag)::value;
+    if constexpr (D <= 64) {
+      if (rs == kSlabs && kSlabs > 1) return launch_s_rows<D, IO, kMap, kSlabs>(a, stream);
+      if constexpr (kSlabs >= 4) {
+        if (rs == 2) return launch_s_rows<D, IO, kMap, 2>(a, stream);
+      }
+    }
+    return launch_s_rows<D, IO, kMap, 1>(a, stream);
+  };
   if (a.n_seg > 1) {
     // the state of S at the segment boundaries: per-segment affine maps, then their composition
-    err = hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, true>),
-                          dim3(hs * 2 * (D / 16)), dim3(64), params, 0, stream);
+    err = rows(std::true_type{});
     if (err != hipSuccess) return err;
     err = launch_combine(a, D, const_cast<float*>(a.seg_S), stream);
     if (err != hipSuccess) return err;
   }
-  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, false>),
-                         dim3(hs * (D / 16)), dim3(64), params, 0, stream);
+  return rows(std::false_type{});
 }
 
 }  // namespace
@@ -572,13 +640,13 @@ hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream
 }
 
 // ---------------------------------------------------------------------------------- time-parallel mode
-// Segments are sized so that heads x segments fills the chip about twice over, but never shorter than 32
+// Segments are sized so that heads x segments gives every compute unit about four workgroups, but never shorter than 32
 // blocks (512 tokens): the map pass costs two extra sweeps of S whatever the segment count.
 SegmentPlan plan_segments(int n_heads, int T, int requested) {
   const int nblk = (T + C - 1) / C;
   int ns = requested;
   if (ns <= 0) {
-    const int by_chip = 512 / (n_heads < 1 ? 1 : n_heads);
+    const int by_chip = 1024 / (n_heads < 1 ? 1 : n_heads);
     const int by_length = nblk / 32;
     ns = by_chip < by_length ? by_chip : by_length;
   }
