@@ -218,7 +218,7 @@ template <int D>
 struct SpdInverse {
   static constexpr int RG = kThreads / D;  // row groups
   static constexpr int NR = D / RG;        // rows per thread
-  double* colp;                            // LDS [2][D + 1]: c, a thread's NR rows contiguous; then d
+  double* colp;                            // LDS [2][D + 1]: c, a thread's NR rows contiguous; then 1 / d
   __device__ __forceinline__ void run(double (&m)[NR]) const {
     const int j = threadIdx.x % D;
     const int rg = threadIdx.x / D;
@@ -231,13 +231,13 @@ struct SpdInverse {
 #pragma unroll
         for (int n = 0; n < NR; ++n) {
           const bool pivot = own_row && n == pn;
-          if (pivot) cp[D] = m[n];
+          if (pivot) cp[D] = 1.0 / m[n];   // the one division of the step
           cp[rg * NR + n] = pivot ? m[n] - 1.0 : m[n];
           m[n] = pivot ? 1.0 : 0.0;
         }
       }
       __syncthreads();
-      const double piv = 1.0 / cp[D];
+      const double piv = cp[D];
       const double cj = cp[jslot];
       const double rj = (j == p) ? piv : (j > p ? cj : -cj) * piv;
 #pragma unroll
