@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--mode", type=int, default=0, help="vla_mode (0 = auto)")
     ap.add_argument("--segments", type=int, default=None,
                     help="time segments for the time-parallel mode (default: the library chooses)")
+    ap.add_argument("--decode", action="store_true",
+                    help="time vla_decode_step (one token for every head of the workload, state in place) "
+                         "instead of vla_forward; the roofline is then the HBM one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB -> 1 GiB elementwise copy kernel (calibration of the "
@@ -51,12 +54,74 @@ def parse_args():
     return ap.parse_args()
 
 
+def decode_main(args):
+    """One decode step per timed step: every head of the workload advances by one token on its resident state.
+    Algorithmic traffic per head-token: S and A read and written (4 d^2 float32) + q, k, v read and o written."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+    import vla_inputs
+
+    c = dict(vla_inputs.CONFIGS[args.workload])
+    B, H, d = args.B or c["B"], c["H"], args.d or c["d"]
+    dtype = c["dtype"]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    io = vla.VLA_BF16 if dtype == "bf16" else vla.VLA_F32
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(c["seed"])
+    n_tok = args.warmup + args.steps
+    q, k, v = ((torch.randn(n_tok, B, H, d, device=dev, generator=gen) * d ** -0.5).to(tdt) for _ in range(3))
+    S = torch.zeros(B, H, d, d, device=dev)
+    A = (torch.eye(d, device=dev) / c["lambda0"]).repeat(B, H, 1, 1).contiguous()
+    o = torch.empty(B, H, d, dtype=tdt, device=dev)
+    stream = torch.cuda.current_stream(dev)
+
+    def step(t):
+        rc = vla.vla_decode_step_raw(q[t].data_ptr(), k[t].data_ptr(), v[t].data_ptr(), S.data_ptr(),
+                                     A.data_ptr(), o.data_ptr(), B, H, d, d, io, stream=stream.cuda_stream)
+        if rc != 0:
+            raise RuntimeError(vla.status_string(rc))
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i, (a, b) in enumerate(ev):
+        a.record(stream)
+        step(args.warmup + i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    avg_launch_s = sum(a.elapsed_time(b) for a, b in ev) / len(ev) / 1e3
+    heads = B * H
+    nbytes = heads * (4 * d * d * 4 + 4 * d * (2 if dtype == "bf16" else 4))
+    gbps = nbytes / avg_launch_s / 1e9
+    print(json.dumps({
+        "metric": "VLA decode step tokens/sec (B*H/s)", "value": heads * args.steps / wall,
+        "unit": "head-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"decode: {heads} heads (B={B} H={H}) d_h={d} {dtype} q/k/v/o, fp32 A and S "
+                               f"updated in place, one token per step", "io_dtype": dtype},
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbps / PEAK_HBM_GBS, "traffic": None, "kernel_ms": avg_launch_s * 1e3,
+                     "algorithmic_bytes_per_launch": nbytes},
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (heads are independent, so more GPUs "
               "would only split the batch); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.decode:
+        decode_main(args)
+        return
 
     import numpy as np
     import torch

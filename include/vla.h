@@ -146,6 +146,27 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
                 int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
                 void* stream);
 
+/*
+ * vla_decode_step -- one token of the same recurrence for every head, on a state that stays where it is
+ * (generation: Section 7.4, the fixed-size state S, A is the whole memory).  Equivalent to vla_forward with
+ * T = 1, S0 = S_T = S and A0 = A_T = A, but organised for the memory traffic that dominates a single step
+ * (2 d^2 floats of state read and written per head against 10 d^2 flop).
+ *
+ *   q, k   [B, H, d_k]      io_dtype, contiguous, read-only
+ *   v      [B, H, d_v]      io_dtype, contiguous, read-only
+ *   S      [B, H, d_v, d_k] float32 row-major, updated in place (required)
+ *   A      [B, H, d_k, d_k] float32 row-major, updated in place (required; symmetric positive definite)
+ *   o      [B, H, d_v]      io_dtype, written; must not overlap any input
+ *   d_k == d_v in {16, 32, 64, 96, 128}
+ *   opts   host pointer or NULL; only eps is used.  The optional lines of Algorithm 1 are not available
+ *          here (VLA_ERR_UNSUPPORTED if any is set): use vla_forward with T = 1 for those.
+ *   stream a hipStream_t passed as void*; NULL is the default stream
+ *
+ * All device pointers must be 16-byte aligned.  Asynchronous, allocates nothing.  Returns a vla_status.
+ */
+int vla_decode_step(const void* q, const void* k, const void* v, float* S, float* A, void* o, int B,
+                    int H, int d_k, int d_v, int io_dtype, const vla_opts* opts, void* stream);
+
 /* Human-readable name of a vla_status (static storage, never NULL). */
 const char* vla_status_string(int status);
 

@@ -14,7 +14,7 @@ VLA_F32, VLA_BF16 = 0, 1
 MODE_AUTO, MODE_SCAN, MODE_CHUNKED, MODE_TWO_PHASE, MODE_TIME_PARALLEL = 0, 1, 2, 3, 4
 
 EXPORTS = ("vla_default_opts", "vla_forward_workspace_bytes", "vla_forward",
-           "vla_status_string", "vla_version", "vla_resolve_mode")
+           "vla_decode_step", "vla_status_string", "vla_version", "vla_resolve_mode")
 
 
 class VlaError(RuntimeError):
@@ -62,6 +62,8 @@ def load_library():
     lib.vla_forward_workspace_bytes.restype = ctypes.c_size_t
     lib.vla_forward.argtypes = [P] * 8 + [I] * 6 + [OP, P, ctypes.c_size_t, P]
     lib.vla_forward.restype = I
+    lib.vla_decode_step.argtypes = [P] * 6 + [I] * 5 + [OP, P]
+    lib.vla_decode_step.restype = I
     lib.vla_status_string.argtypes = [I]
     lib.vla_status_string.restype = ctypes.c_char_p
     lib.vla_version.argtypes = []
@@ -116,6 +118,46 @@ def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *
     return int(load_library().vla_forward(n(q), n(k), n(v), n(S0), n(A0), n(o), n(S_T), n(A_T),
                                           B, H, T, d_k, d_v, io_dtype, ctypes.byref(op),
                                           n(workspace), int(workspace_bytes), n(stream)))
+
+
+def vla_decode_step_raw(q, k, v, S, A, o, B, H, d_k, d_v, io_dtype, *, eps=None, stream=0, **extra) -> int:
+    """Direct call with integer device addresses; returns the vla_status."""
+    op = _opts(None, eps, None, extra)
+    n = lambda x: ctypes.c_void_p(int(x) if x else None)
+    return int(load_library().vla_decode_step(n(q), n(k), n(v), n(S), n(A), n(o), B, H, d_k, d_v,
+                                              io_dtype, ctypes.byref(op), n(stream)))
+
+
+def vla_decode_step(q, k, v, S, A, *, eps=None, stream=None):
+    """One token for every head: q, k, v [B,H,d] on the GPU (float32 or bfloat16); S, A [B,H,d,d] float32 are
+    updated in place.  Returns o [B,H,d]."""
+    import torch
+
+    if not (q.is_cuda and k.is_cuda and v.is_cuda and S.is_cuda and A.is_cuda):
+        raise ValueError("all tensors must be on the GPU (no CPU path exists)")
+    if q.dtype == torch.float32:
+        io = VLA_F32
+    elif q.dtype == torch.bfloat16:
+        io = VLA_BF16
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    if k.dtype != q.dtype or v.dtype != q.dtype or q.dim() != 3 or k.shape != q.shape or v.shape[:2] != q.shape[:2]:
+        raise ValueError("expected q,k [B,H,d_k] and v [B,H,d_v] of one dtype")
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    for name, x, shape in (("S", S, (B, H, dv, dk)), ("A", A, (B, H, dk, dk))):
+        if x.dtype != torch.float32 or tuple(x.shape) != shape or not x.is_contiguous() or x.device != q.device:
+            raise ValueError(f"{name} must be a contiguous float32 tensor of shape {shape} on {q.device}")
+    q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+    with torch.cuda.device(q.device):
+        o = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+        st = stream if stream is not None else torch.cuda.current_stream(q.device)
+        handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
+        rc = vla_decode_step_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), S.data_ptr(), A.data_ptr(),
+                                 o.data_ptr(), B, H, dk, dv, io, eps=eps, stream=handle)
+    if rc != 0:
+        raise VlaError(rc, status_string(rc))
+    return o
 
 
 def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None, stream=None,

@@ -182,4 +182,28 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   return VLA_OK;
 }
 
+int vla_decode_step(const void* q, const void* k, const void* v, float* S, float* A, void* o, int B,
+                    int H, int d_k, int d_v, int io_dtype, const vla_opts* opts, void* stream) {
+  const vla_opts op = resolve_opts(opts);
+  const int st = check_shape(B, H, 1, d_k, d_v, io_dtype, op);
+  if (st != VLA_OK) return st;
+  if (general_path(op)) return VLA_ERR_UNSUPPORTED;
+  if (q == nullptr || k == nullptr || v == nullptr || S == nullptr || A == nullptr || o == nullptr) {
+    return VLA_ERR_INVALID_ARG;
+  }
+  const void* ptrs[] = {q, k, v, S, A, o};
+  for (const void* p : ptrs) {
+    if (!aligned16(p)) return VLA_ERR_INVALID_ARG;
+  }
+  if (o == q || o == k || o == v) return VLA_ERR_INVALID_ARG;
+  const hipError_t err = vla::launch_decode(q, k, v, S, A, o, B * H, d_k, io_dtype, op.eps,
+                                            static_cast<hipStream_t>(stream));
+  if (err != hipSuccess) {
+    fprintf(stderr, "libvla: kernel launch failed: %s (%d)\n", hipGetErrorString(err),
+            static_cast<int>(err));
+    return VLA_ERR_HIP;
+  }
+  return VLA_OK;
+}
+
 }  // extern "C"

@@ -85,4 +85,9 @@ hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hip
 hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* seg_A, hipStream_t stream);
 hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t stream);
 
+
+// One decode step for every head, state updated in place (vla_decode.hip).
+hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
+                         int n_heads, int d, int io_dtype, float eps, hipStream_t stream);
+
 }  // namespace vla

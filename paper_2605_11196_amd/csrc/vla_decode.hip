@@ -1,0 +1,179 @@
+// One decode step (T = 1) of the VLA recurrence for many heads: paper Section 3.3 (eq. (sm), eq. (s-update),
+// read-out numerator of eq. (output)) applied once to a resident state (Section 7.4: the fixed-size state
+// S, A is the whole memory, so generation costs one such step per token).
+//
+// The step reads and writes 2 d^2 floats of state per head against 10 d^2 flop: it is bound by HBM, not by
+// arithmetic, so the kernel is organised around coalesced traffic.  One workgroup per head; 16 consecutive
+// lanes cover one row of a matrix (d/16 consecutive floats each), so a wave instruction moves four whole rows
+// and a row's dot product is a 16-lane DPP reduction.  All of A and S is requested up front (the registers
+// hold both matrices), z = A k^ is the only quantity that has to cross rows, through LDS and one barrier.
+//
+//   n = max(||k||, eps), k^ = k / n;  z = A k^;  delta = max(1 + k^.z, eps);  A -= z z^T / delta
+//   A_t k^ = z / delta (u = k^), alpha^ = (z / delta) / max(||z|| / delta, eps)
+//   e = v - S k^;  S += e alpha^^T;  o = S_old q + e (alpha^ . q)   ( = S_new q )
+#include "vla_mfma_util.h"
+
+namespace vla {
+namespace {
+
+template <int N> struct Vec;
+template <> struct Vec<1> { using type = float; };
+template <> struct Vec<2> { using type = float2; };
+template <> struct Vec<4> { using type = float4; };
+
+// EPL consecutive floats <-> registers, in the widest pieces the alignment of d/16-float segments allows
+template <int EPL>
+__device__ __forceinline__ void load_seg(const float* p, float (&x)[EPL]) {
+  constexpr int VW = EPL % 4 == 0 ? 4 : (EPL % 2 == 0 ? 2 : 1);
+  using V = typename Vec<VW>::type;
+#pragma unroll
+  for (int e = 0; e < EPL; e += VW) {
+    const V v = *reinterpret_cast<const V*>(p + e);
+    const float* f = reinterpret_cast<const float*>(&v);
+#pragma unroll
+    for (int i = 0; i < VW; ++i) x[e + i] = f[i];
+  }
+}
+template <int EPL>
+__device__ __forceinline__ void store_seg(float* p, const float (&x)[EPL]) {
+  constexpr int VW = EPL % 4 == 0 ? 4 : (EPL % 2 == 0 ? 2 : 1);
+  using V = typename Vec<VW>::type;
+#pragma unroll
+  for (int e = 0; e < EPL; e += VW) {
+    V v;
+    float* f = reinterpret_cast<float*>(&v);
+#pragma unroll
+    for (int i = 0; i < VW; ++i) f[i] = x[e + i];
+    *reinterpret_cast<V*>(p + e) = v;
+  }
+}
+template <int EPL>
+__device__ __forceinline__ void load_io(const float* p, float (&x)[EPL]) { load_seg<EPL>(p, x); }
+template <int EPL>
+__device__ __forceinline__ void load_io(const uint16_t* p, float (&x)[EPL]) {
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) x[e] = bf16_to_f32(p[e]);
+}
+
+template <int EPL>
+__device__ __forceinline__ float dot_seg(const float (&x)[EPL], const float (&y)[EPL]) {
+  float s = 0.0f;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) s = fmaf(x[e], y[e], s);
+  return s;
+}
+
+struct DecodeArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  float* S;
+  float* A;
+  void* o;
+  float eps;
+};
+
+template <int D, typename IO>
+__global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs a) {
+  constexpr int EPL = D / 16;                 // floats per lane per row
+  constexpr int ROWS_W = D >= 32 ? 32 : D;    // rows of each matrix per wave
+  constexpr int NP = ROWS_W / 4;              // passes: a wave instruction covers four rows
+  __shared__ float zs[D];
+
+  const int head = blockIdx.x;
+  const int w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int col0 = c * EPL;
+  const int row0 = ROWS_W * w + g;            // row of pass p: row0 + 4 p
+
+  float* Ah = a.A + static_cast<size_t>(head) * D * D;
+  float* Sh = a.S + static_cast<size_t>(head) * D * D;
+  const IO* qh = static_cast<const IO*>(a.q) + static_cast<size_t>(head) * D;
+  const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * D;
+  const IO* vh = static_cast<const IO*>(a.v) + static_cast<size_t>(head) * D;
+  IO* oh = static_cast<IO*>(a.o) + static_cast<size_t>(head) * D;
+
+  // everything is requested before anything is used
+  float Ar[NP][EPL], Sr[NP][EPL];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) load_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
+#pragma unroll
+  for (int p = 0; p < NP; ++p) load_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
+  float kk[EPL], qq[EPL], vr[NP];
+  load_io<EPL>(kh + col0, kk);
+  load_io<EPL>(qh + col0, qq);
+#pragma unroll
+  for (int p = 0; p < NP; ++p) vr[p] = widen(vh[row0 + 4 * p]);
+
+  const float eps = a.eps;
+  const float rn = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(kk, kk))), eps);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) kk[e] *= rn;   // k^
+
+  // z = A k^ : rows of this wave, then the whole vector through LDS
+  float zr[NP];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    zr[p] = row_sum16(dot_seg<EPL>(Ar[p], kk));
+    if (c == 0) zs[row0 + 4 * p] = zr[p];
+  }
+  __syncthreads();
+  float zc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) zc[e] = zs[col0 + e];
+
+  const float delta = fmaxf(1.0f + row_sum16(dot_seg<EPL>(kk, zc)), eps);
+  const float rd = 1.0f / delta;
+  const float an = sqrtf(row_sum16(dot_seg<EPL>(zc, zc))) * rd;   // ||A_t k^||
+  const float ca = rd / fmaxf(an, eps);
+  float al[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) al[e] = zc[e] * ca;               // alpha^
+  const float aq = row_sum16(dot_seg<EPL>(al, qq));
+
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const float f = -zr[p] * rd;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) Ar[p][e] = fmaf(f, zc[e], Ar[p][e]);
+    store_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
+  }
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const float sk = row_sum16(dot_seg<EPL>(Sr[p], kk));
+    const float sq = row_sum16(dot_seg<EPL>(Sr[p], qq));
+    const float er = vr[p] - sk;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) Sr[p][e] = fmaf(er, al[e], Sr[p][e]);
+    store_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
+    if (c == 0) io_store(oh + row0 + 4 * p, fmaf(er, aq, sq));
+  }
+}
+
+template <int D, typename IO>
+hipError_t launch(const DecodeArgs& a, int n_heads, hipStream_t stream) {
+  DecodeArgs args = a;
+  void* params[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(&decode_kernel<D, IO>), dim3(n_heads),
+                         dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
+}
+
+}  // namespace
+
+hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
+                         int n_heads, int d, int io_dtype, float eps, hipStream_t stream) {
+  const DecodeArgs a{q, k, v, S, A, o, eps};
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 16: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);
+    case 32: return bf ? launch<32, uint16_t>(a, n_heads, stream) : launch<32, float>(a, n_heads, stream);
+    case 64: return bf ? launch<64, uint16_t>(a, n_heads, stream) : launch<64, float>(a, n_heads, stream);
+    case 96: return bf ? launch<96, uint16_t>(a, n_heads, stream) : launch<96, float>(a, n_heads, stream);
+    case 128: return bf ? launch<128, uint16_t>(a, n_heads, stream) : launch<128, float>(a, n_heads, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace vla

@@ -89,6 +89,27 @@ def test_host_side_validation_returns_status_without_launch(kw, status):
     assert call(**kw) == status
 
 
+def decode_call(**kw):
+    a = dict(q=FAKE, k=FAKE + 0x1000, v=FAKE + 0x2000, S=FAKE + 0x4000, A=FAKE + 0x8000, o=FAKE + 0x3000,
+             B=1, H=1, d_k=16, d_v=16, io_dtype=vla.VLA_F32)
+    opt = {}
+    for key, val in kw.items():
+        (a if key in a else opt)[key] = val
+    return vla.vla_decode_step_raw(a["q"], a["k"], a["v"], a["S"], a["A"], a["o"], a["B"], a["H"],
+                                   a["d_k"], a["d_v"], a["io_dtype"], **opt)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), 1), (dict(io_dtype=3), 1), (dict(eps=0.0), 1),
+    (dict(S=0), 1), (dict(A=0), 1), (dict(o=0), 1), (dict(k=0), 1),     # the state is required here
+    (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=64), 2),
+    (dict(refresh_period=20), 2), (dict(normalise_output=1), 2),        # options: only through vla_forward
+])
+def test_decode_step_host_side_validation(kw, status):
+    assert decode_call(**kw) == status
+
+
 def test_zero_tokens_without_state_outputs_is_ok_and_launches_nothing():
     assert call(T=0, q=0, k=0, v=0, o=0) == 0
 
