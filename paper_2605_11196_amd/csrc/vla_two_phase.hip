@@ -549,6 +549,228 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------- phase 2, shared operands
+// The same recurrence with one workgroup per (head, time segment): one wave per 16-row slab of S (twice as
+// many waves for the map pass: Q-run slabs, then P-run slabs), the block's operands fetched once for all of
+// them and handed round through LDS.  Used when there are enough (head, segment) pairs to fill the chip: the
+// per-wave kernel above then reads the same operands d/16 times over and every wave waits on its own stream.
+//
+// Pipeline, one barrier per block: the data of block n is requested in iteration n - 3 (two register sets),
+// written to LDS stage n % 2 in iteration n - 1 (after that iteration's barrier, which every wave reaches only
+// when it is done reading the stage for block n - 2) and consumed in iteration n.  Registers are capped at 128
+// so that four workgroups (d <= 64) share a compute unit and 1024 (head, segment) pairs run in one round.
+template <int D, typename IO, bool MAP>
+__global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_kernel(ForwardArgs a) {
+  constexpr int NB = D / 16;
+  constexpr int NSLAB = D / 16;
+  constexpr int NT = 64 * NSLAB * (MAP ? 2 : 1);
+  constexpr int LD = D + 4;
+  constexpr int CH = 4 * D;                     // 16-byte pieces of K^ (and of W, and 4-element pieces of q)
+  static_assert(NT == (MAP ? 2 * CH : CH), "one piece of each big operand per thread");
+  constexpr int NST = 2;
+  struct Stage {
+    float Ks[C * LD];      // K^ [t][j]
+    float Qs[C * LD];      // q  [t][j] widened (unused by the map pass)
+    float Wb[D * LT];      // W  [j][t]
+    float Zs[C * LT];      // Z  [t][s]
+    float NQs[C * LT];     // -NQ^T [t][s]
+    float cv[C];           // -c_t
+  };
+  __shared__ __align__(16) Stage stg[NST];
+
+  const int hs = blockIdx.x;                     // head * n_seg + seg
+  const int head = hs / a.n_seg;
+  const int seg = hs - head * a.n_seg;
+  if (MAP && seg == a.n_seg - 1) return;         // nothing follows the last segment
+  const int tid = threadIdx.x;
+  const int w = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const bool p_run = MAP && w >= NSLAB;          // identity rows, v = 0
+  const int row0 = (w % NSLAB) * 16;
+  const int nblk = (a.T + C - 1) / C;
+  const int bb = seg * a.seg_blocks;
+  const int be = min(nblk, bb + a.seg_blocks);
+  const int T = min(a.T, be * C);
+
+  const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
+  const float* KH = wsh;
+  const float* WT = wsh + static_cast<size_t>(nblk) * C * D;
+  const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+
+  f4 st[NB];   // st[b][r] = S[row0 + c][16b + 4g + r]
+  if constexpr (MAP) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st[b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+  } else {
+    const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * D * D
+                              : (a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr);
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+      st[b] = S0 ? *reinterpret_cast<const f4*>(S0 + (row0 + c) * D + 16 * b + 4 * g) : f4{0, 0, 0, 0};
+  }
+
+  // ---- this thread's share of a block's operands
+  // big operands: piece `pc` of K^ and of q (row pc / (D/4), columns 4 (pc % (D/4)) ..) and of W (row
+  // pc / 4 of [D][16], columns 4 (pc % 4) ..); in the map pass the first half of the threads carries K^ and
+  // the second half W.  small operands: Z (64 pieces), -NQ^T (64), -c (4) on the first threads.
+  const int pc = MAP ? tid % CH : tid;
+  const bool do_k = !MAP || tid < CH;
+  const bool do_w = !MAP || tid >= CH;
+  const int krow = pc / (D / 4), kcol = 4 * (pc % (D / 4));
+  const int wrow = pc / 4, wcol = 4 * (pc % 4);
+  const int sm_src = tid < 64 ? 4 * tid : 2 * C * C + 4 * (tid - 64);
+  const bool do_sm = tid < (MAP ? 64 : 128);   // Z on threads 0-63, -NQ^T on 64-127 (not in the map pass)
+  const bool do_c = tid < 4;                   // -c
+  struct Regs {
+    f4 kx, wx, sx, cx;
+    Raw4<IO> qx;
+    IO v[4];
+  };
+  auto fetch = [&](int blk, Regs& r) {
+    if (do_k) r.kx = *reinterpret_cast<const f4*>(KH + static_cast<size_t>(blk) * (C * D) + krow * D + kcol);
+    if (do_w) r.wx = *reinterpret_cast<const f4*>(WT + static_cast<size_t>(blk) * (D * C) + wrow * C + wcol);
+    if (do_sm) r.sx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + sm_src);
+    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 3 * C * C + 4 * tid);
+    const int lim = T - 1 - blk * C;   // last live token row of the block
+    if constexpr (!MAP) {
+      r.qx.load(qh + static_cast<size_t>(blk) * (C * D) + min(krow, lim) * D + kcol);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      r.v[i] = vh[static_cast<size_t>(blk) * (C * D) + min(4 * g + i, lim) * D + row0 + c];
+  };
+  auto put = [&](const Regs& r, Stage& s) {
+    if (do_k) *reinterpret_cast<f4*>(&s.Ks[krow * LD + kcol]) = r.kx;
+    if (do_w) *reinterpret_cast<f4*>(&s.Wb[wrow * LT + wcol]) = r.wx;
+    if (do_sm) {
+      // Z and -NQ^T rows are 16 floats in the workspace and LT in LDS
+      if (tid < 64) *reinterpret_cast<f4*>(&s.Zs[(tid / 4) * LT + 4 * (tid % 4)]) = r.sx;
+      else *reinterpret_cast<f4*>(&s.NQs[((tid - 64) / 4) * LT + 4 * (tid % 4)]) = r.sx;
+    }
+    if (do_c) *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
+    if constexpr (!MAP) {
+      float x[4];
+      r.qx.unpack(x);
+      *reinterpret_cast<f4*>(&s.Qs[krow * LD + kcol]) = f4{x[0], x[1], x[2], x[3]};
+    }
+  };
+  auto compute = [&](int blk, const Stage& s, const IO (&vv)[4]) {
+    const int t0 = blk * C;
+    f4 ft, ot = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(vv[r]) : 0.0f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 ka = lds4(&s.Ks[c * LD + 16 * b + 4 * g]);
+      f4 qa;
+      if constexpr (!MAP) qa = lds4(&s.Qs[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        ft = mfma16(ka[r], st[b][r], ft);
+        if constexpr (!MAP) ot = mfma16(qa[r], st[b][r], ot);
+      }
+    }
+    const f4 za = lds4(&s.Zs[c * LT + 4 * g]);
+    f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
+    if constexpr (!MAP) {
+      const f4 nqa = lds4(&s.NQs[c * LT + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+      IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
+#ifdef EXP_NOSTORE
+      if (ot[0] == 123.456f) io_store(ob, ot[1]);
+      if (false) {
+#else
+      if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
+#endif
+#pragma unroll
+        for (int r = 0; r < 4; ++r) io_store(ob + r * D, ot[r]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (t0 + 4 * g + r < T) io_store(ob + r * D, ot[r]);
+        }
+      }
+    }
+    const f4 ce = et * lds4(&s.cv[4 * g]);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 wa = lds4(&s.Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st[b] = mfma16(wa[r], ce[r], st[b]);
+    }
+  };
+
+  // prologue: block bb into stage 0 (visible after the first barrier), bb+1 and bb+2 in flight
+  Regs r0, r1;
+  if (bb < be) {
+    fetch(bb, r0);
+    put(r0, stg[0]);
+  }
+  IO vcur[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) vcur[i] = r0.v[i];
+  if (bb + 1 < be) fetch(bb + 1, r0);
+  if (bb + 2 < be) fetch(bb + 2, r1);
+  // iteration n (block bb + n): r0 holds block n+1, r1 block n+2 when n is even, the other way round when odd
+  for (int n = 0; bb + n < be; n += 2) {
+    {
+      const int blk = bb + n;
+      __syncthreads();
+      IO vnext[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vnext[i] = r0.v[i];
+      if (blk + 1 < be) put(r0, stg[(n + 1) % NST]);
+      if (blk + 3 < be) fetch(blk + 3, r0);
+      compute(blk, stg[n % NST], vcur);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vcur[i] = vnext[i];
+    }
+    if (bb + n + 1 < be) {
+      const int blk = bb + n + 1;
+      __syncthreads();
+      IO vnext[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vnext[i] = r1.v[i];
+      if (blk + 1 < be) put(r1, stg[(n + 2) % NST]);
+      if (blk + 3 < be) fetch(blk + 3, r1);
+      compute(blk, stg[(n + 1) % NST], vcur);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vcur[i] = vnext[i];
+    }
+  }
+
+  float* out = nullptr;
+  if constexpr (MAP) {
+    out = a.seg_PQ + (static_cast<size_t>(hs) * 2 + (p_run ? 0 : 1)) * D * D;
+  } else if (a.S_T && seg == a.n_seg - 1) {
+    out = a.S_T + static_cast<size_t>(head) * D * D;
+  }
+  if (out) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+      *reinterpret_cast<f4*>(out + (row0 + c) * D + 16 * b + 4 * g) = st[b];
+  }
+}
+
+template <int D, typename IO, bool MAP>
+hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_lds_kernel<D, IO, MAP>),
+                         dim3(a.n_heads * a.n_seg), dim3(64 * (D / 16) * (MAP ? 2 : 1)), params, 0, stream);
+}
+
 template <int D, typename IO, bool MAP, int RS>
 hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
@@ -582,23 +804,12 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
                           dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), p2, 0, stream);
     if (err != hipSuccess) return err;
   }
-  // Slabs of S per wave: as many as still leave two waves per SIMD (2048 on the chip) and fit the register
-  // file (every slab up to d = 64), else one, for the most waves.
-  constexpr int kSlabs = D / 16;
-  const int waves1 = hs * kSlabs;
-  int rs = 1;
-  if (D <= 64) {
-    while (rs < kSlabs && waves1 / (2 * rs) >= 2048) rs *= 2;
-  }
+  // With enough (head, segment) pairs to fill the chip the block operands are shared through LDS by a
+  // workgroup per pair; with few, one wave per slab of S and deep register prefetch give the most waves.
+  const bool shared = hs >= 256;
   auto rows = [&](auto map_tag) -> hipError_t {
     constexpr bool kMap = decltype(map_tag)::value;
-    if constexpr (D <= 64) {
-      if (rs == kSlabs && kSlabs > 1) return launch_s_rows<D, IO, kMap, kSlabs>(a, stream);
-      if constexpr (kSlabs >= 4) {
-        if (rs == 2) return launch_s_rows<D, IO, kMap, 2>(a, stream);
-      }
-    }
-    return launch_s_rows<D, IO, kMap, 1>(a, stream);
+    return shared ? launch_s_rows_lds<D, IO, kMap>(a, stream) : launch_s_rows<D, IO, kMap, 1>(a, stream);
   };
   if (a.n_seg > 1) {
     // the state of S at the segment boundaries: per-segment affine maps, then their composition

@@ -30,6 +30,24 @@ def test_segments_match_the_sequential_oracle(d, T, segments, dtype):
     print(d, T, segments, dtype, errs)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,T,segments", [(64, 250, 8), (32, 300, 8), (128, 150, 8), (64, 16 * 9, 9)])
+def test_many_head_segment_pairs_take_the_shared_operand_kernels(d, T, segments, dtype):
+    """32 heads x 8 segments = 256 (head, segment) pairs: from there on the S recurrence runs with one
+    workgroup per pair and the block operands staged once through LDS (ragged last block, one- and
+    two-block segments, the three-stage ring wrapping round)."""
+    q, k, v = vla_inputs.gaussian_qkv(4, 8, T, d, seed=1200 + d + T)
+    S0 = np.random.default_rng(d).standard_normal((4, 8, d, d)).astype(np.float32)
+    errs, _, _ = check_parity(q, k, v, S0, None, dtype=dtype, lambda0=0.1, mode=TP, segments=segments)
+    print(d, T, segments, dtype, errs)
+
+
+@pytest.mark.parametrize("d,T", [(64, 100), (128, 33), (32, 200)])
+def test_two_phase_with_many_heads_takes_the_shared_operand_kernel(d, T):
+    q, k, v = vla_inputs.gaussian_qkv(16, 16, T, d, seed=1300 + d)
+    check_parity(q, k, v, lambda0=0.1, mode=3)
+
+
 @pytest.mark.parametrize("d", [32, 64, 128])
 def test_given_initial_state_enters_the_boundary_inverse(d):
     """A non-trivial symmetric positive definite A0 and a non-zero S0 (the state after T1 tokens, from
