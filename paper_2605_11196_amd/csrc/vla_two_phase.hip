@@ -687,12 +687,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
       IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
-#ifdef EXP_NOSTORE
-      if (ot[0] == 123.456f) io_store(ob, ot[1]);
-      if (false) {
-#else
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
-#endif
 #pragma unroll
         for (int r = 0; r < 4; ++r) io_store(ob + r * D, ot[r]);
       } else {
