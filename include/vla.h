@@ -72,7 +72,7 @@ typedef enum {
 typedef enum {
   VLA_OK = 0,
   VLA_ERR_INVALID_ARG = 1, /* null required pointer, non-positive size, misaligned pointer, bad enum */
-  VLA_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for (head size, d_k != d_v, mode) */
+  VLA_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for (head sizes, mode, option) */
   VLA_ERR_WORKSPACE = 3,   /* workspace missing or smaller than vla_forward_workspace_bytes() */
   VLA_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
 } vla_status;
@@ -131,7 +131,8 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may alias S0
  *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may alias A0
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
- *   d_k == d_v in {16, 32, 64, 96, 128}  (the block kernels cover 32, 64, 128)
+ *   d_k == d_v in {16, 32, 64, 96, 128}  (the block kernels cover 32, 64, 128), or d_k, d_v in
+ *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN kernel only, no options)
  *   opts   host pointer or NULL
  *   workspace, workspace_bytes: device scratch of at least
  *          vla_forward_workspace_bytes(...) bytes (may be NULL/0 when that is 0)

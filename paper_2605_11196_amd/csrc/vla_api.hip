@@ -9,8 +9,6 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
-bool supported_head_size(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
-
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 vla_opts resolve_opts(const vla_opts* o) {
@@ -31,7 +29,7 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
   // kernels address one head's [T, d] slab with 32-bit byte offsets
   if (static_cast<long long>(T) * (d_k > d_v ? d_k : d_v) * 4 >= 0x7fffffffLL) return VLA_ERR_UNSUPPORTED;
-  if (d_k != d_v || !supported_head_size(d_k)) return VLA_ERR_UNSUPPORTED;
+  if (!vla::scan_supported(d_k, d_v)) return VLA_ERR_UNSUPPORTED;
   return VLA_OK;
 }
 
@@ -44,17 +42,17 @@ bool general_path(const vla_opts& o) {
 // AUTO: options -> scan family; few heads on a long sequence -> time-parallel (segments of the sequence run
 // concurrently and the S rows spread over d/16 times more workgroups than there are heads); otherwise the
 // fused block kernel.
-int pick_mode(int B, int H, int T, int d, int /*io_dtype*/, const vla_opts& o) {
+int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (general_path(o)) return VLA_MODE_SCAN;
-  if (!vla::chunk_supported(d)) return VLA_MODE_SCAN;
+  if (d != d_v || !vla::chunk_supported(d)) return VLA_MODE_SCAN;
   const long long heads = static_cast<long long>(B) * H;
   return (heads <= 64 && T >= 1024) ? VLA_MODE_TIME_PARALLEL : VLA_MODE_CHUNKED;
 }
 
-bool mode_available(int mode, int d, const vla_opts& o) {
-  if (mode == VLA_MODE_SCAN) return true;
-  if (general_path(o)) return false;
+bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
+  if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernel is square only
+  if (general_path(o) || d != d_v) return false;
   if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
     return vla::chunk_supported(d);
   }
@@ -98,16 +96,16 @@ const char* vla_status_string(int status) {
 int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_opts* opts) {
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return -1;
-  const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  return mode_available(mode, d_k, o) ? mode : -1;
+  const int mode = pick_mode(B, H, T, d_k, d_v, o);
+  return mode_available(mode, d_k, d_v, o) ? mode : -1;
 }
 
 size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
                                    const vla_opts* opts) {
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
-  const int mode = pick_mode(B, H, T, d_k, io_dtype, o);
-  if (!mode_available(mode, d_k, o)) return 0;
+  const int mode = pick_mode(B, H, T, d_k, d_v, o);
+  if (!mode_available(mode, d_k, d_v, o)) return 0;
   if (mode == VLA_MODE_TWO_PHASE) return vla::two_phase_workspace_bytes(B * H, T, d_k);
   if (mode == VLA_MODE_TIME_PARALLEL) return vla::time_parallel_workspace_bytes(B * H, T, d_k, o.segments);
   return 0;
@@ -129,8 +127,8 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   }
   if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
 
-  int mode = pick_mode(B, H, T, d_k, io_dtype, op);
-  if (!mode_available(mode, d_k, op)) return VLA_ERR_UNSUPPORTED;
+  int mode = pick_mode(B, H, T, d_k, d_v, op);
+  if (!mode_available(mode, d_k, d_v, op)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
     // AUTO never fails for want of a workspace: it falls back to the fused block kernel
@@ -160,7 +158,7 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
     case VLA_MODE_SCAN:
       err = general_path(op)
                 ? vla::launch_scan_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
-                : vla::launch_scan(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+                : vla::launch_scan(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_CHUNKED:
       err = vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
@@ -187,7 +185,7 @@ int vla_decode_step(const void* q, const void* k, const void* v, float* S, float
   const vla_opts op = resolve_opts(opts);
   const int st = check_shape(B, H, 1, d_k, d_v, io_dtype, op);
   if (st != VLA_OK) return st;
-  if (general_path(op)) return VLA_ERR_UNSUPPORTED;
+  if (general_path(op) || d_k != d_v) return VLA_ERR_UNSUPPORTED;
   if (q == nullptr || k == nullptr || v == nullptr || S == nullptr || A == nullptr || o == nullptr) {
     return VLA_ERR_INVALID_ARG;
   }

@@ -52,8 +52,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return static_cast<uint16_t>(x >> 16);
 }
 
-// Token-by-token scan, one workgroup per head (vla_scan.hip).
-hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+// Token-by-token scan, one workgroup per head (vla_scan.hip); the only kernel family with d_k != d_v.
+bool scan_supported(int d_k, int d_v);
+hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream);
 // Same, with the optional lines of Algorithm 1 (separate u, refresh, normalised read-out, ELU+1).
 hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 

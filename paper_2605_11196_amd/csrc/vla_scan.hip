@@ -35,21 +35,23 @@ __device__ __forceinline__ void load4(const uint16_t* p, float out[4]) {
 __device__ __forceinline__ void store1(float* p, float x) { *p = x; }
 __device__ __forceinline__ void store1(uint16_t* p, float x) { *p = f32_to_bf16_rne(x); }
 
-template <int D, typename IO>
-__global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
-  constexpr int NT = 2 * D;
+// D = d_k is the length of a row of either matrix (and of q, k); DV = d_v is the number of rows of S (and the
+// length of v, o).  Threads [0, D) own the rows of A, threads [D, D + DV) the rows of S.
+template <int D, int DV, typename IO>
+__global__ void __launch_bounds__(D + DV) scan_kernel(ForwardArgs a) {
+  constexpr int NT = D + DV;
   constexpr int RED_LANES = D < 64 ? D : 64;  // A-role lanes that share one wave
   constexpr int NWA = (D + 63) / 64;          // waves publishing partial sums
 
   __shared__ __align__(16) float qs[kTile * D];
   __shared__ __align__(16) float ks[kTile * D];
-  __shared__ __align__(16) float vs[kTile * D];
+  __shared__ __align__(16) float vs[kTile * DV];
   __shared__ __align__(16) float zb[2][D];
   __shared__ __align__(16) float red[2][NWA][4];
 
   const int head = blockIdx.x;
   const int tid = threadIdx.x;
-  const int role = tid / D;  // 0: a row of A, 1: a row of S
+  const int role = tid < D ? 0 : 1;  // 0: a row of A, 1: a row of S
   const int i = tid - role * D;
   const int T = a.T;
 
@@ -57,7 +59,7 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
   {
     const float* src = role == 0 ? a.A0 : a.S0;
     if (src != nullptr) {
-      const float* p = src + (static_cast<size_t>(head) * D + i) * D;
+      const float* p = src + (static_cast<size_t>(head) * (role == 0 ? D : DV) + i) * D;
 #pragma unroll
       for (int j = 0; j < D; j += 4) load4(p + j, &row[j]);
     } else {
@@ -68,10 +70,11 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
   }
 
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slabv = static_cast<size_t>(head) * static_cast<size_t>(T) * DV;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
-  const IO* vh = static_cast<const IO*>(a.v) + slab;
-  IO* oh = static_cast<IO*>(a.o) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slabv;
+  IO* oh = static_cast<IO*>(a.o) + slabv;
   const float eps = a.eps;
 
   for (int t0 = 0; t0 < T; t0 += kTile) {
@@ -84,7 +87,10 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
       *reinterpret_cast<float4*>(&qs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
       load4(kh + off, x);
       *reinterpret_cast<float4*>(&ks[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
-      load4(vh + off, x);
+    }
+    for (int idx = tid; idx < nt * (DV / 4); idx += NT) {
+      float x[4];
+      load4(vh + static_cast<size_t>(t0) * DV + static_cast<size_t>(idx) * 4, x);
       *reinterpret_cast<float4*>(&vs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
     }
     __syncthreads();
@@ -172,7 +178,7 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
           row[j + 3] = fmaf(f, zj.w, row[j + 3]);
         }
       } else {
-        const float e = vs[tt * D + i] - mv * inv_n;
+        const float e = vs[tt * DV + i] - mv * inv_n;
         const float g = e * ca;
 #pragma unroll
         for (int j = 0; j < D; j += 4) {
@@ -182,14 +188,14 @@ __global__ void __launch_bounds__(2 * D) scan_kernel(ForwardArgs a) {
           row[j + 2] = fmaf(g, zj.z, row[j + 2]);
           row[j + 3] = fmaf(g, zj.w, row[j + 3]);
         }
-        store1(oh + static_cast<size_t>(t0 + tt) * D + i, fmaf(g, zq, rv));
+        store1(oh + static_cast<size_t>(t0 + tt) * DV + i, fmaf(g, zq, rv));
       }
     }
   }
 
   float* dst = role == 0 ? a.A_T : a.S_T;
   if (dst != nullptr) {
-    float* p = dst + (static_cast<size_t>(head) * D + i) * D;
+    float* p = dst + (static_cast<size_t>(head) * (role == 0 ? D : DV) + i) * D;
 #pragma unroll
     for (int j = 0; j < D; j += 4) {
       *reinterpret_cast<float4*>(p + j) = make_float4(row[j], row[j + 1], row[j + 2], row[j + 3]);
@@ -417,26 +423,43 @@ hipError_t launch_general(const ForwardArgs& a, hipStream_t stream) {
                          dim3(2 * D), params, 0, stream);
 }
 
-template <int D, typename IO>
+template <int D, int DV, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   // hipLaunchKernel reports this launch's own status; the sticky hipGetLastError() value may
   // belong to an unrelated earlier call made by the host program.
   ForwardArgs args = a;
   void* params[] = {&args};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_kernel<D, IO>), dim3(a.n_heads),
-                         dim3(2 * D), params, 0, stream);
+  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_kernel<D, DV, IO>), dim3(a.n_heads),
+                         dim3(D + DV), params, 0, stream);
+}
+template <int D, int DV>
+hipError_t launch_io(const ForwardArgs& a, int io_dtype, hipStream_t stream) {
+  return io_dtype == 1 ? launch<D, DV, uint16_t>(a, stream) : launch<D, DV, float>(a, stream);
 }
 
 }  // namespace
 
-hipError_t launch_scan(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
-  const bool bf = io_dtype == 1;
-  switch (d) {
-    case 16: return bf ? launch<16, uint16_t>(a, stream) : launch<16, float>(a, stream);
-    case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
-    case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
-    case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);
-    case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+// Square heads of every supported size, and value heads half or twice as wide as the key heads.
+bool scan_supported(int d_k, int d_v) {
+  if (d_k == d_v) return d_k == 16 || d_k == 32 || d_k == 64 || d_k == 96 || d_k == 128;
+  const bool pow2 = (d_k == 16 || d_k == 32 || d_k == 64 || d_k == 128) &&
+                    (d_v == 16 || d_v == 32 || d_v == 64 || d_v == 128);
+  return pow2 && (d_v == 2 * d_k || d_k == 2 * d_v);
+}
+
+hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
+  switch (d_k * 1000 + d_v) {
+    case 16016: return launch_io<16, 16>(a, io_dtype, stream);
+    case 32032: return launch_io<32, 32>(a, io_dtype, stream);
+    case 64064: return launch_io<64, 64>(a, io_dtype, stream);
+    case 96096: return launch_io<96, 96>(a, io_dtype, stream);
+    case 128128: return launch_io<128, 128>(a, io_dtype, stream);
+    case 16032: return launch_io<16, 32>(a, io_dtype, stream);
+    case 32016: return launch_io<32, 16>(a, io_dtype, stream);
+    case 32064: return launch_io<32, 64>(a, io_dtype, stream);
+    case 64032: return launch_io<64, 32>(a, io_dtype, stream);
+    case 64128: return launch_io<64, 128>(a, io_dtype, stream);
+    case 128064: return launch_io<128, 64>(a, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -282,3 +282,76 @@ def test_heads_are_independent_and_output_is_causal():
     q2[:, :, 50:] += 1; k2[:, :, 50:] *= -2; v2[:, :, 50:] = 7
     o2, _, _ = gpu_forward(q2, k2, v2)
     assert np.array_equal(o2[:, :, :50], o[:, :, :50])
+
+
+@pytest.mark.parametrize("mode,shape", [(2, (2, 4, 300, 128)), (4, (1, 4, 1024, 64)), (1, (2, 2, 100, 96))])
+def test_forward_can_be_captured_in_a_hip_graph_and_replayed(mode, shape):
+    """The library only enqueues kernels (no allocation, no host synchronisation, no memset nodes), so a call
+    can be captured; every replay must reproduce the eager result for the inputs then in the buffers."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, T, d = shape
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    q, k, v = (torch.randn(B, H, T, d, device=dev, generator=gen) for _ in range(3))
+    o = torch.empty_like(q)
+    S = torch.empty(B, H, d, d, device=dev)
+    A = torch.empty(B, H, d, d, device=dev)
+    need = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_F32, mode=mode, segments=4)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+    def call(stream):
+        rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(), S.data_ptr(),
+                                 A.data_ptr(), B, H, T, d, d, vla.VLA_F32, mode=mode, segments=4,
+                                 workspace=ws.data_ptr(), workspace_bytes=need, stream=stream.cuda_stream)
+        assert rc == 0
+
+    side = torch.cuda.Stream(dev)
+    side.wait_stream(torch.cuda.current_stream(dev))
+    with torch.cuda.stream(side):
+        call(side)                       # warm-up outside capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream(dev))
+    for rep in range(3):
+        for x in (q, k, v):
+            x.copy_(torch.randn(B, H, T, d, device=dev, generator=gen))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (o, S, A)]
+        call(torch.cuda.current_stream(dev))     # eager, same buffers
+        torch.cuda.synchronize()
+        for g, e in zip(got, (o, S, A)):
+            assert torch.equal(g, e), rep
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dk,dv", [(16, 32), (32, 16), (32, 64), (64, 32), (64, 128), (128, 64)])
+def test_value_heads_half_or_twice_as_wide_as_key_heads(dk, dv, dtype):
+    """d_k != d_v: S is d_v x d_k, A is d_k x d_k (Section 3.3 only fixes the shapes through o = S q)."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, T = 2, 3, 147
+    rng = np.random.default_rng(1000 + dk + dv)
+    q, k = (rng.standard_normal((B, H, T, dk)).astype(np.float32) for _ in range(2))
+    v = rng.standard_normal((B, H, T, dv)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
+    if dtype == "bf16":
+        q, k, v = (vla_inputs.round_to_bf16(x) for x in (q, k, v))
+    ref = oracle.forward(q, k, v, S0, None, lambda0=0.1)
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tq, tk, tv = (torch.from_numpy(x).to(dev).to(tdt) for x in (q, k, v))
+    o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1)
+    torch.cuda.synchronize()
+    assert tuple(o.shape) == (B, H, T, dv) and tuple(S_T.shape) == (B, H, dv, dk) and tuple(A_T.shape) == (B, H, dk, dk)
+    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+    assert max(errs.values()) <= TOL[dtype], errs
