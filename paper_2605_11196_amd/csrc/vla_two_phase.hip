@@ -13,6 +13,10 @@
 //   phase 1b (zc_kernel):      one wave per (head, block), the C x C work the S recurrence needs
 //   phase 2  (s_rows_kernel):  one wave per (head, 16-row slab of S); operands come straight from
 //                              global memory in MFMA operand layout, no LDS and no barriers
+//            (s_rows_lds_kernel, many heads): one workgroup per head, operands shared through LDS
+//
+// Every kernel also takes a time segment of the sequence instead of the whole of it: the time-parallel mode
+// (driver at the end of this file, boundary states in vla_segments.hip) runs the segments concurrently.
 #include "vla_mfma_util.h"
 
 #include <type_traits>
@@ -351,25 +355,23 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
 }
 
 // ------------------------------------------------------------------------------------------ phase 2
-// One wave per (head, time segment, group of RS 16-row slabs of S).  st[s][b][r] = S[row(s) + c][16b + 4g + r].
-// The operands of a block (K^, W, Z, -NQ^T, -c, q) are the same for every row of S, so a wave that holds
-// RS slabs reads them once for all of them: RS = 1 gives the most waves (few heads, latency bound), larger
-// RS divides the memory traffic when there are enough (head, segment) pairs to fill the chip anyway.
+// One wave per (head, time segment, 16-row slab of S), no LDS and no barriers: the most waves when heads are
+// few.  st[b][r] = S[row0 + c][16b + 4g + r]; the operands of a block (K^, W, Z, -NQ^T, -c, q) come straight
+// from global memory in MFMA operand layout.
 //
 // MAP = false: the recurrence proper: reads q, writes o.
 // MAP = true:  the affine map S_end = S_start P + Q of one segment, for the time-parallel mode.  Rows of S
 //              are independent, so row i of P is what row i of the identity evolves into with v = 0, and Q is
-//              what a zero state evolves into with the real v: twice the row groups per (head, segment),
+//              what a zero state evolves into with the real v: twice the slabs per (head, segment),
 //              nothing read from q and nothing written to o; the end states go to seg_PQ.
 //
 // Workgroup ids are dealt round-robin over the 8 XCDs, each with its own L2; the id is decoded so that all
 // waves of one (head, segment) sit on the same XCD and share the operands they all read through its L2.
-template <int D, int DEPTH, typename IO, bool MAP, int RS>
+template <int D, int DEPTH, typename IO, bool MAP>
 __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   constexpr int NB = D / 16;
-  constexpr int GROUPS = (D / 16) / RS;              // row groups per run
-  constexpr int WPH = MAP ? 2 * GROUPS : GROUPS;     // waves per (head, segment)
-  static_assert((D / 16) % RS == 0, "row groups");
+  constexpr int NSLAB = D / 16;
+  constexpr int WPH = MAP ? 2 * NSLAB : NSLAB;       // waves per (head, segment)
   const int xcd = blockIdx.x & 7;
   const int rest = blockIdx.x >> 3;
   const int hs = (rest / WPH) * 8 + xcd;             // head * n_seg + seg
@@ -377,8 +379,8 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   if (hs >= a.n_heads * a.n_seg) return;
   const int head = hs / a.n_seg;
   const int seg = hs - head * a.n_seg;
-  const bool p_run = MAP && grp >= GROUPS;           // identity rows, v = 0
-  const int row0 = (grp % GROUPS) * RS * 16;
+  const bool p_run = MAP && grp >= NSLAB;            // identity rows, v = 0
+  const int row0 = (grp % NSLAB) * 16;
   const int lane = threadIdx.x;
   const int c = lane & 15;
   const int g = lane >> 4;
@@ -397,30 +399,18 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
-  f4 st[RS][NB];
+  f4 st[NB];
   if constexpr (MAP) {
 #pragma unroll
-    for (int s = 0; s < RS; ++s)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          st[s][b][r] = (p_run && row0 + 16 * s + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+      for (int r = 0; r < 4; ++r) st[b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
   } else {
     const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * D * D
                               : (a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr);
 #pragma unroll
-    for (int s = 0; s < RS; ++s)
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        if (S0) {
-          const float4 x =
-              *reinterpret_cast<const float4*>(S0 + (row0 + 16 * s + c) * D + 16 * b + 4 * g);
-          st[s][b] = f4{x.x, x.y, x.z, x.w};
-        } else {
-          st[s][b] = f4{0, 0, 0, 0};
-        }
-      }
+    for (int b = 0; b < NB; ++b)
+      st[b] = S0 ? *reinterpret_cast<const f4*>(S0 + (row0 + c) * D + 16 * b + 4 * g) : f4{0, 0, 0, 0};
   }
 
   // operands of one block, in MFMA operand layout, straight from global memory
@@ -428,11 +418,11 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     f4 ka[NB], wa[NB];
     Raw4<IO> qa[NB];
     f4 za, nqa, ncg;
-    IO v[RS][4];
+    IO v[4];
   };
   // Addresses are a per-block uniform base (scalar registers) plus lane-constant 32-bit offsets, so that a
   // load costs no vector address arithmetic; only the ragged last block clamps its token rows.
-  const unsigned ko = static_cast<unsigned>(c * D + 4 * g);   // K^ row c; also q row c (elements)
+  const unsigned ko = static_cast<unsigned>(c * D + 4 * g);   // K^ row c
   const unsigned wo = static_cast<unsigned>(c * C + 4 * g);   // W row c of a 16-column slice; Z / NQ row c
   const unsigned vo = static_cast<unsigned>(4 * g * D + row0 + c);  // v and o: token 4g, column row0 + c
   auto load_ops = [&](int blk, Ops& o) {
@@ -453,11 +443,8 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + wo);
     o.ncg = *reinterpret_cast<const f4*>(sp + 3 * C * C + 4 * g);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const unsigned vr = static_cast<unsigned>(min(4 * g + r, lim) * D + row0 + c);
-#pragma unroll
-      for (int s = 0; s < RS; ++s) o.v[s][r] = vb[vr + 16 * s];
-    }
+    for (int r = 0; r < 4; ++r)
+      o.v[r] = vb[static_cast<unsigned>(min(4 * g + r, lim) * D + row0 + c)];
   };
 
   auto compute = [&](int blk, const Ops& cur) {
@@ -465,47 +452,40 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     IO* ob = oh + static_cast<size_t>(blk) * (C * D);
     // Rows of q past the end hold a copy of the last token (clamped loads); row t of the read-out depends on
     // row t of q only, and those rows are never stored, so they need no masking.
-    float qx[NB][4];
+    f4 ft, ot = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      float qx[4];
+      if constexpr (!MAP) cur.qa[b].unpack(qx);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        ft = mfma16(cur.ka[b][r], st[b][r], ft);
+        if constexpr (!MAP) ot = mfma16(qx[r], st[b][r], ot);
+      }
+    }
+    f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
     if constexpr (!MAP) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) cur.qa[b].unpack(qx[b]);
-    }
+      for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
+      if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
 #pragma unroll
-    for (int s = 0; s < RS; ++s) {
-      f4 ft, ot = f4{0, 0, 0, 0};
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[s][r]) : 0.0f;
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
+        for (int r = 0; r < 4; ++r) io_store(ob + vo + r * D, ot[r]);
+      } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          ft = mfma16(cur.ka[b][r], st[s][b][r], ft);
-          if constexpr (!MAP) ot = mfma16(qx[b][r], st[s][b][r], ot);
+          if (t0 + 4 * g + r < T) io_store(ob + vo + r * D, ot[r]);
         }
       }
-      f4 et = f4{0, 0, 0, 0};
-#pragma unroll
-      for (int r = 0; r < 4; ++r) et = mfma16(cur.za[r], ft[r], et);
-      if constexpr (!MAP) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
-        if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
-#pragma unroll
-          for (int r = 0; r < 4; ++r) io_store(ob + vo + r * D + 16 * s, ot[r]);
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (t0 + 4 * g + r < T) io_store(ob + vo + r * D + 16 * s, ot[r]);
-          }
-        }
-      }
-      const f4 ce = et * cur.ncg;
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) st[s][b] = mfma16(cur.wa[b][r], ce[r], st[s][b]);
     }
+    const f4 ce = et * cur.ncg;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st[b] = mfma16(cur.wa[b][r], ce[r], st[b]);
   };
 
   // Operands are fetched DEPTH blocks ahead into rotating register sets (the loop is unrolled by DEPTH + 1
@@ -541,12 +521,21 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   }
   if (out) {
 #pragma unroll
-    for (int s = 0; s < RS; ++s)
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-        *reinterpret_cast<float4*>(out + (row0 + 16 * s + c) * D + 16 * b + 4 * g) =
-            make_float4(st[s][b][0], st[s][b][1], st[s][b][2], st[s][b][3]);
+    for (int b = 0; b < NB; ++b)
+      *reinterpret_cast<f4*>(out + (row0 + c) * D + 16 * b + 4 * g) = st[b];
   }
+}
+
+template <int D, typename IO, bool MAP>
+hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  constexpr int kDepth = D <= 64 ? 2 : 1;  // register budget: three operand sets only fit up to d = 64
+  constexpr int kWph = (MAP ? 2 : 1) * (D / 16);
+  const int hs = a.n_heads * a.n_seg;
+  const unsigned grid = static_cast<unsigned>((hs + 7) / 8) * 8u * kWph;
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, MAP>), dim3(grid),
+                         dim3(64), params, 0, stream);
 }
 
 // ------------------------------------------------------------------------------- phase 2, shared operands
@@ -766,19 +755,6 @@ hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
                          dim3(a.n_heads * a.n_seg), dim3(64 * (D / 16) * (MAP ? 2 : 1)), params, 0, stream);
 }
 
-template <int D, typename IO, bool MAP, int RS>
-hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
-  ForwardArgs args = a;
-  void* params[] = {&args};
-  // register budget: three operand sets only fit a single slab per wave up to d = 64
-  constexpr int kDepth = (RS == 1 && D <= 64) ? 2 : 1;
-  constexpr int kWph = (MAP ? 2 : 1) * (D / 16) / RS;
-  const int hs = a.n_heads * a.n_seg;
-  const unsigned grid = static_cast<unsigned>((hs + 7) / 8) * 8u * kWph;
-  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, MAP, RS>), dim3(grid),
-                         dim3(64), params, 0, stream);
-}
-
 // Phase 1, 1b and 2 over every (head, segment) of `a`.
 template <int D, int NW, typename IO>
 hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
@@ -804,7 +780,7 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   const bool shared = hs >= 256;
   auto rows = [&](auto map_tag) -> hipError_t {
     constexpr bool kMap = decltype(map_tag)::value;
-    return shared ? launch_s_rows_lds<D, IO, kMap>(a, stream) : launch_s_rows<D, IO, kMap, 1>(a, stream);
+    return shared ? launch_s_rows_lds<D, IO, kMap>(a, stream) : launch_s_rows<D, IO, kMap>(a, stream);
   };
   if (a.n_seg > 1) {
     // the state of S at the segment boundaries: per-segment affine maps, then their composition
