@@ -822,14 +822,14 @@ hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream
 }
 
 // ---------------------------------------------------------------------------------- time-parallel mode
-// Segments are sized so that heads x segments gives every compute unit about four workgroups, but never shorter than 32
-// blocks (512 tokens): the map pass costs two extra sweeps of S whatever the segment count.
+// Segments are sized so that heads x segments gives every compute unit about four workgroups, but never
+// shorter than 16 blocks (256 tokens): the map pass costs two extra sweeps of S whatever the segment count.
 SegmentPlan plan_segments(int n_heads, int T, int requested) {
   const int nblk = (T + C - 1) / C;
   int ns = requested;
   if (ns <= 0) {
     const int by_chip = 1024 / (n_heads < 1 ? 1 : n_heads);
-    const int by_length = nblk / 32;
+    const int by_length = nblk / 16;
     ns = by_chip < by_length ? by_chip : by_length;
   }
   if (ns > 256) ns = 256;

@@ -149,9 +149,9 @@ def test_time_parallel_workspace_follows_the_segment_plan():
     big = vla.vla_forward_workspace_bytes(1, 1, 16 * 4096, d, d, vla.VLA_F32,
                                           mode=vla.MODE_TIME_PARALLEL, segments=100000)
     assert big == 4096 * (2 * 16 * d + 784) * 4 + 256 * d * d * 24
-    # the library's own choice: about 1024 (head, segment) pairs, segments of at least 32 blocks
+    # the library's own choice: about 1024 (head, segment) pairs, segments of at least 16 blocks
     auto = tp(0)
-    assert auto == two + B * H * 16 * d * d * 24          # 512 blocks / 32 = 16 < 1024 / 16 heads = 64
+    assert auto == two + B * H * 32 * d * d * 24          # 512 blocks / 16 = 32 < 1024 / 16 heads = 64
 
 
 def test_torch_front_end_refuses_cpu_tensors():

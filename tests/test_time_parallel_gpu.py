@@ -20,7 +20,7 @@ TP = 4  # VLA_MODE_TIME_PARALLEL
     (32, 200, 256),     # more segments asked for than blocks: one block per segment
     (128, 513, 2),      # second segment ends in a one-token block
     (128, 300, 7),
-    (64, 4096, 0),      # the library's own choice (8 segments for 6 heads)
+    (64, 4096, 0),      # the library's own choice (16 segments for 6 heads)
     (32, 2048, 0),
     (64, 16, 4),        # a single block: degenerates to one segment
 ])
