@@ -159,8 +159,10 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
  *   A      [B, H, d_k, d_k] float32 row-major, updated in place (required; symmetric positive definite)
  *   o      [B, H, d_v]      io_dtype, written; must not overlap any input
  *   d_k == d_v in {16, 32, 64, 96, 128}
- *   opts   host pointer or NULL; only eps is used.  The optional lines of Algorithm 1 are not available
- *          here (VLA_ERR_UNSUPPORTED if any is set): use vla_forward with T = 1 for those.
+ *   opts   host pointer or NULL.  eps and the optional lines of Algorithm 1 are honoured as in vla_forward
+ *          with T = 1: u [B, H, d_k] (io_dtype) with u_scale, the identity refresh (this call is step
+ *          step_offset + 1 of the schedule), normalise_output with zkey0 / zkey_T [B, H, d_k] (may alias),
+ *          feature_map.  lambda0, mode and segments are not used.
  *   stream a hipStream_t passed as void*; NULL is the default stream
  *
  * All device pointers must be 16-byte aligned.  Asynchronous, allocates nothing.  Returns a vla_status.

@@ -128,9 +128,12 @@ def vla_decode_step_raw(q, k, v, S, A, o, B, H, d_k, d_v, io_dtype, *, eps=None,
                                               io_dtype, ctypes.byref(op), n(stream)))
 
 
-def vla_decode_step(q, k, v, S, A, *, eps=None, stream=None):
+def vla_decode_step(q, k, v, S, A, *, eps=None, stream=None, u=None, u_scale=None, refresh_period=None,
+                    refresh_eta=None, step_offset=None, normalise_output=None, feature_map=None, zkey=None):
     """One token for every head: q, k, v [B,H,d] on the GPU (float32 or bfloat16); S, A [B,H,d,d] float32 are
-    updated in place.  Returns o [B,H,d]."""
+    updated in place, and so is `zkey` [B,H,d] float32 (the running key sum of the normalised read-out) when
+    given.  The optional lines of Algorithm 1 are switched on as in vla_forward; this call is step
+    step_offset + 1 of the refresh schedule.  Returns o [B,H,d]."""
     import torch
 
     if not (q.is_cuda and k.is_cuda and v.is_cuda and S.is_cuda and A.is_cuda):
@@ -145,16 +148,26 @@ def vla_decode_step(q, k, v, S, A, *, eps=None, stream=None):
         raise ValueError("expected q,k [B,H,d_k] and v [B,H,d_v] of one dtype")
     B, H, dk = q.shape
     dv = v.shape[-1]
-    for name, x, shape in (("S", S, (B, H, dv, dk)), ("A", A, (B, H, dk, dk))):
-        if x.dtype != torch.float32 or tuple(x.shape) != shape or not x.is_contiguous() or x.device != q.device:
+    for name, x, shape in (("S", S, (B, H, dv, dk)), ("A", A, (B, H, dk, dk)), ("zkey", zkey, (B, H, dk))):
+        if x is not None and (x.dtype != torch.float32 or tuple(x.shape) != shape or not x.is_contiguous()
+                              or x.device != q.device):
             raise ValueError(f"{name} must be a contiguous float32 tensor of shape {shape} on {q.device}")
+    if u is not None and (u.dtype != q.dtype or tuple(u.shape) != tuple(q.shape) or u.device != q.device):
+        raise ValueError("u must match q in dtype, shape and device")
     q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+    u = None if u is None else u.contiguous()
+    p = lambda x: None if x is None else x.data_ptr()
     with torch.cuda.device(q.device):
         o = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
         st = stream if stream is not None else torch.cuda.current_stream(q.device)
         handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
+        extra = dict(u=p(u), u_scale=u_scale, refresh_period=refresh_period, refresh_eta=refresh_eta,
+                     step_offset=step_offset,
+                     normalise_output=None if normalise_output is None else int(bool(normalise_output)),
+                     feature_map=None if feature_map is None else int(bool(feature_map)),
+                     zkey0=p(zkey), zkey_T=p(zkey))
         rc = vla_decode_step_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), S.data_ptr(), A.data_ptr(),
-                                 o.data_ptr(), B, H, dk, dv, io, eps=eps, stream=handle)
+                                 o.data_ptr(), B, H, dk, dv, io, eps=eps, stream=handle, **extra)
     if rc != 0:
         raise VlaError(rc, status_string(rc))
     return o

@@ -87,8 +87,9 @@ hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* 
 hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t stream);
 
 
-// One decode step for every head, state updated in place (vla_decode.hip).
+// One decode step for every head, state updated in place (vla_decode.hip).  `opt` carries eps and the
+// optional lines of Algorithm 1 (u, refresh schedule, read-out normaliser, feature map, key sum).
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
-                         int n_heads, int d, int io_dtype, float eps, hipStream_t stream);
+                         int n_heads, int d, int io_dtype, const ForwardArgs& opt, hipStream_t stream);
 
 }  // namespace vla

@@ -71,6 +71,15 @@ struct DecodeArgs {
   float* A;
   void* o;
   float eps;
+  // the optional lines of Algorithm 1 (decode_general_kernel only)
+  const void* u;
+  float u_scale;
+  int refresh;          // 1: this step adds refresh_eta to the diagonal of A
+  float refresh_eta;
+  int normalise_output;
+  int feature_map;
+  const float* zkey0;
+  float* zkey_T;
 };
 
 template <int D, typename IO>
@@ -152,19 +161,145 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
   }
 }
 
+// The same step with every line of Algorithm 1 switchable.  With u~ the raw penalty direction (the key itself
+// when none is supplied), k the key after the optional feature map, n_k = max(||k||, eps), n_u = max(||u~||, eps),
+// su = u_scale / n_u (1 / n_k without a supplied u):
+//   z' = A u~, y' = A k           (one pass over the rows of A, two dot products each)
+//   delta = max(1 + su^2 (u~ . z'), eps);   A -= su^2 z' z'^T / delta;   A += eta I on a refresh step
+//   a = A_t k^ = (y' - z' su^2 (u~ . y') / delta) / n_k  (+ eta k^);   alpha^ = a / max(||a||, eps)
+//   e = v - (S k) / n_k;  S += e alpha^^T;  o = S_old q + e (alpha^ . q)
+//   zkey += k;  o /= max(q . zkey, eps) when the read-out is normalised (eq. (output))
+__device__ __forceinline__ float elu1d(float x) { return x > 0.0f ? x + 1.0f : expf(x); }
+
+template <int D, typename IO>
+__global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_general_kernel(DecodeArgs a) {
+  constexpr int EPL = D / 16;
+  constexpr int ROWS_W = D >= 32 ? 32 : D;
+  constexpr int NP = ROWS_W / 4;
+  __shared__ float zs[D];
+  __shared__ float ys[D];
+
+  const int head = blockIdx.x;
+  const int w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int col0 = c * EPL;
+  const int row0 = ROWS_W * w + g;
+
+  float* Ah = a.A + static_cast<size_t>(head) * D * D;
+  float* Sh = a.S + static_cast<size_t>(head) * D * D;
+  const size_t hv = static_cast<size_t>(head) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + hv;
+  const IO* kh = static_cast<const IO*>(a.k) + hv;
+  const IO* vh = static_cast<const IO*>(a.v) + hv;
+  IO* oh = static_cast<IO*>(a.o) + hv;
+
+  float Ar[NP][EPL], Sr[NP][EPL];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) load_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
+#pragma unroll
+  for (int p = 0; p < NP; ++p) load_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
+  float kk[EPL], qq[EPL], uu[EPL], zk[EPL], vr[NP];
+  load_io<EPL>(kh + col0, kk);
+  load_io<EPL>(qh + col0, qq);
+  if (a.feature_map) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) { kk[e] = elu1d(kk[e]); qq[e] = elu1d(qq[e]); }
+  }
+  if (a.u != nullptr) {
+    load_io<EPL>(static_cast<const IO*>(a.u) + hv + col0, uu);
+  } else {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) uu[e] = kk[e];
+  }
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) zk[e] = (a.zkey0 ? a.zkey0[hv + col0 + e] : 0.0f) + kk[e];   // key sum after this token
+#pragma unroll
+  for (int p = 0; p < NP; ++p) vr[p] = widen(vh[row0 + 4 * p]);
+
+  const float eps = a.eps;
+  const float inv_nk = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(kk, kk))), eps);
+  const float su = (a.u != nullptr ? a.u_scale : 1.0f) / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(uu, uu))), eps);
+  const float su2 = su * su;
+
+  float zr[NP];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    zr[p] = row_sum16(dot_seg<EPL>(Ar[p], uu));
+    const float yr = row_sum16(dot_seg<EPL>(Ar[p], kk));
+    if (c == 0) {
+      zs[row0 + 4 * p] = zr[p];
+      ys[row0 + 4 * p] = yr;
+    }
+  }
+  __syncthreads();
+  float zc[EPL], yc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    zc[e] = zs[col0 + e];
+    yc[e] = ys[col0 + e];
+  }
+  const float uz = row_sum16(dot_seg<EPL>(uu, zc));
+  const float uy = row_sum16(dot_seg<EPL>(uu, yc));
+  const float delta = fmaxf(1.0f + su2 * uz, eps);
+  const float cz = su2 / delta;
+  const float eta = a.refresh ? a.refresh_eta : 0.0f;
+  float al[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) al[e] = (yc[e] - zc[e] * cz * uy) * inv_nk + eta * kk[e] * inv_nk;   // a = A_t k^
+  const float inv_an = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(al, al))), eps);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) al[e] *= inv_an;                                                       // alpha^
+  const float aq = row_sum16(dot_seg<EPL>(al, qq));
+  const float qz = row_sum16(dot_seg<EPL>(qq, zk));
+  const float onorm = a.normalise_output ? 1.0f / fmaxf(qz, eps) : 1.0f;
+
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const float f = -zr[p] * cz;
+    const int row = row0 + 4 * p;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      Ar[p][e] = fmaf(f, zc[e], Ar[p][e]);
+      Ar[p][e] += (row == col0 + e) ? eta : 0.0f;
+    }
+    store_seg<EPL>(Ah + row * D + col0, Ar[p]);
+  }
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const float sk = row_sum16(dot_seg<EPL>(Sr[p], kk)) * inv_nk;
+    const float sq = row_sum16(dot_seg<EPL>(Sr[p], qq));
+    const float er = vr[p] - sk;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) Sr[p][e] = fmaf(er, al[e], Sr[p][e]);
+    store_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
+    if (c == 0) io_store(oh + row0 + 4 * p, fmaf(er, aq, sq) * onorm);
+  }
+  if (a.zkey_T != nullptr && w == 0 && g == 0) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) a.zkey_T[hv + col0 + e] = zk[e];
+  }
+}
+
 template <int D, typename IO>
 hipError_t launch(const DecodeArgs& a, int n_heads, hipStream_t stream) {
   DecodeArgs args = a;
   void* params[] = {&args};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&decode_kernel<D, IO>), dim3(n_heads),
-                         dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
+  const bool general = a.u != nullptr || a.refresh != 0 || a.normalise_output != 0 || a.feature_map != 0 ||
+                       a.zkey0 != nullptr || a.zkey_T != nullptr;
+  const void* fn = general ? reinterpret_cast<const void*>(&decode_general_kernel<D, IO>)
+                           : reinterpret_cast<const void*>(&decode_kernel<D, IO>);
+  return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
 }
 
 }  // namespace
 
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
-                         int n_heads, int d, int io_dtype, float eps, hipStream_t stream) {
-  const DecodeArgs a{q, k, v, S, A, o, eps};
+                         int n_heads, int d, int io_dtype, const ForwardArgs& opt, hipStream_t stream) {
+  const bool refresh = opt.refresh_period > 0 && ((opt.step_offset + 1) % opt.refresh_period) == 0;
+  const DecodeArgs a{q, k, v, S, A, o, opt.eps, opt.u, opt.u_scale, refresh ? 1 : 0, opt.refresh_eta,
+                     opt.normalise_output, opt.feature_map, opt.zkey0, opt.zkey_T};
   const bool bf = io_dtype == 1;
   switch (d) {
     case 16: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);

@@ -105,7 +105,7 @@ def decode_call(**kw):
     (dict(S=0), 1), (dict(A=0), 1), (dict(o=0), 1), (dict(k=0), 1),     # the state is required here
     (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
     (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=64), 2),
-    (dict(refresh_period=20), 2), (dict(normalise_output=1), 2),        # options: only through vla_forward
+    (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1), (dict(refresh_period=-2), 1),   # option arguments are checked too
 ])
 def test_decode_step_host_side_validation(kw, status):
     assert decode_call(**kw) == status

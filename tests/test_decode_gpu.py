@@ -84,3 +84,53 @@ def test_decode_step_degenerate_tokens():
     assert np.array_equal(to_np(S)[0, 0], S0[0, 0]) and np.array_equal(to_np(A)[0, 0], A0[0, 0])
     assert slab_rel_err(to_np(o)[:, :, None], ref["o"], 2) <= TOL["f32"]
     assert slab_rel_err(to_np(S), ref["S_T"], 2) <= TOL["f32"] and slab_rel_err(to_np(A), ref["A_T"], 2) <= TOL["f32"]
+
+
+OPTION_SETS = {
+    "u_scaled": dict(u=True, u_scale="rsqrt_d"),
+    "refresh": dict(refresh_period=5, refresh_eta=1e-3),
+    "normalised_elu": dict(normalise_output=1, feature_map=1),
+    "algorithm1": dict(u=True, u_scale="rsqrt_d", refresh_period=4, refresh_eta=1e-3, normalise_output=1,
+                       feature_map=1),
+}
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name", sorted(OPTION_SETS))
+@pytest.mark.parametrize("d", [16, 64, 96, 128])
+def test_decode_steps_with_the_optional_lines_of_algorithm_1(d, name, dtype):
+    """A chain of decode calls with options (refresh phase and key sum carried from call to call) against the
+    oracle run over the same tokens as one sequence with the same options."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, steps = 2, 2, 17
+    opt = dict(OPTION_SETS[name])
+    q, k, v = vla_inputs.gaussian_qkv(B, H, steps, d, seed=5000 + d)
+    u = np.random.default_rng(d).standard_normal((B, H, steps, d)).astype(np.float32) if opt.pop("u", False) else None
+    if opt.get("u_scale") == "rsqrt_d":
+        opt["u_scale"] = d ** -0.5
+    if dtype == "bf16":
+        q, k, v = (vla_inputs.round_to_bf16(x) for x in (q, k, v))
+        u = None if u is None else vla_inputs.round_to_bf16(u)
+    ref = oracle.forward(q, k, v, lambda0=0.1, u=u, **opt)
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tq, tk, tv = (torch.from_numpy(x).to(dev).to(tdt) for x in (q, k, v))
+    tu = None if u is None else torch.from_numpy(u).to(dev).to(tdt)
+    S = torch.zeros(B, H, d, d, device=dev)
+    A = (torch.eye(d, device=dev) * (1.0 / np.float32(0.1))).repeat(B, H, 1, 1).contiguous()
+    zkey = torch.zeros(B, H, d, device=dev) if opt.get("normalise_output") else None
+    outs = []
+    for t in range(steps):
+        outs.append(vla.vla_decode_step(tq[:, :, t].contiguous(), tk[:, :, t].contiguous(),
+                                        tv[:, :, t].contiguous(), S, A, step_offset=t, zkey=zkey,
+                                        u=None if tu is None else tu[:, :, t].contiguous(), **opt))
+    torch.cuda.synchronize()
+    o = to_np(torch.stack(outs, dim=2))
+    errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(to_np(S), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A), ref["A_T"], 2))
+    if zkey is not None:
+        errs["zkey"] = slab_rel_err(to_np(zkey), ref["zkey_T"], 1)
+    assert max(errs.values()) <= TOL[dtype], errs
