@@ -212,7 +212,7 @@ __global__ void __launch_bounds__(D + DV) scan_kernel(ForwardArgs a) {
 //   a = A_t k^ = y'/n_k - z' su^2 (u~ . y') / (n_k delta)  (+ eta k^)       (A symmetric)
 //   alpha^ = a / max(||a||, eps);  e = v - (S k)/n_k;  S += e alpha^^T;  o = S_{t-1} q + e (alpha^ . q)
 //   zkey += k;  o /= max(q . zkey, eps)  when the read-out is normalised (eq. (output))
-// Two reduction rounds per token (a needs delta and u~ . y' first), hence two barriers per token.
+// Two reductions per token (a needs delta and u~ . y' first), hence two barriers per token.
 constexpr int kTileG = 16;
 
 __device__ __forceinline__ float elu1(float x) { return x > 0.0f ? x + 1.0f : expf(x); }
@@ -309,7 +309,7 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
       const float mv = m0 + m1;
       const float rv = r0 + r1;
 
-      // ---- round 1: k.k, u~.u~, u~.z', u~.y', q.zkey
+      // ---- first reduction: k.k, u~.u~, u~.z', u~.y', q.zkey
       float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
       float ki = 0.f;
       if (role == 0) {
@@ -349,7 +349,7 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
       const float eta = refresh ? a.refresh_eta : 0.0f;
       const float4* z4 = reinterpret_cast<const float4*>(&zb[par][0]);
 
-      // ---- round 2: a = A_t k^ on the A threads; ||a||^2, a.q
+      // ---- second reduction: a = A_t k^ on the A threads; ||a||^2, a.q
       float t2[2] = {0.f, 0.f};
       if (role == 0) {
         const float ai = (rv - mv * cz * uy) * inv_nk + eta * ki * inv_nk;
