@@ -410,7 +410,9 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         if (t < T) {
           const unsigned ooff = static_cast<unsigned>(t * D + vcol);
 #pragma unroll
-          for (int jn = 0; jn < NJ; ++jn) io_store(oh + ooff + 16 * jn, ot[jn][r]);
+          for (int jn = 0; jn + 1 < NJ; jn += 2)
+            io_store2(oh + ooff + 16 * jn, oh + ooff + 16 * jn + 16, ot[jn][r], ot[jn + 1][r]);
+          if (NJ % 2 == 1) io_store(oh + ooff + 16 * (NJ - 1), ot[NJ - 1][r]);
         }
       }
     }

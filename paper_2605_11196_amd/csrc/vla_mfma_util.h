@@ -78,6 +78,19 @@ __device__ __forceinline__ float io_load(const float* p) { return *p; }
 __device__ __forceinline__ float io_load(const uint16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void io_store(float* p, float x) { *p = x; }
 __device__ __forceinline__ void io_store(uint16_t* p, float x) { *p = f32_to_bf16_rne(x); }
+// Two values to two addresses.  For bf16 the pair is rounded (to nearest even) by one packed hardware
+// conversion and the halves are stored separately.
+__device__ __forceinline__ void io_store2(float* p0, float* p1, float x0, float x1) {
+  *p0 = x0;
+  *p1 = x1;
+}
+__device__ __forceinline__ void io_store2(uint16_t* p0, uint16_t* p1, float x0, float x1) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  typedef float fl2 __attribute__((ext_vector_type(2)));
+  const uint32_t u = __builtin_bit_cast(uint32_t, __builtin_convertvector(fl2{x0, x1}, bf2));
+  *p0 = static_cast<uint16_t>(u & 0xffffu);
+  *p1 = static_cast<uint16_t>(u >> 16);
+}
 
 // A staged row segment of EPT consecutive elements, held in its raw (packed) form until it is used.
 template <typename IO, int EPT> struct RawRow;
