@@ -130,10 +130,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   // normalise this thread's share of the keys of the block starting at t0 and put K^, Q into LDS half `buf`
   auto stage = [&](int t0, int buf) {
     float kx[EPT];
+    const bool ragged = t0 + C > T;   // uniform: only the last block can hold rows past the end
     const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
     kpre.unpack(kx);
+    if (ragged) {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+    }
     float ss = 0.0f;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
@@ -146,8 +149,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
     }
     qpre.unpack(kx);
+    if (ragged) {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+    }
 #pragma unroll
     for (int e = 0; e < EPT; e += 4) {
       *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
@@ -183,7 +188,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
     for (int jn = 0; jn < NJ; ++jn)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? -widen(vpre[jn][r]) : 0.0f;
+      for (int r = 0; r < 4; ++r) ft[jn][r] = neg_widen(vpre[jn][r]);
+    if (t0 + C > T) {  // uniform: rows past the end of the sequence are zero tokens
+#pragma unroll
+      for (int jn = 0; jn < NJ; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? ft[jn][r] : 0.0f;
+    }
     if (t0 + C < T) load_v(t0 + C);
     VLA_STAMP(1);
 
@@ -342,9 +353,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) m[s4 + e] = lr[e];
       }
-      float dl = m[0];
-#pragma unroll
-      for (int s = 1; s < C; ++s) dl = (cc == s) ? m[s] : dl;  // L_cc
+      const float dl = Lrs[c * LT + c];  // L_cc
       float wn2 = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];

@@ -135,5 +135,11 @@ template <int EPT> struct RawRow<uint16_t, EPT> {
 };
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t x) { return bf16_to_f32(x); }
+// -x widened to float32: for bf16 the shift and the sign flip are one shift-and-add (adding the top bit is
+// flipping it).
+__device__ __forceinline__ float neg_widen(float x) { return -x; }
+__device__ __forceinline__ float neg_widen(uint16_t x) {
+  return __uint_as_float((static_cast<uint32_t>(x) << 16) + 0x80000000u);
+}
 
 }  // namespace vla
