@@ -140,9 +140,18 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     float ss = 0.0f;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
+    // the TPR = 16 threads of a token row are one DPP row; 1 / max(||k||, eps) = rsqrt(max(||k||^2, eps^2)),
+    // hardware reciprocal square root refined by one Newton step
+    static_assert(TPR == 16 || TPR < 16, "a token row within one DPP row");
+    if constexpr (TPR == 16) {
+      ss = row_sum16(ss);
+    } else {
 #pragma unroll
-    for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-    const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
+      for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    }
+    const float sm = fmaxf(ss, eps * eps);
+    float rn = __builtin_amdgcn_rsqf(sm);
+    rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f);
 #pragma unroll
     for (int e = 0; e < EPT; e += 4) {
       *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg + e]) =
@@ -357,9 +366,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       float wn2 = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
-      const float rdl = 1.0f / dl;
-      const float an = sqrtf(wn2) * rdl;       // ||A_t k^_t|| = ||w_t|| / L_tt
-      const float cs = rdl / fmaxf(an, eps);   // alpha^_t = c_t w_t
+      // hardware reciprocal and square root (1 ulp): c_t only scales the write direction
+      const float rdl = __builtin_amdgcn_rcpf(dl);
+      const float an = __builtin_amdgcn_sqrtf(wn2) * rdl;                // ||A_t k^_t|| = ||w_t|| / L_tt
+      const float cs = rdl * __builtin_amdgcn_rcpf(fmaxf(an, eps));      // alpha^_t = c_t w_t
       if (g == 0) cvec[c] = -cs;  // the residual tiles carry -E, see below
       // Z = (I + strict_lower(L) diag(c))^{-1}: lane c holds column c (rows of L live in lanes 0-31)
       float nm[C], Zr[C];
