@@ -300,8 +300,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
       for (int t = 0; t < C; ++t) {
         const float p = readlane(m[t], t);  // pivot = delta_t >= 1
-        float ri = __builtin_amdgcn_rsqf(p);
-        ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);  // one Newton step on 1/sqrt(p)
+        const float ri = __builtin_amdgcn_rsqf(p);  // 1 ulp; L only has to satisfy L L^T = I + G to rounding
         const float li = m[t] * ri;  // lanes <32: column t of L;  lanes >=32: row t of L^{-1}, final
         m[t] = li;
 #pragma unroll
