@@ -139,7 +139,10 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
       for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
 #pragma unroll
       for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      const float rn = 1.0f / fmaxf(sqrtf(ss), eps);
+      // 1 / max(||k||, eps) = rsqrt(max(||k||^2, eps^2)): hardware reciprocal square root, one Newton step
+      const float sm = fmaxf(ss, eps * eps);
+      float rn = __builtin_amdgcn_rsqf(sm);
+      rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f);
       float* kg = KH + static_cast<size_t>(t0 + srow) * D + sseg;
 #pragma unroll
       for (int e = 0; e < EPT; e += 4) {
@@ -220,8 +223,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
 #pragma unroll
       for (int t = 0; t < C; ++t) {
         const float p = readlane(m[t], t);
-        float ri = __builtin_amdgcn_rsqf(p);
-        ri = ri * fmaf(-0.5f * p * ri, ri, 1.5f);
+        const float ri = __builtin_amdgcn_rsqf(p);  // 1 ulp; L only has to satisfy L L^T = I + G to rounding
         const float li = m[t] * ri;
         m[t] = li;
 #pragma unroll
@@ -325,9 +327,10 @@ __global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nbl
   float dl = m[0];
 #pragma unroll
   for (int s = 1; s < C; ++s) dl = (c == s) ? m[s] : dl;
-  const float rdl = 1.0f / dl;
-  const float an = sqrtf(wn2) * rdl;
-  const float cs = rdl / fmaxf(an, eps);
+  // hardware reciprocal and square root (1 ulp): c_t only scales the write direction
+  const float rdl = __builtin_amdgcn_rcpf(dl);
+  const float an = __builtin_amdgcn_sqrtf(wn2) * rdl;
+  const float cs = rdl * __builtin_amdgcn_rcpf(fmaxf(an, eps));
 
   float nm[C], Zr[C];
   float ncs = -cs;
