@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # same counter's reading for a plain copy kernel of known size); see profiles/. None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # (workload, T, resolved mode): bytes per launch -- profiles/chunk_kernel_large_batch_hbm_traffic.txt
-    ("large_batch", 8192, 2): 17049609 * 1024,
+    ("large_batch", 8192, 2): 17049094 * 1024,
 }
 
 
