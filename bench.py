@@ -131,7 +131,7 @@ def main():
 
     c = dict(vla_inputs.CONFIGS[args.workload])
     if args.workload == "long_context":
-        c["T"] = args.T or 65536
+        c["T"] = args.T or 131072
     elif args.T:
         c["T"] = args.T
     if args.B:
