@@ -81,6 +81,43 @@ def test_segment_count_only_changes_rounding():
             assert slab_rel_err(x, y, nd) <= 2e-5, segments
 
 
+@pytest.mark.parametrize("heads", [3, 64])
+def test_state_outputs_may_alias_inputs_or_be_null(heads):
+    """S_T / A_T written over S0 / A0 (the boundary kernels have read them by then) and left out altogether;
+    few heads take the per-wave S kernels, 64 heads x 4 segments the shared-operand ones."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    d, T, seg = 64, 200, 4
+    dev = torch.device("cuda:0")
+    q, k, v = (torch.from_numpy(x).to(dev) for x in vla_inputs.gaussian_qkv(1, heads, T, d, seed=400))
+    S0 = torch.randn((1, heads, d, d), device=dev)
+    A0 = torch.eye(d, device=dev).expand(1, heads, d, d).contiguous() * 2.0
+    o_ref, S_ref, A_ref = vla.vla_forward(q, k, v, S0, A0, mode=TP, segments=seg)
+    S_al, A_al = S0.clone(), A0.clone()
+    o = torch.empty_like(q)
+    need = vla.vla_forward_workspace_bytes(1, heads, T, d, d, vla.VLA_F32, mode=TP, segments=seg)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    st = torch.cuda.current_stream().cuda_stream
+    args = (1, heads, T, d, d, vla.VLA_F32)
+    kw = dict(mode=TP, segments=seg, workspace=ws.data_ptr(), workspace_bytes=need, stream=st)
+    rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), S_al.data_ptr(), A_al.data_ptr(),
+                             o.data_ptr(), S_al.data_ptr(), A_al.data_ptr(), *args, **kw)
+    assert rc == 0
+    o2 = torch.empty_like(q)
+    rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), S0.data_ptr(), A0.data_ptr(),
+                             o2.data_ptr(), 0, 0, *args, **kw)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(S_al, S_ref) and torch.equal(A_al, A_ref)
+    assert torch.equal(o2, o_ref)
+    ref = oracle.forward(q.cpu().numpy(), k.cpu().numpy(), v.cpu().numpy(), S0.cpu().numpy(), A0.cpu().numpy())
+    assert slab_rel_err(o.cpu().numpy(), ref["o"], 2) <= TOL["f32"]
+    assert slab_rel_err(S_al.cpu().numpy(), ref["S_T"], 2) <= TOL["f32"]
+    assert slab_rel_err(A_al.cpu().numpy(), ref["A_T"], 2) <= TOL["f32"]
+
+
 def test_workspace_and_option_checks():
     import torch
 
