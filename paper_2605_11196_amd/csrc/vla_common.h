@@ -59,7 +59,7 @@ hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hip
 hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
-// Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 64 and 128.
+// Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 32, 64 and 128.
 bool chunk_supported(int d);
 hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
