@@ -18,8 +18,8 @@ namespace {
 
 template <int N> struct Vec;
 template <> struct Vec<1> { using type = float; };
-template <> struct Vec<2> { using type = float2; };
-template <> struct Vec<4> { using type = float4; };
+template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
 // EPL consecutive floats <-> registers, in the widest pieces the alignment of d/16-float segments allows
 template <int EPL>
