@@ -475,8 +475,8 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
-#pragma unroll
-        for (int r = 0; r < 4; ++r) io_store(ob + vo + r * D, ot[r]);
+        io_store2(ob + vo, ob + vo + D, ot[0], ot[1]);
+        io_store2(ob + vo + 2 * D, ob + vo + 3 * D, ot[2], ot[3]);
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -680,8 +680,8 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
       IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
-#pragma unroll
-        for (int r = 0; r < 4; ++r) io_store(ob + r * D, ot[r]);
+        io_store2(ob, ob + D, ot[0], ot[1]);
+        io_store2(ob + 2 * D, ob + 3 * D, ot[2], ot[3]);
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
