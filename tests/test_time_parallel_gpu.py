@@ -71,6 +71,23 @@ def test_recall_workload_with_zero_and_repeated_directions():
     check_parity(q, k, v, lambda0=c["lambda0"], mode=TP, segments=8)
 
 
+def test_result_is_deterministic():
+    """Every reduction has a fixed order (Gram partials summed in wave order, no floating-point atomics): two
+    calls on the same inputs agree bit for bit, for the per-wave and for the shared-operand S kernels."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    dev = torch.device("cuda:0")
+    for heads, T, seg in ((3, 777, 5), (64, 333, 4)):
+        q, k, v = (torch.from_numpy(x).to(dev) for x in vla_inputs.gaussian_qkv(1, heads, T, 64, seed=T))
+        a = vla.vla_forward(q, k, v, mode=TP, segments=seg)
+        b = vla.vla_forward(q, k, v, mode=TP, segments=seg)
+        torch.cuda.synchronize()
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
 def test_segment_count_only_changes_rounding():
     d, T = 64, 1536
     q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=31)
