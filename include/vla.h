@@ -42,7 +42,7 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
  *   AUTO     : the library picks: SCAN when an option of Algorithm 1 is switched on or the head
- *              size has no block kernel; TIME_PARALLEL for B*H <= 64 and T >= 1024 if the caller
+ *              size has no block kernel; TIME_PARALLEL for B*H <= 64 (128 below d = 128) and T >= 1024 if the caller
  *              passed the workspace vla_forward_workspace_bytes() asks for (else CHUNKED);
  *              CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
