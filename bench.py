@@ -25,8 +25,9 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by the
 # same counter's reading for a plain copy kernel of known size); see profiles/. None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # (workload, T, resolved mode): bytes per launch -- profiles/chunk_kernel_large_batch_hbm_traffic.txt
-    ("large_batch", 8192, 2): 17049094 * 1024,
+    # (B, H, T, d_h, io dtype, resolved mode): bytes per launch --
+    # profiles/chunk_kernel_large_batch_hbm_traffic.txt
+    (64, 32, 8192, 128, "bf16", 2): 17049094 * 1024,
 }
 
 
@@ -230,7 +231,7 @@ def main():
             "peak": PEAK_FP32_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved_tflops / PEAK_FP32_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T, resolved)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((B, H, T, d, dtype, resolved)),
             "kernel_ms": avg_launch_s * 1e3,
             "algorithmic_flop_per_launch": flops,
             "algorithmic_bytes_per_launch": io_bytes,
