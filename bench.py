@@ -47,6 +47,10 @@ def parse_args():
     ap.add_argument("--decode", action="store_true",
                     help="time vla_decode_step (one token for every head of the workload, state in place) "
                          "instead of vla_forward; the roofline is then the HBM one")
+    ap.add_argument("--options", default="none", choices=["none", "paper"],
+                    help="'paper': switch on every optional line of Algorithm 1 (separate penalty directions u "
+                         "with u_scale = 1/sqrt(d_h), identity refresh every 20 steps, normalised read-out, "
+                         "ELU+1 features); the flop count per head-token is then 12 d^2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB -> 1 GiB elementwise copy kernel (calibration of the "
@@ -157,21 +161,29 @@ def main():
         q, k, v = (torch.from_numpy(x).to(dev)
                    for x in vla_inputs.gaussian_qkv(B, H, T, d, c["seed"], c["std"]))
 
+    extra = {}
+    if args.options == "paper":
+        gen_u = torch.Generator(device=dev)
+        gen_u.manual_seed(c["seed"] + 1000)
+        u = torch.randn(B, H, T, d, device=dev, generator=gen_u).to(tdt)
+        extra = dict(u=u.data_ptr(), u_scale=d ** -0.5, refresh_period=20, refresh_eta=1e-3,
+                     normalise_output=1, feature_map=1)
     o = torch.empty_like(v)
     S_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
     A_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
     mode = args.mode
     need = vla.vla_forward_workspace_bytes(B, H, T, d, d, io, lambda0=c["lambda0"], mode=mode,
-                                           segments=args.segments)
+                                           segments=args.segments, **extra)
     ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
-    resolved = vla.resolve_mode(B, H, T, d, d, io, mode=mode)
+    resolved = vla.resolve_mode(B, H, T, d, d, io, mode=mode, **extra)
     stream = torch.cuda.current_stream(dev)
 
     def step():
         rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(),
                                  S_T.data_ptr(), A_T.data_ptr(), B, H, T, d, d, io,
                                  lambda0=c["lambda0"], mode=mode, workspace=ws.data_ptr(),
-                                 workspace_bytes=need, stream=stream.cuda_stream, segments=args.segments)
+                                 workspace_bytes=need, stream=stream.cuda_stream, segments=args.segments,
+                                 **extra)
         if rc != 0:
             raise RuntimeError(vla.status_string(rc))
 
@@ -204,7 +216,8 @@ def main():
 
     head_tokens = B * H * T
     value = head_tokens * args.steps / wall
-    flops = 10.0 * d * d * head_tokens           # algorithmic flop per launch (5 d^2 FMA per head-token)
+    # algorithmic flop per launch: 5 d^2 FMA per head-token, 6 d^2 with separate penalty directions
+    flops = (12.0 if args.options == "paper" else 10.0) * d * d * head_tokens
     io_bytes = (2 if dtype == "bf16" else 4) * 4 * d * head_tokens   # q,k,v read + o written
     achieved_tflops = flops / avg_launch_s / 1e12
     mode_names = {1: "scan", 2: "chunked", 3: "two_phase", 4: "time_parallel"}

@@ -41,15 +41,16 @@ extern "C" {
 typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
- *   AUTO     : the library picks: SCAN when an option of Algorithm 1 is switched on or the head
- *              size has no block kernel; TIME_PARALLEL for B*H <= 64 (128 below d = 128) and T >= 1024 if the caller
- *              passed the workspace vla_forward_workspace_bytes() asks for (else CHUNKED);
- *              CHUNKED otherwise.
+ *   AUTO     : the library picks: SCAN when the head size has no block kernel; CHUNKED when an option
+ *              of Algorithm 1 is switched on; else TIME_PARALLEL for B*H <= 64 (128 below d = 128) and
+ *              T >= 1024 if the caller passed the workspace vla_forward_workspace_bytes() asks for
+ *              (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
  *              resident in registers (FP32 vector ALU).
  *   CHUNKED  : tokens are processed in blocks; the block form of the same
  *              recurrence turns the matrix-vector work into dense FP32 matrix
- *              products (MFMA).  Same result up to float32 rounding order.
+ *              products (MFMA).  Same result up to float32 rounding order.  A second block kernel
+ *              carries the options of Algorithm 1 (blocks then end at every refresh step).
  *   TWO_PHASE: phase 1 runs the A recurrence and writes k^_t, alpha^_t to the
  *              workspace; phase 2 runs the S recurrence with the rows of S spread
  *              over several workgroups (for small B*H).  Allowed because A never
@@ -81,8 +82,8 @@ typedef enum {
  * vla_default_opts() and then change fields: later library versions may append fields.
  *
  * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
- * With any of them set only the SCAN kernel family applies (AUTO selects it; asking for CHUNKED,
- * TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED). */
+ * With any of them set the SCAN and CHUNKED kernel families apply (AUTO selects CHUNKED where the head
+ * size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED). */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
   float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the

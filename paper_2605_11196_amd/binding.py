@@ -98,14 +98,16 @@ def _opts(lambda0, eps, mode, extra=None):
 
 
 def vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, *, lambda0=None, eps=None,
-                                mode=None, segments=None) -> int:
-    o = _opts(lambda0, eps, mode, dict(segments=segments))
+                                mode=None, segments=None, **extra) -> int:
+    """`extra`: further vla_opts fields by name, as in vla_forward_raw."""
+    o = _opts(lambda0, eps, mode, dict(extra, segments=segments))
     return int(load_library().vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype,
                                                           ctypes.byref(o)))
 
 
-def resolve_mode(B, H, T, d_k, d_v, io_dtype, *, mode=None) -> int:
-    o = _opts(None, None, mode)
+def resolve_mode(B, H, T, d_k, d_v, io_dtype, *, mode=None, **extra) -> int:
+    """`extra`: further vla_opts fields by name, as in vla_forward_raw."""
+    o = _opts(None, None, mode, extra)
     return int(load_library().vla_resolve_mode(B, H, T, d_k, d_v, io_dtype, ctypes.byref(o)))
 
 

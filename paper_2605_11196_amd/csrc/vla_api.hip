@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 300;  // 0.3.0
+constexpr int kVersion = 400;  // 0.4.0
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -39,13 +39,13 @@ bool general_path(const vla_opts& o) {
          o.zkey0 != nullptr || o.zkey_T != nullptr;
 }
 
-// AUTO: options -> scan family; few heads on a long sequence -> time-parallel (segments of the sequence run
-// concurrently and the S rows spread over d/16 times more workgroups than there are heads); otherwise the
-// fused block kernel.
+// AUTO: head sizes without a block kernel -> scan family; options -> the block kernel that carries them;
+// few heads on a long sequence -> time-parallel (segments of the sequence run concurrently and the S rows
+// spread over d/16 times more workgroups than there are heads); otherwise the fused block kernel.
 int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
-  if (general_path(o)) return VLA_MODE_SCAN;
   if (d != d_v || !vla::chunk_supported(d)) return VLA_MODE_SCAN;
+  if (general_path(o)) return VLA_MODE_CHUNKED;
   const long long heads = static_cast<long long>(B) * H;
   // measured crossover at T = 16384: 64 heads at d = 128 (5.4 against 7.7 ms; 128 heads 9.1 against 7.7),
   // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.4 against 5.0)
@@ -54,11 +54,10 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
 }
 
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
-  if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernel is square only
-  if (general_path(o) || d != d_v) return false;
-  if (mode == VLA_MODE_CHUNKED || mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
-    return vla::chunk_supported(d);
-  }
+  if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernels are square only
+  if (d != d_v || !vla::chunk_supported(d)) return false;
+  if (mode == VLA_MODE_CHUNKED) return true;
+  if (mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) return !general_path(o);
   return false;
 }
 
@@ -164,7 +163,9 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
                 : vla::launch_scan(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_CHUNKED:
-      err = vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+      err = general_path(op)
+                ? vla::launch_chunk_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
+                : vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_TWO_PHASE:
       err = vla::launch_two_phase(a, d_k, io_dtype, static_cast<hipStream_t>(stream));

@@ -1,0 +1,563 @@
+// Block form of the VLA recurrence with the optional lines of Algorithm 1 (paper, pseudocode appendix) on
+// FP32 MFMA: a penalty direction u_t supplied separately from the key (eq. (penalty)), the periodic identity
+// refresh A += eta I, the normalised read-out of eq. (output) with its running key sum, and the ELU+1
+// feature map on q and k (Section 3.3).
+//
+// Within a block of at most C = 16 tokens (rows = tokens), entering state A0 (symmetric), S0:
+//
+//   Y^T = U A0 ,  X^T = K^ A0                        (C x d)   z and A0 k^ before the in-block corrections
+//   G = Y^T U^T = L L^T - I                          (C x C)   L_tt^2 = delta_t
+//   W^T = L^{-1} Y^T                                 (C x d)   A_t = A0 - sum_{s<=t} w_s w_s^T   (eq. (sm))
+//   Hm = L^{-1} (Y^T K^^T)                           (C x C)   Hm[s][t] = w_s . k^_t
+//   alpha_t = x_t - sum_{s<=t} Hm[s][t] w_s                    = A_t k^_t          (post-update A)
+//   c_t = 1 / max(||alpha_t||, eps)                            alpha^_t = c_t alpha_t
+//   P[s][t] = alpha_s . k^_t = (X^T K^^T)[s][t] - sum_{r<=s} Hm[r][s] Hm[r][t]
+//   AQ[s][t] = alpha_s . q_t = (X^T Q^T)[s][t] - sum_{r<=s} Hm[r][s] (L^{-1} Y^T Q^T)[r][t]
+//   F^T = V - K^ S0^T ,  E^T = Z F^T ,  Z = (I + N)^{-1},  N[t][s] = c_s P[s][t] for s < t    (eq. (s-update))
+//   O^T = Q S0^T + NQ^T E^T ,  NQ[s][t] = c_s AQ[s][t] for s <= t, else 0
+//   S1^T = S0^T + Alpha diag(c) E^T ,  A1 = A0 - W W^T
+//
+// With u = k^ the rows of X and Y coincide and this reduces to the block form of the plain kernel.
+//
+// Identity refresh: a step whose 1-based index is a multiple of the period adds eta I to A after the
+// rank-1 update and before the write direction is formed.  Blocks are cut so that such a step is the last
+// live token of its block (shorter blocks are padded with zero tokens, which are exact no-ops); then only
+// that token sees the refreshed matrix: alpha_t += eta k^_t, AQ[t][t] += eta k^_t . q_t, and A1 += eta I.
+//
+// Normalised read-out: o_t is divided by max(q_t . zkey_t, eps), zkey_t = zkey_0 + sum_{s<=t} k_s with k_s
+// the key as used before L2 normalisation, k_s = max(||k_s||, eps) k^_s; inside a block
+// q_t . zkey_t = q_t . zkey_start + sum_{s<=t} ||k_s|| (Q K^^T)[t][s].
+//
+// Work split: D/16 waves per (batch, head); wave w owns columns [16w, 16w+16) of A and the same rows of S
+// as 16x16 MFMA accumulator tiles resident in VGPRs for the whole sequence.  The C x C Gram matrices are
+// shared out over the waves (each one contracts over the whole head dimension), the C x C factorisations
+// run on one wave each, rotating with the block index.
+//
+// v_mfma_f32_16x16x4_f32 register layout, lane l = 16*g + c:
+//   A operand: A[m = c][k = g]      B operand: B[k = g][n = c]      C/D: reg r -> D[m = 4g + r][n = c]
+#include "vla_mfma_util.h"
+
+namespace vla {
+namespace {
+
+// C x C Gram matrices of a block, [m][n] = sum_j left[m][j] right[n][j]
+enum GramTile {
+  kG = 0,   // Y U^T
+  kGK,      // Y K^^T
+  kGQ,      // Y Q^T
+  kGX,      // X K^^T
+  kXQ,      // X Q^T
+  kQK,      // Q K^^T      (normalised read-out)
+  kQZ,      // Q zkey^T    (normalised read-out; only column 0 is populated)
+  kNumGram
+};
+
+__device__ __forceinline__ float elu_plus_one(float x) { return x > 0.0f ? x + 1.0f : __expf(x); }
+
+template <int D, typename IO, bool HASU>
+__global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
+  constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
+  constexpr int NB = D / 16;       // 16-row blocks over the head dimension
+  constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
+  constexpr int EPT = 4;           // staged elements per thread per tensor
+  constexpr int TPR = D / EPT;     // threads per token row (8, 16 or 32: inside one wave)
+  constexpr int UROWS = HASU ? C : 1;
+  // without a separate u: Y = X and the Gram matrices that differ only in u against k^ coincide
+  constexpr int iGK = HASU ? kGK : kG;
+  constexpr int iGX = HASU ? kGX : kG;
+  constexpr int iXQ = HASU ? kXQ : kGQ;
+
+  __shared__ __align__(16) float Ksb[2][C * LD];      // K^  [t][j], double-buffered over blocks
+  __shared__ __align__(16) float Qsb[2][C * LD];      // Q   [t][j]
+  __shared__ __align__(16) float Usb[UROWS * LD];     // U   [t][j] (dead after the Gram phase of its block)
+  __shared__ __align__(16) float Ys[C * LD];          // Y^T [t][j]
+  __shared__ __align__(16) float Xsb[UROWS * LD];     // X^T [t][j]
+  __shared__ __align__(16) float Wb[D * LT];          // W     [j][t]
+  __shared__ __align__(16) float Ab[D * LT];          // Alpha [j][t]
+  __shared__ __align__(16) float Gs[kNumGram][C * LT];
+  __shared__ __align__(16) float Lis[C * LT];         // L^{-1} [t][s]
+  __shared__ __align__(16) float Ps[C * LT];          // P transposed: [t][s] = alpha_s . k^_t
+  __shared__ __align__(16) float Zs[C * LT];          // Z   [t][s]
+  __shared__ __align__(16) float NQs[C * LT];         // -NQ^T [t][s]
+  __shared__ __align__(16) float wn2p[NW][C];         // per-wave partial ||alpha_t||^2
+  __shared__ __align__(16) float cvec[C];             // -c_t
+  __shared__ __align__(16) float rdens[C];            // 1 / max(q_t . zkey_t, eps)
+  __shared__ __align__(16) float nks[2][C];           // max(||k_t||, eps), double-buffered with K^
+  __shared__ __align__(16) float zks[D];              // running key sum (each wave touches its own columns)
+
+  const int head = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int T = a.T;
+  const float eps = a.eps;
+  const int col0 = 16 * w;
+  const int period = a.refresh_period;
+  const float eta = a.refresh_eta;
+  const bool norm_out = a.normalise_output != 0;
+  const bool key_sum = norm_out || a.zkey_T != nullptr;
+  const bool fmap = a.feature_map != 0;
+  const float* Us = HASU ? Usb : nullptr;   // set per block when u = k^
+  const float* Xs = HASU ? Xsb : Ys;
+
+  // ---- resident state: At[b][r] = A[16b + 4g + r][col0 + c],  St[b][r] = S[col0 + c][16b + 4g + r]
+  f4 At[NB], St[NB];
+  {
+    const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float diag = 1.0f / a.lambda0;
+    const int arc = (4 * g) * D + col0 + c;
+    const int src = (col0 + c) * D + 4 * g;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      if (A0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) At[b][r] = A0[arc + (16 * b + r) * D];
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) At[b][r] = (16 * b + 4 * g + r == col0 + c) ? diag : 0.0f;
+      }
+      if (S0) {
+        const float4 x = *reinterpret_cast<const float4*>(S0 + src + 16 * b);
+        St[b] = f4{x.x, x.y, x.z, x.w};
+      } else {
+        St[b] = f4{0, 0, 0, 0};
+      }
+    }
+  }
+  if (lane < 16) zks[col0 + lane] = a.zkey0 ? a.zkey0[static_cast<size_t>(head) * D + col0 + lane] : 0.0f;
+
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  const IO* uh = HASU ? static_cast<const IO*>(a.u) + slab : nullptr;
+  IO* oh = static_cast<IO*>(a.o) + slab;
+
+  // staging role of this thread: token row and 4-element column segment
+  const int srow = tid / TPR;
+  const int sseg = (tid % TPR) * EPT;
+  const int vcol = col0 + c;
+
+  // Tokens of the block that starts at t: at most C, not past the end, and cut after a refresh step.
+  auto block_len = [&](int t) -> int {
+    int len = T - t < C ? T - t : C;
+    if (period > 0) {
+      const int r = (a.step_offset + t + 1) % period;     // step index of token t modulo the period
+      const int to_refresh = r == 0 ? 1 : period - r + 1;  // tokens up to and including the next refresh step
+      len = len < to_refresh ? len : to_refresh;
+    }
+    return len;
+  };
+
+  RawRow<IO, EPT> kpre, qpre, upre;
+  IO vpre[4];  // V in accumulator layout: V[t0 + 4g + r][col0 + c]
+
+  // Loads never branch on the row: rows past the end read the last valid row and are zeroed when consumed.
+  auto load_kqu = [&](int t0) {
+    const int tr = t0 + srow;
+    const unsigned off = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+    kpre.load(kh + off);
+    qpre.load(qh + off);
+    if constexpr (HASU) upre.load(uh + off);
+  };
+  auto load_v = [&](int t0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int t = t0 + 4 * g + r;
+      vpre[r] = vh[static_cast<unsigned>((t < T ? t : T - 1) * D + vcol)];
+    }
+  };
+  auto row_total = [&](float x) -> float {
+#pragma unroll
+    for (int off = TPR / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+  };
+  // 1 / max(sqrt(ss), eps): hardware reciprocal square root refined by one Newton step
+  auto inv_norm = [&](float ss, float& clamped) -> float {
+    clamped = fmaxf(ss, eps * eps);
+    const float rn = __builtin_amdgcn_rsqf(clamped);
+    return rn * fmaf(-0.5f * clamped * rn, rn, 1.5f);
+  };
+  // this thread's share of the block [t0, t0 + len): K^, Q (and U) into LDS half `buf`
+  auto stage = [&](int len, int buf) {
+    const bool live = srow < len;
+    float x[EPT];
+    kpre.unpack(x);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (fmap) x[e] = elu_plus_one(x[e]);
+      x[e] = live ? x[e] : 0.0f;
+    }
+    float ss = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) ss = fmaf(x[e], x[e], ss);
+    float sm;
+    const float rn = inv_norm(row_total(ss), sm);
+    *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg]) = f4{x[0] * rn, x[1] * rn, x[2] * rn, x[3] * rn};
+    if (sseg == 0) nks[buf][srow] = sm * rn;  // max(||k||, eps)
+    qpre.unpack(x);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (fmap) x[e] = elu_plus_one(x[e]);
+      x[e] = live ? x[e] : 0.0f;
+    }
+    *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg]) = f4{x[0], x[1], x[2], x[3]};
+    if constexpr (HASU) {
+      upre.unpack(x);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) x[e] = live ? x[e] : 0.0f;
+      float uu = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) uu = fmaf(x[e], x[e], uu);
+      float um;
+      const float su = a.u_scale * inv_norm(row_total(uu), um);
+      *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = f4{x[0] * su, x[1] * su, x[2] * su, x[3] * su};
+    }
+  };
+
+  int len = 0;
+  if (T > 0) {
+    len = block_len(0);
+    load_kqu(0);
+    load_v(0);
+    stage(len, 0);
+    if (len < T) load_kqu(len);
+  }
+  __syncthreads();  // block 0 staged, zks initialised
+
+  int blk = 0;
+  for (int t0 = 0; t0 < T; ++blk) {
+    const float* Ks = Ksb[blk & 1];
+    const float* Qs = Qsb[blk & 1];
+    if constexpr (!HASU) Us = Ks;
+    const int tn = t0 + len;                         // start of the next block
+    const int lenn = tn < T ? block_len(tn) : 0;
+    const bool refresh_here = period > 0 && ((a.step_offset + t0 + len) % period) == 0;
+    auto stage_next = [&]() {
+      if (tn < T) {
+        stage(lenn, (blk + 1) & 1);
+        if (tn + lenn < T) load_kqu(tn + lenn);
+      }
+    };
+    int cc = c;  // opaque copy: keeps lane-dependent masks from being hoisted out of the loop
+    asm volatile("" : "+v"(cc));
+
+    f4 ft;  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ft[r] = (4 * g + r < len) ? neg_widen(vpre[r]) : 0.0f;
+    if (tn < T) load_v(tn);
+
+    // ================= Y^T = U A0, X^T = K^ A0 (this wave's columns) -> LDS;  -F^T = K^ S0^T - V^T
+    f4 yt = f4{0, 0, 0, 0}, xt = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
+      if constexpr (HASU) {
+        const f4 ua = lds4(&Us[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) yt = mfma16(ua[r], At[b][r], yt);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) xt = mfma16(ka[r], At[b][r], xt);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) yt = mfma16(ka[r], At[b][r], yt);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], St[b][r], ft);
+    }
+    if constexpr (!HASU) xt = yt;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      Ys[(4 * g + r) * LD + col0 + c] = yt[r];
+      if constexpr (HASU) Xsb[(4 * g + r) * LD + col0 + c] = xt[r];
+    }
+    __syncthreads();  // (1) Y^T, X^T complete
+
+    // ================= Gram matrices, shared out over the waves
+    {
+      int slot = 0;
+#pragma unroll
+      for (int i = 0; i < kNumGram; ++i) {
+        if (!HASU && (i == kGK || i == kGX || i == kXQ)) continue;
+        if ((i == kQK || i == kQZ) && !norm_out) continue;
+        const bool mine = (slot % NW) == w;
+        ++slot;
+        if (!mine) continue;
+        const float* left = (i == kG || i == kGK || i == kGQ) ? Ys : (i == kGX || i == kXQ) ? Xs : Qs;
+        const float* right = (i == kG) ? Us : (i == kGK || i == kGX || i == kQK) ? Ks : Qs;
+        f4 acc0 = f4{0, 0, 0, 0}, acc1 = f4{0, 0, 0, 0};  // two chains: the tile is one wave's whole job here
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const f4 av = lds4(&left[c * LD + 16 * b + 4 * g]);
+          f4 bv;
+          if (i == kQZ) {
+            const f4 zv = lds4(&zks[16 * b + 4 * g]);
+            bv = (cc == 0) ? zv : f4{0, 0, 0, 0};
+          } else {
+            bv = lds4(&right[c * LD + 16 * b + 4 * g]);
+          }
+          acc0 = mfma16(av[0], bv[0], acc0);
+          acc1 = mfma16(av[1], bv[1], acc1);
+          acc0 = mfma16(av[2], bv[2], acc0);
+          acc1 = mfma16(av[3], bv[3], acc1);
+        }
+        acc0 += acc1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Gs[i][(4 * g + r) * LT + c] = acc0[r];
+      }
+    }
+    __syncthreads();  // (2) Gram matrices visible
+
+    // ================= phase 1 (one wave): Cholesky of I + G and L^{-1}
+    const int sw = (blk + head) % NW;
+    const int sw2 = (sw + (NW > 2 ? NW / 2 + 1 : 1)) % NW;  // another wave, on another SIMD, forms c, Z, NQ
+    f4 ot;  // R^T = Q S0^T, later O^T
+    auto r_pass = [&]() {
+      ot = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ot = mfma16(qa[r], St[b][r], ot);
+      }
+    };
+    if (w != sw) {
+      r_pass();
+      stage_next();
+    } else {
+      // Lanes 0-31 hold rows of I + G (-> rows of L), lanes 32-63 columns of the identity (-> columns of
+      // L^{-1}); one broadcast of L[j][t] serves the trailing update and the forward substitution.
+      float m[C];
+      const bool lower = lane < 32;
+#pragma unroll
+      for (int s4 = 0; s4 < C; s4 += 4) {
+        const f4 acc = lds4(&Gs[kG][c * LT + s4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m[s4 + e] = (lower ? acc[e] : 0.0f) + ((s4 + e) == cc ? 1.0f : 0.0f);
+      }
+#pragma unroll
+      for (int t = 0; t < C; ++t) {
+        const float p = readlane(m[t], t);  // pivot = delta_t >= 1
+        const float ri = __builtin_amdgcn_rsqf(p);
+        const float li = m[t] * ri;  // lanes <32: column t of L;  lanes >=32: row t of L^{-1}, final
+        m[t] = li;
+#pragma unroll
+        for (int j = t + 1; j < C; ++j) m[j] = fmaf(-li, readlane(li, j), m[j]);
+      }
+      if (g == 2) {
+#pragma unroll
+        for (int t = 0; t < C; ++t) Lis[t * LT + c] = m[t];
+      }
+    }
+    __syncthreads();  // (3) L^{-1} visible
+
+    // ================= W^T = L^{-1} Y^T,  Hm = L^{-1} (Y K^^T),  Alpha^T = X^T - M W^T,  ||alpha_t||^2
+    const f4 la = lds4(&Lis[c * LT + 4 * g]);
+    f4 nwt;   // -W^T tile
+    f4 mop;   // M as an A operand: M[t = c][s = 4g + r] = Hm[s][t] for s <= t
+    f4 nhm;   // -Hm in accumulator layout
+    {
+      f4 acc = f4{0, 0, 0, 0};
+      f4 hm = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        acc = mfma16(la[r], yt[r], acc);
+        hm = mfma16(la[r], Gs[iGK][(4 * g + r) * LT + c], hm);
+      }
+      nwt = -acc;
+      nhm = -hm;
+      *reinterpret_cast<f4*>(&Wb[(col0 + c) * LT + 4 * g]) = acc;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) mop[r] = (4 * g + r <= cc) ? hm[r] : 0.0f;
+      f4 at = xt;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) at = mfma16(mop[r], nwt[r], at);
+      if (refresh_here) {  // uniform: the last live token sees A + eta I
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float kv = Ks[(4 * g + r) * LD + col0 + c];
+          at[r] = (4 * g + r == len - 1) ? fmaf(eta, kv, at[r]) : at[r];
+        }
+      }
+      f4 n2 = at * at;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
+      if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
+      *reinterpret_cast<f4*>(&Ab[(col0 + c) * LT + 4 * g]) = at;
+    }
+    __syncthreads();  // (4) W, Alpha and the norm partials visible
+
+    // ================= phase 2 (wave sw2): c_t, Z, NQ, read-out denominators -- the others update A
+    auto update_A = [&]() {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 wa = lds4(&Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) At[b] = mfma16(wa[r], nwt[r], At[b]);
+      }
+      if (refresh_here) {  // + eta on the diagonal: rows 16w + 4g + r against column 16w + c
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          if (b == w) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) At[b][r] += (4 * g + r == cc) ? eta : 0.0f;
+          }
+        }
+      }
+    };
+    if (w != sw2) update_A();
+    if (w == sw) stage_next();
+    if (w == sw2) {
+      float wn2 = 0.0f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
+      const float cs = __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(wn2), eps));  // alpha^_t = c_t alpha_t
+      if (g == 0) cvec[c] = -cs;
+      // P and AQ in accumulator layout [s = 4g + r][t = c]
+      f4 pt, aq;
+      f4 nhq = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        pt[r] = Gs[iGX][(4 * g + r) * LT + c];
+        aq[r] = Gs[iXQ][(4 * g + r) * LT + c];
+        nhq = mfma16(-la[r], Gs[kGQ][(4 * g + r) * LT + c], nhq);  // -(L^{-1} Y Q^T)
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        pt = mfma16(mop[r], nhm[r], pt);
+        aq = mfma16(mop[r], nhq[r], aq);
+      }
+      if (refresh_here) {  // alpha of the last live token carries + eta k^: its read-out weight gains eta k^.q
+        const int tl = len - 1;
+        float kq = 0.0f;
+        for (int j = lane; j < D; j += 64) kq = fmaf(Ks[tl * LD + j], Qs[tl * LD + j], kq);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) kq += __shfl_xor(kq, off);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) aq[r] = (4 * g + r == tl && cc == tl) ? fmaf(eta, kq, aq[r]) : aq[r];
+      }
+      // rows of P^T on lanes: lane t reads alpha_s . k^_t for all s
+      *reinterpret_cast<f4*>(&Ps[c * LT + 4 * g]) = pt;
+      float m[C];
+#pragma unroll
+      for (int s4 = 0; s4 < C; s4 += 4) {
+        const f4 pr = lds4(&Ps[c * LT + s4]);  // same wave wrote it: LDS operations of one wave are ordered
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m[s4 + e] = pr[e];
+      }
+      float nm[C], Zr[C];
+      float ncs = -cs;
+      asm volatile("s_nop 1" : "+v"(ncs));   // a DPP read of a VGPR needs 2 wait states after its write
+      scale_cols<0>(m, nm, ncs);             // lane t: -P[s][t] c_s = -N[t][s]
+      asm volatile("s_nop 1" : "+v"(nm[0]));
+      z_rows<0>(nm, Zr, cc);
+      if (g == 0) {
+#pragma unroll
+        for (int t = 0; t < C; ++t) Zs[t * LT + c] = Zr[t];
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int s = 4 * g + r;
+        const float csr = __shfl(cs, s);
+        NQs[c * LT + s] = (s <= c) ? -(csr * aq[r]) : 0.0f;
+      }
+      if (norm_out) {  // q_t . zkey_t for t = 4g + r: key-sum part + in-block part over s = c <= t
+        const float nk = nks[blk & 1][c];
+        f4 den;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float qk = Gs[kQK][(4 * g + r) * LT + c];
+          const float qz = Gs[kQZ][(4 * g + r) * LT + c];
+          den[r] = row_sum16(qz + ((cc <= 4 * g + r) ? qk * nk : 0.0f));
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) den[r] = 1.0f / fmaxf(den[r], eps);
+        if (c == 0) *reinterpret_cast<f4*>(&rdens[4 * g]) = den;
+      }
+    }
+    __syncthreads();  // (5) Z, NQ, c, denominators visible
+
+    // ================= -E^T = Z (-F^T), O^T = Q S0^T + (-NQ^T)(-E^T), store o;  ce = diag(c) E^T
+    f4 ce;
+    {
+      const f4 za = lds4(&Zs[c * LT + 4 * g]);
+      f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
+      if (w == sw) r_pass();
+      const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
+      const f4 cg = lds4(&cvec[4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+      ce = et * cg;
+      if (norm_out) ot *= lds4(&rdens[4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (4 * g + r < len) io_store(oh + static_cast<unsigned>((t0 + 4 * g + r) * D + vcol), ot[r]);
+      }
+    }
+    // ================= S^T += Alpha diag(c) E^T  (and A -= W W^T on the wave that formed Z)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const f4 aa = lds4(&Ab[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) St[b] = mfma16(aa[r], ce[r], St[b]);
+    }
+    if (w == sw2) update_A();
+    if (key_sum && lane < 16) {  // zkey += sum over the block's tokens of ||k_s|| k^_s, this wave's columns
+      float zk = zks[col0 + lane];
+#pragma unroll
+      for (int s = 0; s < C; ++s) zk = fmaf(nks[blk & 1][s], Ks[s * LD + col0 + lane], zk);
+      zks[col0 + lane] = zk;
+    }
+    t0 = tn;
+    len = lenn;
+  }
+
+  // ---- final state
+  {
+    float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
+    float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+    const int arc = (4 * g) * D + col0 + c;
+    const int src = (col0 + c) * D + 4 * g;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      if (AT) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) AT[arc + (16 * b + r) * D] = At[b][r];
+      }
+      if (ST) {
+        *reinterpret_cast<float4*>(ST + src + 16 * b) = make_float4(St[b][0], St[b][1], St[b][2], St[b][3]);
+      }
+    }
+    if (a.zkey_T != nullptr && lane < 16) {
+      a.zkey_T[static_cast<size_t>(head) * D + col0 + lane] = zks[col0 + lane];
+    }
+  }
+}
+
+template <int D, typename IO>
+hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  const void* fn = a.u != nullptr ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true>)
+                                  : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false>);
+  return hipLaunchKernel(fn, dim3(a.n_heads), dim3(4 * D), params, 0, stream);
+}
+
+}  // namespace
+
+hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
+    case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
+    case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace vla

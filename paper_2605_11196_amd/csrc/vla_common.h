@@ -20,7 +20,7 @@ struct ForwardArgs {
   float lambda0;
   float eps;
   float* ws;  // device workspace (two-phase mode), else nullptr
-  // the remaining lines of Algorithm 1 (general scan kernel only)
+  // the remaining lines of Algorithm 1 (general scan and general block kernels)
   const void* u;
   float u_scale;
   int refresh_period;
@@ -62,6 +62,8 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 32, 64 and 128.
 bool chunk_supported(int d);
 hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+// Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); same head sizes.
+hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
 // Two-phase split (vla_two_phase.hip): A recurrence first, then the rows of S on many workgroups.

@@ -95,6 +95,7 @@ __device__ __forceinline__ void io_store2(uint16_t* p0, uint16_t* p1, float x0, 
 // A staged row segment of EPT consecutive elements, held in its raw (packed) form until it is used.
 template <typename IO, int EPT> struct RawRow;
 template <int EPT> struct RawRow<float, EPT> {
+  static_assert(EPT % 4 == 0, "whole 16-byte pieces");
   float4 v[EPT / 4];
   __device__ __forceinline__ void load(const float* p) {
 #pragma unroll
@@ -112,23 +113,27 @@ template <int EPT> struct RawRow<float, EPT> {
   }
 };
 template <int EPT> struct RawRow<uint16_t, EPT> {
-  uint4 v[EPT / 8];
+  static_assert(EPT % 4 == 0, "whole 8-byte pieces");
+  static constexpr int PW = EPT % 8 == 0 ? 4 : 2;   // 32-bit words per load: 16-byte pieces, else 8-byte ones
+  static constexpr int NP = EPT / (2 * PW);
+  typedef uint32_t Piece __attribute__((ext_vector_type(PW)));
+  Piece v[NP];
   __device__ __forceinline__ void load(const uint16_t* p) {
 #pragma unroll
-    for (int e = 0; e < EPT / 8; ++e) v[e] = *reinterpret_cast<const uint4*>(p + 8 * e);
+    for (int e = 0; e < NP; ++e) v[e] = *reinterpret_cast<const Piece*>(p + 2 * PW * e);
   }
   __device__ __forceinline__ void zero() {
 #pragma unroll
-    for (int e = 0; e < EPT / 8; ++e) v[e] = make_uint4(0u, 0u, 0u, 0u);
+    for (int e = 0; e < NP; ++e) v[e] = Piece(0u);
   }
   __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
 #pragma unroll
-    for (int e = 0; e < EPT / 8; ++e) {
-      const uint32_t u[4] = {v[e].x, v[e].y, v[e].z, v[e].w};
+    for (int e = 0; e < NP; ++e) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        x[8 * e + 2 * i] = __uint_as_float(u[i] << 16);
-        x[8 * e + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+      for (int i = 0; i < PW; ++i) {
+        const uint32_t u = v[e][i];
+        x[2 * (PW * e + i)] = __uint_as_float(u << 16);
+        x[2 * (PW * e + i) + 1] = __uint_as_float(u & 0xffff0000u);
       }
     }
   }

@@ -1,6 +1,7 @@
 """GPU parity for the optional lines of Algorithm 1 (separate penalty direction u, periodic identity
-refresh, normalised read-out with the running key sum, ELU+1 feature map): general scan kernel through
-the C ABI against the fp64 oracle, same error metric and tolerances as the main parity tests."""
+refresh, normalised read-out with the running key sum, ELU+1 feature map): the general scan kernel and the
+general block kernel through the C ABI against the fp64 oracle, same error metric and tolerances as the main
+parity tests."""
 import numpy as np
 import pytest
 
@@ -11,7 +12,14 @@ from parity_utils import TOL, slab_rel_err, to_np
 pytestmark = pytest.mark.gpu
 
 
-def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, **opt):
+SCAN, BLOCK = 1, 2
+
+
+def modes_for(d):
+    return [SCAN, BLOCK] if d in (32, 64, 128) else [SCAN]
+
+
+def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, mode=None, **opt):
     import torch
 
     import paper_2605_11196_amd as vla
@@ -24,7 +32,7 @@ def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, **op
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     t = lambda x, dt=tdt: None if x is None else torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(dt)
     o, S_T, A_T, zk = vla.vla_forward(t(q), t(k), t(v), t(S0, torch.float32), t(A0, torch.float32),
-                                       u=t(u), zkey0=t(zkey0, torch.float32), return_zkey=True,
+                                       u=t(u), zkey0=t(zkey0, torch.float32), return_zkey=True, mode=mode,
                                        lambda0=opt.get("lambda0"), eps=opt.get("eps"),
                                        u_scale=opt.get("u_scale"), refresh_period=opt.get("refresh_period"),
                                        refresh_eta=opt.get("refresh_eta"), step_offset=opt.get("step_offset"),
@@ -66,18 +74,20 @@ def test_option_parity(name, d, T, dtype):
         q, k = np.abs(q) + 0.05, np.abs(k) + 0.05
     u = rng.standard_normal(q.shape).astype(np.float32) if cfg.pop("with_u", False) else None
     cfg.pop("want_zkey_only", None)
-    got, ref = run_both(q, k, v, dtype=dtype, u=u, lambda0=0.1, **cfg)
-    print(name, d, T, dtype, assert_close(got, ref, TOL[dtype]))
+    for mode in modes_for(d):
+        got, ref = run_both(q, k, v, dtype=dtype, u=u, lambda0=0.1, mode=mode, **cfg)
+        print(name, d, T, dtype, mode, assert_close(got, ref, TOL[dtype]))
 
 
-def test_split_sequence_with_every_option_carries_state():
+@pytest.mark.parametrize("mode", [SCAN, BLOCK])
+def test_split_sequence_with_every_option_carries_state(mode):
     """[0,T1) then [T1,T) with S, A, the key sum and the refresh phase carried == one call."""
     d, T, T1 = 64, 101, 37
     rng = np.random.default_rng(5)
     q, k, v = vla_inputs.gaussian_qkv(1, 3, T, d, seed=55)
     u = rng.standard_normal(q.shape).astype(np.float32)
     opt = dict(lambda0=0.1, u_scale=0.125, refresh_period=8, refresh_eta=1e-2, normalise_output=True,
-               feature_map=True)
+               feature_map=True, mode=mode)
     full, ref = run_both(q, k, v, u=u, **opt)
     assert_close(full, ref, 1e-4)
     a, _ = run_both(q[:, :, :T1], k[:, :, :T1], v[:, :, :T1], u=u[:, :, :T1], **opt)
@@ -87,17 +97,59 @@ def test_split_sequence_with_every_option_carries_state():
     assert_close(joined, ref, 1e-4)
 
 
-def test_options_are_refused_by_the_block_kernels():
+@pytest.mark.parametrize("period", [1, 2, 5, 16, 17, 33])
+@pytest.mark.parametrize("offset", [0, 3])
+def test_block_kernel_cuts_blocks_at_every_refresh_period(period, offset):
+    """Blocks end at refresh steps: periods below, at and above the block length, with a carried phase."""
+    d, T = 32, 77
+    q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=300 + period)
+    opt = dict(lambda0=0.1, refresh_period=period, refresh_eta=5e-3, step_offset=offset)
+    got, ref = run_both(q, k, v, mode=BLOCK, **opt)
+    print(period, offset, assert_close(got, ref, 1e-4))
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_block_kernel_options_on_zero_keys_and_tiny_directions(d):
+    """Zero keys (no write, the read still happens), zero and tiny penalty directions (no A update for a zero
+    u; a tiny one is normalised like any other), and a sequence shorter than a block."""
+    T = 23
+    rng = np.random.default_rng(d)
+    q, k, v = vla_inputs.gaussian_qkv(2, 2, T, d, seed=40 + d)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    k[:, :, 3] = 0.0
+    k[:, :, 17:19] = 0.0
+    u[:, :, 5] = 0.0
+    u[:, :, 9] *= 1e-7
+    opt = dict(lambda0=0.1, u_scale=d ** -0.5, refresh_period=7, refresh_eta=1e-3)
+    got, ref = run_both(q, k, v, u=u, mode=BLOCK, **opt)
+    print(d, assert_close(got, ref, 1e-4))
+    got, ref = run_both(q[:, :, :5], k[:, :, :5], v[:, :, :5], u=u[:, :, :5], mode=BLOCK, **opt)
+    print(d, "T=5", assert_close(got, ref, 1e-4))
+
+
+def test_block_kernel_with_options_holds_the_tolerance_on_a_long_sequence():
+    d, T = 64, 6000
+    rng = np.random.default_rng(11)
+    q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=77)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    opt = dict(lambda0=0.1, u_scale=0.125, refresh_period=20, refresh_eta=1e-3, normalise_output=True,
+               feature_map=True)
+    got, ref = run_both(q, k, v, u=u, mode=BLOCK, **opt)
+    print(assert_close(got, ref, 1e-4))
+
+
+def test_options_are_refused_by_the_segment_modes_and_taken_by_the_block_kernel():
     import torch
 
     import paper_2605_11196_amd as vla
 
     dev = torch.device("cuda:0")
     x = torch.randn(1, 1, 32, 64, device=dev)
-    for mode in (vla.MODE_CHUNKED, vla.MODE_TWO_PHASE):
+    for mode in (vla.MODE_TWO_PHASE, vla.MODE_TIME_PARALLEL):
         with pytest.raises(vla.VlaError) as e:
             vla.vla_forward(x, x, x, mode=mode, refresh_period=4)
         assert e.value.status == 2
-    o, _, _ = vla.vla_forward(x, x, x, refresh_period=4)     # AUTO falls back to the scan family
-    torch.cuda.synchronize()
-    assert torch.isfinite(o).all()
+    for mode in (None, vla.MODE_CHUNKED, vla.MODE_SCAN):
+        o, _, _ = vla.vla_forward(x, x, x, mode=mode, refresh_period=4)
+        torch.cuda.synchronize()
+        assert torch.isfinite(o).all()
