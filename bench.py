@@ -218,11 +218,14 @@ def main():
     value = head_tokens * args.steps / wall
     # algorithmic flop per launch: 5 d^2 FMA per head-token, 6 d^2 with separate penalty directions
     flops = (12.0 if args.options == "paper" else 10.0) * d * d * head_tokens
-    io_bytes = (2 if dtype == "bf16" else 4) * 4 * d * head_tokens   # q,k,v read + o written
+    n_streams = 5 if args.options == "paper" else 4                  # q,k,v (and u) read + o written
+    io_bytes = (2 if dtype == "bf16" else 4) * n_streams * d * head_tokens
     achieved_tflops = flops / avg_launch_s / 1e12
     mode_names = {1: "scan", 2: "chunked", 3: "two_phase", 4: "time_parallel"}
     workload = (f"{args.workload}: B={B} H={H} T={T} d_h={d} {dtype} q/k/v/o, fp32 A and S, "
                 f"lambda0={c['lambda0']}")
+    if args.options == "paper":
+        workload += ", every option of Algorithm 1 on (u with u_scale=1/sqrt(d_h), refresh 20, normalised, ELU+1)"
     out = {
         "metric": "VLA forward tokens/sec (B*H*T/s)",
         "value": value,
@@ -244,7 +247,7 @@ def main():
             "peak": PEAK_FP32_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved_tflops / PEAK_FP32_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((B, H, T, d, dtype, resolved)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((B, H, T, d, dtype, resolved)) if args.options == "none" else None,
             "kernel_ms": avg_launch_s * 1e3,
             "algorithmic_flop_per_launch": flops,
             "algorithmic_bytes_per_launch": io_bytes,
@@ -264,8 +267,13 @@ def main():
         pick = lambda x: x.reshape(n_all, *x.shape[2:]).index_select(0, sel).float().cpu().numpy()[None]
         qs, ks, vs = (pick(x).astype(np.float64) for x in (q, k, v))
         oracle.load()
+        oracle_opt = {}
+        if args.options == "paper":
+            oracle_opt = dict(u=pick(u).astype(np.float64), u_scale=extra["u_scale"],
+                              refresh_period=extra["refresh_period"], refresh_eta=extra["refresh_eta"],
+                              normalise_output=True, feature_map=True)
         tc0 = time.perf_counter()
-        ref = oracle.forward(qs, ks, vs, lambda0=c["lambda0"])
+        ref = oracle.forward(qs, ks, vs, lambda0=c["lambda0"], **oracle_opt)
         tc1 = time.perf_counter()
         cpu_rate = len(idx) * T / (tc1 - tc0)
         got = pick(o).astype(np.float64)

@@ -142,12 +142,17 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   const int vcol = col0 + c;
 
   // Tokens of the block that starts at t: at most C, not past the end, and cut after a refresh step.
-  auto block_len = [&](int t) -> int {
+  // `phase` is the step index of token t modulo the period; on return it is that of the next block's first
+  // token and `refresh` says whether the block's last token is a refresh step.
+  auto block_len = [&](int t, int& phase, bool& refresh) -> int {
     int len = T - t < C ? T - t : C;
+    refresh = false;
     if (period > 0) {
-      const int r = (a.step_offset + t + 1) % period;     // step index of token t modulo the period
-      const int to_refresh = r == 0 ? 1 : period - r + 1;  // tokens up to and including the next refresh step
-      len = len < to_refresh ? len : to_refresh;
+      const int to_refresh = phase == 0 ? 1 : period - phase + 1;  // tokens up to and including the refresh step
+      refresh = to_refresh <= len;
+      len = refresh ? to_refresh : len;
+      phase += len;                      // at most period + 1
+      phase -= phase >= period ? period : 0;
     }
     return len;
   };
@@ -219,8 +224,10 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   };
 
   int len = 0;
+  int phase = period > 0 ? (a.step_offset + 1) % period : 0;  // of the next block still to be planned
+  bool refresh_here = false;
   if (T > 0) {
-    len = block_len(0);
+    len = block_len(0, phase, refresh_here);
     load_kqu(0);
     load_v(0);
     stage(len, 0);
@@ -234,8 +241,8 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     const float* Qs = Qsb[blk & 1];
     if constexpr (!HASU) Us = Ks;
     const int tn = t0 + len;                         // start of the next block
-    const int lenn = tn < T ? block_len(tn) : 0;
-    const bool refresh_here = period > 0 && ((a.step_offset + t0 + len) % period) == 0;
+    bool refresh_next = false;
+    const int lenn = tn < T ? block_len(tn, phase, refresh_next) : 0;
     auto stage_next = [&]() {
       if (tn < T) {
         stage(lenn, (blk + 1) & 1);
@@ -515,6 +522,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     }
     t0 = tn;
     len = lenn;
+    refresh_here = refresh_next;
   }
 
   // ---- final state
