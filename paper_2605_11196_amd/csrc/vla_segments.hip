@@ -206,40 +206,46 @@ __global__ void __launch_bounds__(kThreads) gram_prefix_kernel(double* G, int n_
 // Gauss-Jordan inverse, in place, of a symmetric positive definite D x D matrix spread over the workgroup's
 // registers (no pivoting needed for such a matrix): thread (rg, j) holds m[n] = M[rg + RG n][j].
 //
-// Step p, with d = M[p][p]: replace column p by the unit vector e_p, then M <- M - c r^T with
-//   c_i = M[i][p] (i != p), c_p = d - 1;   r_j = M[p][j] / d (j != p), r_p = 1 / d
+// Step p, with d = M[p][p]:  M <- M - c r^T  with
+//   c_i = M[i][p] (i != p), c_p = d - 1;   r_j = M[p][j] / d (j != p), r_p = 1 + 1 / d
 // which is the usual in-place sweep (M[i][j] - M[i][p] M[p][j] / d off the pivot row and column, -M[i][p] / d in
 // column p, M[p][j] / d in row p, 1 / d at the pivot) written so that every element takes the same fused
-// multiply-add.  The pivot row is not fetched at all: after p steps the not yet eliminated part of M is a
-// Schur complement (symmetric) and the eliminated part of row p is minus the transposed column, so
-// M[p][j] = M[j][p] for j > p and -M[j][p] for j < p.  Only column p goes through LDS, double-buffered: one
-// barrier per step.
+// multiply-add and no thread has to pick out "its" pivot element.  The pivot row is not fetched at all: after p
+// steps the not yet eliminated part of M is a Schur complement (symmetric) and the eliminated part of row p is
+// minus the transposed column, so M[p][j] = M[j][p] for j > p and -M[j][p] for j < p.  Only column p goes
+// through LDS (its RG owners copy their registers out, then the owner of the pivot reads d back from LDS and
+// patches c_p), double-buffered: one barrier per step.
 template <int D>
 struct SpdInverse {
   static constexpr int RG = kThreads / D;  // row groups
   static constexpr int NR = D / RG;        // rows per thread
-  double* colp;                            // LDS [2][D + 1]: c, a thread's NR rows contiguous; then 1 / d
+  static constexpr int STRIDE = D + 2;     // doubles per pivot buffer: c (a thread's NR rows contiguous), then d
+  static_assert(NR % 2 == 0, "the column is copied out in 16-byte pieces");
+  double* colp;                            // LDS [2][STRIDE]
   __device__ __forceinline__ void run(double (&m)[NR]) const {
+    typedef double d2 __attribute__((ext_vector_type(2)));
     const int j = threadIdx.x % D;
     const int rg = threadIdx.x / D;
     const int jslot = (j % RG) * NR + j / RG;   // where c_j sits
     for (int p = 0; p < D; ++p) {
-      double* cp = colp + (p & 1) * (D + 1);
+      double* cp = colp + (p & 1) * STRIDE;
       if (j == p) {
-        const int pn = p / RG;
-        const bool own_row = rg == p % RG;
 #pragma unroll
-        for (int n = 0; n < NR; ++n) {
-          const bool pivot = own_row && n == pn;
-          if (pivot) cp[D] = 1.0 / m[n];   // the one division of the step
-          cp[rg * NR + n] = pivot ? m[n] - 1.0 : m[n];
-          m[n] = pivot ? 1.0 : 0.0;
+        for (int n = 0; n < NR; n += 2) *reinterpret_cast<d2*>(&cp[rg * NR + n]) = d2{m[n], m[n + 1]};
+        if (rg == p % RG) {
+          const int pslot = (p % RG) * NR + p / RG;
+          const double d = cp[pslot];   // this thread's own write, read back: LDS operations of a wave are ordered
+          cp[D] = d;
+          cp[pslot] = d - 1.0;
         }
       }
       __syncthreads();
-      const double piv = cp[D];
+      const double d = cp[D];
+      double piv = __builtin_amdgcn_rcp(d);   // refined twice: full double precision
+      piv = piv * fma(-d, piv, 2.0);
+      piv = piv * fma(-d, piv, 2.0);
       const double cj = cp[jslot];
-      const double rj = (j == p) ? piv : (j > p ? cj : -cj) * piv;
+      const double rj = (j == p) ? 1.0 + piv : (j > p ? cj : -cj) * piv;
 #pragma unroll
       for (int n = 0; n < NR; ++n) {
         m[n] = fma(-cp[rg * NR + n], rj, m[n]);
@@ -255,7 +261,7 @@ template <int D>
 __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const double* G, float* seg_A) {
   constexpr int RG = kThreads / D;
   constexpr int NR = D / RG;
-  __shared__ __align__(16) double colp[2 * (D + 1)];
+  __shared__ __align__(16) double colp[2 * SpdInverse<D>::STRIDE];
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
