@@ -47,8 +47,8 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (d != d_v || !vla::chunk_supported(d)) return VLA_MODE_SCAN;
   if (general_path(o)) return VLA_MODE_CHUNKED;
   const long long heads = static_cast<long long>(B) * H;
-  // measured crossover at T = 16384: 64 heads at d = 128 (5.4 against 7.7 ms; 128 heads 9.1 against 7.7),
-  // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.4 against 5.0)
+  // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
+  // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0)
   const long long few = d >= 128 ? 64 : 128;
   return (heads <= few && T >= 1024) ? VLA_MODE_TIME_PARALLEL : VLA_MODE_CHUNKED;
 }
