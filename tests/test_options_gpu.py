@@ -153,3 +153,81 @@ def test_options_are_refused_by_the_segment_modes_and_taken_by_the_block_kernel(
         o, _, _ = vla.vla_forward(x, x, x, mode=mode, refresh_period=4)
         torch.cuda.synchronize()
         assert torch.isfinite(o).all()
+
+
+@pytest.mark.parametrize("d", [32, 128])
+def test_block_kernel_with_options_is_deterministic_and_replays_in_a_hip_graph(d):
+    """Same bits on every run (no atomics, fixed reduction orders); a captured call replays like the eager one
+    on new inputs; S, A and the key sum may be updated in place."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, T = 2, 3, 150
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3)
+    q, k, v, u = (torch.randn(B, H, T, d, device=dev, generator=gen) for _ in range(4))
+    o = torch.empty_like(q)
+    S = torch.empty(B, H, d, d, device=dev)
+    A = torch.empty(B, H, d, d, device=dev)
+    zk = torch.empty(B, H, d, device=dev)
+    opt = dict(u=u.data_ptr(), u_scale=0.25, refresh_period=20, refresh_eta=1e-3, normalise_output=1,
+               feature_map=1, zkey_T=zk.data_ptr(), mode=BLOCK)
+
+    def call(stream):
+        rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(), S.data_ptr(),
+                                 A.data_ptr(), B, H, T, d, d, vla.VLA_F32, stream=stream.cuda_stream, **opt)
+        assert rc == 0
+
+    side = torch.cuda.Stream(dev)
+    side.wait_stream(torch.cuda.current_stream(dev))
+    with torch.cuda.stream(side):
+        call(side)
+    side.synchronize()
+    first = [x.clone() for x in (o, S, A, zk)]
+    with torch.cuda.stream(side):
+        call(side)
+    side.synchronize()
+    for a, b in zip(first, (o, S, A, zk)):
+        assert torch.equal(a, b)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream(dev))
+    for rep in range(3):
+        for x in (q, k, v, u):
+            x.copy_(torch.randn(B, H, T, d, device=dev, generator=gen))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (o, S, A, zk)]
+        call(torch.cuda.current_stream(dev))
+        torch.cuda.synchronize()
+        for g, e in zip(got, (o, S, A, zk)):
+            assert torch.equal(g, e), rep
+
+    # state carried in place: S_T = S0, A_T = A0, zkey_T = zkey0 (second half of a split sequence)
+    T1 = 70
+    sl = lambda x, a, b: x[:, :, a:b].contiguous()
+    parts = [(sl(q, 0, T1), sl(k, 0, T1), sl(v, 0, T1), sl(u, 0, T1)), (sl(q, T1, T), sl(k, T1, T), sl(v, T1, T), sl(u, T1, T))]
+    call(torch.cuda.current_stream(dev))
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (o, S, A, zk)]
+    S2 = torch.zeros(B, H, d, d, device=dev)
+    A2 = (torch.eye(d, device=dev) * 10.0).repeat(B, H, 1, 1).contiguous()
+    z2 = torch.zeros(B, H, d, device=dev)
+    outs = []
+    off = 0
+    for qq, kk, vv, uu in parts:
+        oo = torch.empty_like(qq)
+        rc = vla.vla_forward_raw(qq.data_ptr(), kk.data_ptr(), vv.data_ptr(), S2.data_ptr(), A2.data_ptr(),
+                                 oo.data_ptr(), S2.data_ptr(), A2.data_ptr(), B, H, qq.shape[2], d, d, vla.VLA_F32,
+                                 **dict(opt, u=uu.data_ptr(), zkey0=z2.data_ptr(), zkey_T=z2.data_ptr(),
+                                        step_offset=off))
+        assert rc == 0
+        off += qq.shape[2]
+        outs.append(oo)
+    torch.cuda.synchronize()
+    rel = lambda a, b: float((a - b).abs().max() / b.abs().max())
+    assert rel(torch.cat(outs, dim=2), want[0]) < 1e-4
+    assert rel(S2, want[1]) < 1e-4 and rel(A2, want[2]) < 1e-4 and rel(z2, want[3]) < 1e-5
