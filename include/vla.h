@@ -50,7 +50,7 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
  *   CHUNKED  : tokens are processed in blocks; the block form of the same
  *              recurrence turns the matrix-vector work into dense FP32 matrix
  *              products (MFMA).  Same result up to float32 rounding order.  A second block kernel
- *              carries the options of Algorithm 1 (blocks then end at every refresh step).
+ *              carries the options of Algorithm 1.
  *   TWO_PHASE: phase 1 runs the A recurrence and writes k^_t, alpha^_t to the
  *              workspace; phase 2 runs the S recurrence with the rows of S spread
  *              over several workgroups (for small B*H).  Allowed because A never

@@ -17,12 +17,18 @@
 //   O^T = Q S0^T + NQ^T E^T ,  NQ[s][t] = c_s AQ[s][t] for s <= t, else 0
 //   S1^T = S0^T + Alpha diag(c) E^T ,  A1 = A0 - W W^T
 //
-// With u = k^ the rows of X and Y coincide and this reduces to the block form of the plain kernel.
+// With u = k^ and no refresh the rows of X and Y coincide and this reduces to the block form of the plain
+// kernel (template flag FULL = false: one sweep of A, two Gram matrices).
 //
 // Identity refresh: a step whose 1-based index is a multiple of the period adds eta I to A after the
-// rank-1 update and before the write direction is formed.  Blocks are cut so that such a step is the last
-// live token of its block (shorter blocks are padded with zero tokens, which are exact no-ops); then only
-// that token sees the refreshed matrix: alpha_t += eta k^_t, AQ[t][t] += eta k^_t . q_t, and A1 += eta I.
+// rank-1 update and before the write direction is formed, anywhere inside a block.  With n_t the number of
+// refresh steps among the block's tokens before t and n'_t = n_{t+1} (before or at t), token t updates with
+// A0 + eta n_t I - sum_{r<t} w_r w_r^T and writes with A0 + eta n'_t I - sum_{r<=t} w_r w_r^T, so everything
+// above holds with
+//   y'_t = y_t + eta n_t u_t ,   x'_t = x_t + eta n'_t k^_t
+// in place of y_t, x_t (the Gram matrices are formed from Y', X'), with the matrix to factor taken as
+// I + u_s . y'_t for t <= s (the upper triangle of Y' U^T, mirrored: the base matrix of the earlier token
+// counts), and A1 = A0 + eta n_C I - W W^T.
 //
 // Normalised read-out: o_t is divided by max(q_t . zkey_t, eps), zkey_t = zkey_0 + sum_{s<=t} k_s with k_s
 // the key as used before L2 normalisation, k_s = max(||k_s||, eps) k^_s; inside a block
@@ -54,18 +60,19 @@ enum GramTile {
 
 __device__ __forceinline__ float elu_plus_one(float x) { return x > 0.0f ? x + 1.0f : __expf(x); }
 
-template <int D, typename IO, bool HASU>
+// FULL: Y and X differ (a separate u, or a refresh period): two sweeps of A and five Gram matrices.
+template <int D, typename IO, bool FULL>
 __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
   constexpr int NB = D / 16;       // 16-row blocks over the head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
   constexpr int EPT = 4;           // staged elements per thread per tensor
   constexpr int TPR = D / EPT;     // threads per token row (8, 16 or 32: inside one wave)
-  constexpr int UROWS = HASU ? C : 1;
-  // without a separate u: Y = X and the Gram matrices that differ only in u against k^ coincide
-  constexpr int iGK = HASU ? kGK : kG;
-  constexpr int iGX = HASU ? kGX : kG;
-  constexpr int iXQ = HASU ? kXQ : kGQ;
+  constexpr int UROWS = FULL ? C : 1;
+  // Y = X: the Gram matrices that differ only in u against k^ coincide
+  constexpr int iGK = FULL ? kGK : kG;
+  constexpr int iGX = FULL ? kGX : kG;
+  constexpr int iXQ = FULL ? kXQ : kGQ;
 
   __shared__ __align__(16) float Ksb[2][C * LD];      // K^  [t][j], double-buffered over blocks
   __shared__ __align__(16) float Qsb[2][C * LD];      // Q   [t][j]
@@ -84,6 +91,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   __shared__ __align__(16) float rdens[C];            // 1 / max(q_t . zkey_t, eps)
   __shared__ __align__(16) float nks[2][C];           // max(||k_t||, eps), double-buffered with K^
   __shared__ __align__(16) float zks[D];              // running key sum (each wave touches its own columns)
+  __shared__ __align__(16) float ens[2][C + 4];       // eta n_i, i = 0..C: refresh steps among a block's first i tokens
 
   const int head = blockIdx.x;
   const int tid = threadIdx.x;
@@ -99,8 +107,9 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   const bool norm_out = a.normalise_output != 0;
   const bool key_sum = norm_out || a.zkey_T != nullptr;
   const bool fmap = a.feature_map != 0;
-  const float* Us = HASU ? Usb : nullptr;   // set per block when u = k^
-  const float* Xs = HASU ? Xsb : Ys;
+  const bool has_u = a.u != nullptr;
+  const float* Us = FULL ? Usb : nullptr;   // set per block when Y = X
+  const float* Xs = FULL ? Xsb : Ys;
 
   // ---- resident state: At[b][r] = A[16b + 4g + r][col0 + c],  St[b][r] = S[col0 + c][16b + 4g + r]
   f4 At[NB], St[NB];
@@ -133,29 +142,13 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const IO* vh = static_cast<const IO*>(a.v) + slab;
-  const IO* uh = HASU ? static_cast<const IO*>(a.u) + slab : nullptr;
+  const IO* uh = has_u ? static_cast<const IO*>(a.u) + slab : kh;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
   // staging role of this thread: token row and 4-element column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
   const int vcol = col0 + c;
-
-  // Tokens of the block that starts at t: at most C, not past the end, and cut after a refresh step.
-  // `phase` is the step index of token t modulo the period; on return it is that of the next block's first
-  // token and `refresh` says whether the block's last token is a refresh step.
-  auto block_len = [&](int t, int& phase, bool& refresh) -> int {
-    int len = T - t < C ? T - t : C;
-    refresh = false;
-    if (period > 0) {
-      const int to_refresh = phase == 0 ? 1 : period - phase + 1;  // tokens up to and including the refresh step
-      refresh = to_refresh <= len;
-      len = refresh ? to_refresh : len;
-      phase += len;                      // at most period + 1
-      phase -= phase >= period ? period : 0;
-    }
-    return len;
-  };
 
   RawRow<IO, EPT> kpre, qpre, upre;
   IO vpre[4];  // V in accumulator layout: V[t0 + 4g + r][col0 + c]
@@ -166,7 +159,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     const unsigned off = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
     kpre.load(kh + off);
     qpre.load(qh + off);
-    if constexpr (HASU) upre.load(uh + off);
+    if (has_u) upre.load(uh + off);
   };
   auto load_v = [&](int t0) {
 #pragma unroll
@@ -186,8 +179,9 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     const float rn = __builtin_amdgcn_rsqf(clamped);
     return rn * fmaf(-0.5f * clamped * rn, rn, 1.5f);
   };
-  // this thread's share of the block [t0, t0 + len): K^, Q (and U) into LDS half `buf`
-  auto stage = [&](int len, int buf) {
+  // this thread's share of a block of `len` live tokens whose first token has step index idx0 (1-based, counted
+  // over the whole sequence): K^, Q (and U) into LDS half `buf`, and the refresh counts of the block
+  auto stage = [&](int len, int idx0, int buf) {
     const bool live = srow < len;
     float x[EPT];
     kpre.unpack(x);
@@ -201,7 +195,8 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     for (int e = 0; e < EPT; ++e) ss = fmaf(x[e], x[e], ss);
     float sm;
     const float rn = inv_norm(row_total(ss), sm);
-    *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg]) = f4{x[0] * rn, x[1] * rn, x[2] * rn, x[3] * rn};
+    const f4 kn = f4{x[0] * rn, x[1] * rn, x[2] * rn, x[3] * rn};
+    *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg]) = kn;
     if (sseg == 0) nks[buf][srow] = sm * rn;  // max(||k||, eps)
     qpre.unpack(x);
 #pragma unroll
@@ -210,43 +205,47 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       x[e] = live ? x[e] : 0.0f;
     }
     *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg]) = f4{x[0], x[1], x[2], x[3]};
-    if constexpr (HASU) {
-      upre.unpack(x);
+    if constexpr (FULL) {
+      if (has_u) {
+        upre.unpack(x);
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) x[e] = live ? x[e] : 0.0f;
-      float uu = 0.0f;
+        for (int e = 0; e < EPT; ++e) x[e] = live ? x[e] : 0.0f;
+        float uu = 0.0f;
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) uu = fmaf(x[e], x[e], uu);
-      float um;
-      const float su = a.u_scale * inv_norm(row_total(uu), um);
-      *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = f4{x[0] * su, x[1] * su, x[2] * su, x[3] * su};
+        for (int e = 0; e < EPT; ++e) uu = fmaf(x[e], x[e], uu);
+        float um;
+        const float su = a.u_scale * inv_norm(row_total(uu), um);
+        *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = f4{x[0] * su, x[1] * su, x[2] * su, x[3] * su};
+      } else {
+        *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = kn;   // u = k^
+      }
+      if (tid <= C) {  // multiples of the period among the step indices idx0 .. idx0 + tid - 1
+        const int n = period > 0 ? (idx0 - 1 + tid) / period - (idx0 - 1) / period : 0;
+        ens[buf][tid] = eta * static_cast<float>(n);
+      }
     }
   };
 
-  int len = 0;
-  int phase = period > 0 ? (a.step_offset + 1) % period : 0;  // of the next block still to be planned
-  bool refresh_here = false;
   if (T > 0) {
-    len = block_len(0, phase, refresh_here);
     load_kqu(0);
     load_v(0);
-    stage(len, 0);
-    if (len < T) load_kqu(len);
+    stage(T < C ? T : C, a.step_offset + 1, 0);
+    if (C < T) load_kqu(C);
   }
   __syncthreads();  // block 0 staged, zks initialised
 
   int blk = 0;
-  for (int t0 = 0; t0 < T; ++blk) {
+  for (int t0 = 0; t0 < T; t0 += C, ++blk) {
     const float* Ks = Ksb[blk & 1];
     const float* Qs = Qsb[blk & 1];
-    if constexpr (!HASU) Us = Ks;
-    const int tn = t0 + len;                         // start of the next block
-    bool refresh_next = false;
-    const int lenn = tn < T ? block_len(tn, phase, refresh_next) : 0;
+    const float* en = ens[blk & 1];
+    if constexpr (!FULL) Us = Ks;
+    const int len = T - t0 < C ? T - t0 : C;
+    const int tn = t0 + C;                           // start of the next block
     auto stage_next = [&]() {
       if (tn < T) {
-        stage(lenn, (blk + 1) & 1);
-        if (tn + lenn < T) load_kqu(tn + lenn);
+        stage(T - tn < C ? T - tn : C, a.step_offset + tn + 1, (blk + 1) & 1);
+        if (tn + C < T) load_kqu(tn + C);
       }
     };
     int cc = c;  // opaque copy: keeps lane-dependent masks from being hoisted out of the loop
@@ -262,7 +261,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const f4 ka = lds4(&Ks[c * LD + 16 * b + 4 * g]);
-      if constexpr (HASU) {
+      if constexpr (FULL) {
         const f4 ua = lds4(&Us[c * LD + 16 * b + 4 * g]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) yt = mfma16(ua[r], At[b][r], yt);
@@ -275,11 +274,23 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], St[b][r], ft);
     }
-    if constexpr (!HASU) xt = yt;
+    if constexpr (FULL) {
+      if (period > 0) {  // y'_t = y_t + eta n_t u_t,  x'_t = x_t + eta n'_t k^_t  (n'_t = n_{t+1})
+        const f4 e0 = lds4(&en[4 * g]);
+        const f4 e1 = f4{e0[1], e0[2], e0[3], en[4 * g + 4]};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          yt[r] = fmaf(e0[r], Us[(4 * g + r) * LD + col0 + c], yt[r]);
+          xt[r] = fmaf(e1[r], Ks[(4 * g + r) * LD + col0 + c], xt[r]);
+        }
+      }
+    } else {
+      xt = yt;
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       Ys[(4 * g + r) * LD + col0 + c] = yt[r];
-      if constexpr (HASU) Xsb[(4 * g + r) * LD + col0 + c] = xt[r];
+      if constexpr (FULL) Xsb[(4 * g + r) * LD + col0 + c] = xt[r];
     }
     __syncthreads();  // (1) Y^T, X^T complete
 
@@ -288,7 +299,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       int slot = 0;
 #pragma unroll
       for (int i = 0; i < kNumGram; ++i) {
-        if (!HASU && (i == kGK || i == kGX || i == kXQ)) continue;
+        if (!FULL && (i == kGK || i == kGX || i == kXQ)) continue;
         if ((i == kQK || i == kQZ) && !norm_out) continue;
         const bool mine = (slot % NW) == w;
         ++slot;
@@ -341,7 +352,14 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       const bool lower = lane < 32;
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
-        const f4 acc = lds4(&Gs[kG][c * LT + s4]);
+        f4 acc = lds4(&Gs[kG][c * LT + s4]);
+        if (FULL && period > 0) {  // entry (c, s) with s < c from its mirror image (s, c): see the header
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float mir = Gs[kG][(s4 + e) * LT + c];
+            acc[e] = (s4 + e < cc) ? mir : acc[e];
+          }
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) m[s4 + e] = (lower ? acc[e] : 0.0f) + ((s4 + e) == cc ? 1.0f : 0.0f);
       }
@@ -382,13 +400,6 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       f4 at = xt;
 #pragma unroll
       for (int r = 0; r < 4; ++r) at = mfma16(mop[r], nwt[r], at);
-      if (refresh_here) {  // uniform: the last live token sees A + eta I
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float kv = Ks[(4 * g + r) * LD + col0 + c];
-          at[r] = (4 * g + r == len - 1) ? fmaf(eta, kv, at[r]) : at[r];
-        }
-      }
       f4 n2 = at * at;
 #pragma unroll
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
@@ -405,12 +416,13 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) At[b] = mfma16(wa[r], nwt[r], At[b]);
       }
-      if (refresh_here) {  // + eta on the diagonal: rows 16w + 4g + r against column 16w + c
+      if (FULL && period > 0) {  // + eta n on the diagonal (rows 16w + 4g + r against column 16w + c), n counted
+        const float en_end = en[len];  // over the live tokens
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
           if (b == w) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) At[b][r] += (4 * g + r == cc) ? eta : 0.0f;
+            for (int r = 0; r < 4; ++r) At[b][r] += (4 * g + r == cc) ? en_end : 0.0f;
           }
         }
       }
@@ -436,15 +448,6 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) {
         pt = mfma16(mop[r], nhm[r], pt);
         aq = mfma16(mop[r], nhq[r], aq);
-      }
-      if (refresh_here) {  // alpha of the last live token carries + eta k^: its read-out weight gains eta k^.q
-        const int tl = len - 1;
-        float kq = 0.0f;
-        for (int j = lane; j < D; j += 64) kq = fmaf(Ks[tl * LD + j], Qs[tl * LD + j], kq);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) kq += __shfl_xor(kq, off);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) aq[r] = (4 * g + r == tl && cc == tl) ? fmaf(eta, kq, aq[r]) : aq[r];
       }
       // rows of P^T on lanes: lane t reads alpha_s . k^_t for all s
       *reinterpret_cast<f4*>(&Ps[c * LT + 4 * g]) = pt;
@@ -520,9 +523,6 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       for (int s = 0; s < C; ++s) zk = fmaf(nks[blk & 1][s], Ks[s * LD + col0 + lane], zk);
       zks[col0 + lane] = zk;
     }
-    t0 = tn;
-    len = lenn;
-    refresh_here = refresh_next;
   }
 
   // ---- final state
@@ -551,8 +551,9 @@ template <int D, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  const void* fn = a.u != nullptr ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true>)
-                                  : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false>);
+  const bool full = a.u != nullptr || a.refresh_period > 0;
+  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true>)
+                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false>);
   return hipLaunchKernel(fn, dim3(a.n_heads), dim3(4 * D), params, 0, stream);
 }
 

@@ -99,8 +99,9 @@ def test_split_sequence_with_every_option_carries_state(mode):
 
 @pytest.mark.parametrize("period", [1, 2, 5, 16, 17, 33])
 @pytest.mark.parametrize("offset", [0, 3])
-def test_block_kernel_cuts_blocks_at_every_refresh_period(period, offset):
-    """Blocks end at refresh steps: periods below, at and above the block length, with a carried phase."""
+def test_block_kernel_takes_refresh_steps_anywhere_inside_a_block(period, offset):
+    """Refresh steps fall anywhere inside the 16-token blocks: periods below, at and above the block length
+    (several refreshes per block, one, or none), with a carried phase."""
     d, T = 32, 77
     q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=300 + period)
     opt = dict(lambda0=0.1, refresh_period=period, refresh_eta=5e-3, step_offset=offset)
