@@ -83,7 +83,8 @@ typedef enum {
  *
  * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
  * With any of them set the SCAN and CHUNKED kernel families apply (AUTO selects CHUNKED where the head
- * size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED). */
+ * size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED).
+ * feature_map on its own costs nothing extra in CHUNKED mode. */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
   float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the

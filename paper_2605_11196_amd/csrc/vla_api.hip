@@ -33,11 +33,14 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   return VLA_OK;
 }
 
-// true when any of the optional lines of Algorithm 1 is switched on
-bool general_path(const vla_opts& o) {
-  return o.u != nullptr || o.refresh_period > 0 || o.normalise_output != 0 || o.feature_map != 0 ||
-         o.zkey0 != nullptr || o.zkey_T != nullptr;
+// true when an optional line of Algorithm 1 that only the general kernels carry is switched on
+bool needs_general_kernel(const vla_opts& o) {
+  return o.u != nullptr || o.refresh_period > 0 || o.normalise_output != 0 || o.zkey0 != nullptr ||
+         o.zkey_T != nullptr;
 }
+// true when any of the optional lines of Algorithm 1 is switched on (the plain block kernel carries the
+// feature map by itself)
+bool general_path(const vla_opts& o) { return needs_general_kernel(o) || o.feature_map != 0; }
 
 // AUTO: head sizes without a block kernel -> scan family; options -> the block kernel that carries them;
 // few heads on a long sequence -> time-parallel (segments of the sequence run concurrently and the S rows
@@ -163,7 +166,7 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
                 : vla::launch_scan(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_CHUNKED:
-      err = general_path(op)
+      err = needs_general_kernel(op)
                 ? vla::launch_chunk_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
                 : vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
       break;

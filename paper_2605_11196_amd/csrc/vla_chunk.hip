@@ -32,7 +32,8 @@
 namespace vla {
 namespace {
 
-template <int D, int NW, typename IO>
+// FMAP: q and k are replaced by ELU(x) + 1 while they are staged (the feature map of Section 3.3).
+template <int D, int NW, typename IO, bool FMAP>
 __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   constexpr int SL = D / NW;       // columns of A (rows of S) owned by one wave
   constexpr int NJ = SL / 16;      // 16-wide tiles in a slab
@@ -133,6 +134,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     const bool ragged = t0 + C > T;   // uniform: only the last block can hold rows past the end
     const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
     kpre.unpack(kx);
+    if constexpr (FMAP) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = kx[e] > 0.0f ? kx[e] + 1.0f : __expf(kx[e]);
+    }
     if (ragged) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
@@ -158,6 +163,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
     }
     qpre.unpack(kx);
+    if constexpr (FMAP) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = kx[e] > 0.0f ? kx[e] + 1.0f : __expf(kx[e]);
+    }
     if (ragged) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
@@ -476,8 +485,9 @@ template <int D, int NW, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO>), dim3(a.n_heads),
-                         dim3(64 * NW), params, 0, stream);
+  const void* fn = a.feature_map ? reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO, true>)
+                                 : reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO, false>);
+  return hipLaunchKernel(fn, dim3(a.n_heads), dim3(64 * NW), params, 0, stream);
 }
 
 }  // namespace
