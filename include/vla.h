@@ -42,7 +42,7 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
  *   AUTO     : the library picks: SCAN when the head size has no block kernel; CHUNKED when an option
- *              of Algorithm 1 is switched on; else TIME_PARALLEL for B*H <= 64 (128 below d = 128) and
+ *              of Algorithm 1 other than feature_map is switched on; else TIME_PARALLEL for B*H <= 64 (128 below d = 128) and
  *              T >= 1024 if the caller passed the workspace vla_forward_workspace_bytes() asks for
  *              (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
@@ -82,9 +82,9 @@ typedef enum {
  * vla_default_opts() and then change fields: later library versions may append fields.
  *
  * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
- * With any of them set the SCAN and CHUNKED kernel families apply (AUTO selects CHUNKED where the head
- * size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns VLA_ERR_UNSUPPORTED).
- * feature_map on its own costs nothing extra in CHUNKED mode. */
+ * With any of them except feature_map set, the SCAN and CHUNKED kernel families apply (AUTO selects
+ * CHUNKED where the head size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns
+ * VLA_ERR_UNSUPPORTED).  feature_map on its own is carried by every mode and changes no routing. */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
   float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the

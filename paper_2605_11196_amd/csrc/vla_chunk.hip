@@ -136,7 +136,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     kpre.unpack(kx);
     if constexpr (FMAP) {
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = kx[e] > 0.0f ? kx[e] + 1.0f : __expf(kx[e]);
+      for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
     }
     if (ragged) {
 #pragma unroll
@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     qpre.unpack(kx);
     if constexpr (FMAP) {
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = kx[e] > 0.0f ? kx[e] + 1.0f : __expf(kx[e]);
+      for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
     }
     if (ragged) {
 #pragma unroll

@@ -58,8 +58,6 @@ enum GramTile {
   kNumGram
 };
 
-__device__ __forceinline__ float elu_plus_one(float x) { return x > 0.0f ? x + 1.0f : __expf(x); }
-
 // FULL: Y and X differ (a separate u, or a refresh period): two sweeps of A and five Gram matrices.
 template <int D, typename IO, bool FULL>
 __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {

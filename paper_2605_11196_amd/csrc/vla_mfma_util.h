@@ -138,6 +138,9 @@ template <int EPT> struct RawRow<uint16_t, EPT> {
     }
   }
 };
+// ELU(x) + 1, the feature map of Section 3.3
+__device__ __forceinline__ float elu_plus_one(float x) { return x > 0.0f ? x + 1.0f : __expf(x); }
+
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t x) { return bf16_to_f32(x); }
 // -x widened to float32: for bf16 the shift and the sign flip are one shift-and-add (adding the top bit is

@@ -110,6 +110,10 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
     const int t = t0 + srow;
     double x[EPT];
     o.widen(x);
+    if (a.feature_map) {   // ELU(x) + 1 in float32, as the kernels that run the recurrence apply it
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) x[e] = static_cast<double>(elu_plus_one(static_cast<float>(x[e])));
+    }
     double ss = 0.0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {

@@ -81,6 +81,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   const int tb = seg * a.seg_blocks * C;                                   // first token of the segment
   const int T = min(a.T, tb + a.seg_blocks * C);                           // one past its last token
   const float eps = a.eps;
+  const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are staged
   const int col0 = SL * w;
   const int nblk = (a.T + C - 1) / C;                                      // blocks of the whole sequence
 
@@ -132,6 +133,10 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
       float kx[EPT];
       const bool live = t0 + srow < T;
       kpre.unpack(kx);
+      if (fmap) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
+      }
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
       float ss = 0.0f;
@@ -151,6 +156,10 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
         *reinterpret_cast<f4*>(kg + e) = kv;
       }
       qpre.unpack(kx);
+      if (fmap) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
+      }
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
 #pragma unroll
@@ -399,6 +408,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const bool fmap = a.feature_map != 0;   // q is replaced by ELU(x) + 1 as it is consumed
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -461,7 +471,13 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       float qx[4];
-      if constexpr (!MAP) cur.qa[b].unpack(qx);
+      if constexpr (!MAP) {
+        cur.qa[b].unpack(qx);
+        if (fmap) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) qx[r] = elu_plus_one(qx[r]);
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         ft = mfma16(cur.ka[b][r], st[b][r], ft);
@@ -592,6 +608,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
+  const bool fmap = a.feature_map != 0;   // q is replaced by ELU(x) + 1 as it is consumed
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -651,6 +668,10 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     if constexpr (!MAP) {
       float x[4];
       r.qx.unpack(x);
+      if (fmap) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = elu_plus_one(x[i]);
+      }
       *reinterpret_cast<f4*>(&s.Qs[krow * LD + kcol]) = f4{x[0], x[1], x[2], x[3]};
     }
   };

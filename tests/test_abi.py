@@ -65,6 +65,10 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=vla.MODE_SCAN, normalise_output=1) == vla.MODE_SCAN
     for mode in (vla.MODE_TWO_PHASE, vla.MODE_TIME_PARALLEL):
         assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, normalise_output=1) == -1
+        assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, feature_map=1) == mode
+    # the feature map alone keeps the plain routing
+    assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, feature_map=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_CHUNKED, feature_map=1) == -1
 
 
@@ -85,7 +89,7 @@ def call(**kw):
     (dict(B=0), 1), (dict(H=-1), 1), (dict(T=-1), 1), (dict(d_k=0, d_v=0), 1),
     (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
     (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
-    (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, feature_map=1), 2),
+    (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, normalise_output=1), 2),
     (dict(mode=2, d_k=96, d_v=96, refresh_period=3), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q

@@ -139,6 +139,31 @@ def test_block_kernel_with_options_holds_the_tolerance_on_a_long_sequence():
     print(assert_close(got, ref, 1e-4))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,T,mode,segments", [(64, 2100, 4, 5), (128, 1100, 4, 3), (32, 700, 4, 4), (64, 300, 3, None),
+                                               (128, 130, 3, None), (128, 257, 2, None)])
+def test_feature_map_alone_runs_on_every_block_mode(d, T, mode, segments, dtype):
+    """ELU+1 on q and k with no other option: plain block kernel, two-phase and time-parallel modes (the Gram
+    sums behind the segment boundaries are then sums over the mapped keys)."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    q, k, v = vla_inputs.gaussian_qkv(1, 3, T, d, seed=d + T)
+    if dtype == "bf16":
+        q, k, v = (vla_inputs.round_to_bf16(x) for x in (q, k, v))
+    ref = oracle.forward(q, k, v, lambda0=0.1, feature_map=True)
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(tdt)
+    o, S_T, A_T = vla.vla_forward(t(q), t(k), t(v), lambda0=0.1, feature_map=True, mode=mode, segments=segments)
+    torch.cuda.synchronize()
+    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+    print(d, T, mode, dtype, errs)
+    assert max(errs.values()) <= TOL[dtype], errs
+
+
 def test_options_are_refused_by_the_segment_modes_and_taken_by_the_block_kernel():
     import torch
 
