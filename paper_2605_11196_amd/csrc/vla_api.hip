@@ -26,6 +26,8 @@ int check_shape(int B, int H, int T, int d_k, int d_v, int io_dtype, const vla_o
   if (o.segments < 0) return VLA_ERR_INVALID_ARG;
   if (!(o.lambda0 > 0.0f) || !(o.eps > 0.0f)) return VLA_ERR_INVALID_ARG;
   if (o.refresh_period < 0 || o.step_offset < 0 || !(o.u_scale == o.u_scale)) return VLA_ERR_INVALID_ARG;
+  // step indices (step_offset + t + 1, with a block of look-ahead) are 32-bit in the kernels
+  if (static_cast<long long>(o.step_offset) + T + 64 > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
   if (static_cast<long long>(B) * H > 0x7fffffffLL) return VLA_ERR_INVALID_ARG;
   // kernels address one head's [T, d] slab with 32-bit byte offsets
   if (static_cast<long long>(T) * (d_k > d_v ? d_k : d_v) * 4 >= 0x7fffffffLL) return VLA_ERR_UNSUPPORTED;

@@ -88,7 +88,7 @@ def call(**kw):
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), 1), (dict(H=-1), 1), (dict(T=-1), 1), (dict(d_k=0, d_v=0), 1),
     (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
-    (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
+    (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(step_offset=2**31 - 20, refresh_period=4), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
     (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, normalise_output=1), 2),
     (dict(mode=2, d_k=96, d_v=96, refresh_period=3), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
