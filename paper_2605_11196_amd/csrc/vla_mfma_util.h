@@ -74,8 +74,6 @@ __device__ __forceinline__ void scale_cols(const float (&m)[C], float (&nm)[C], 
   }
 }
 
-__device__ __forceinline__ float io_load(const float* p) { return *p; }
-__device__ __forceinline__ float io_load(const uint16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void io_store(float* p, float x) { *p = x; }
 __device__ __forceinline__ void io_store(uint16_t* p, float x) { *p = f32_to_bf16_rne(x); }
 // Two values to two addresses.  For bf16 the pair is rounded (to nearest even) by one packed hardware
@@ -101,10 +99,6 @@ template <int EPT> struct RawRow<float, EPT> {
 #pragma unroll
     for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const float4*>(p + 4 * e);
   }
-  __device__ __forceinline__ void zero() {
-#pragma unroll
-    for (int e = 0; e < EPT / 4; ++e) v[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-  }
   __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
 #pragma unroll
     for (int e = 0; e < EPT / 4; ++e) {
@@ -121,10 +115,6 @@ template <int EPT> struct RawRow<uint16_t, EPT> {
   __device__ __forceinline__ void load(const uint16_t* p) {
 #pragma unroll
     for (int e = 0; e < NP; ++e) v[e] = *reinterpret_cast<const Piece*>(p + 2 * PW * e);
-  }
-  __device__ __forceinline__ void zero() {
-#pragma unroll
-    for (int e = 0; e < NP; ++e) v[e] = Piece(0u);
   }
   __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
 #pragma unroll
