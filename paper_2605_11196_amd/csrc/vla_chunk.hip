@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 
   const int head = blockIdx.x;
   const int tid = threadIdx.x;
-  const int w = tid >> 6;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known to be uniform
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
