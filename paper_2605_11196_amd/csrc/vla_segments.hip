@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
   const int seg = blockIdx.x - head * a.n_seg;
   if (seg == a.n_seg - 1) return;
   const int tid = threadIdx.x;
-  const int w = tid >> 6;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
@@ -327,7 +327,7 @@ __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, f
   __shared__ __align__(16) float xs[2][16 * LDX];
   const int head = blockIdx.x / NB;
   const int row0 = (blockIdx.x - head * NB) * 16;
-  const int jb = threadIdx.x >> 6;    // column slice of this wave
+  const int jb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // column slice of this wave
   const int lane = threadIdx.x & 63;
   const int c = lane & 15;
   const int g = lane >> 4;

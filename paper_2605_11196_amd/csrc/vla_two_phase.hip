@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
   const int tid = threadIdx.x;
-  const int w = tid >> 6;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
@@ -591,7 +591,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const int seg = hs - head * a.n_seg;
   if (MAP && seg == a.n_seg - 1) return;         // nothing follows the last segment
   const int tid = threadIdx.x;
-  const int w = tid >> 6;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
