@@ -62,6 +62,10 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 32, 64 and 128.
 bool chunk_supported(int d);
 hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+// Same block form, several heads per workgroup (vla_chunk_multihead.hip); head sizes 32 and 64.
+// launch_chunk picks it by head size and head count (prefer_multihead).
+bool prefer_multihead(int d, int n_heads);
+hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 // Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); same head sizes.
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 

@@ -257,3 +257,14 @@ def test_block_kernel_with_options_is_deterministic_and_replays_in_a_hip_graph(d
     rel = lambda a, b: float((a - b).abs().max() / b.abs().max())
     assert rel(torch.cat(outs, dim=2), want[0]) < 1e-4
     assert rel(S2, want[1]) < 1e-4 and rel(A2, want[2]) < 1e-4 and rel(z2, want[3]) < 1e-5
+
+
+@pytest.mark.parametrize("d,B,H", [(32, 5, 210), (64, 3, 100)])
+def test_feature_map_with_many_small_heads(d, B, H):
+    """The block kernel that shares a workgroup between several heads carries the feature map too."""
+    q, k, v = vla_inputs.gaussian_qkv(B, H, 27, d, seed=4000 + d)
+    got, ref = run_both(q, k, v, lambda0=0.1, feature_map=True, mode=BLOCK)
+    errs = dict(o=slab_rel_err(got["o"], ref["o"], 2), S=slab_rel_err(got["S_T"], ref["S_T"], 2),
+                A=slab_rel_err(got["A_T"], ref["A_T"], 2))
+    print(d, B * H, errs)
+    assert max(errs.values()) <= 1e-4, errs

@@ -371,3 +371,24 @@ def test_block_modes_hold_the_float32_tolerance_on_long_sequences(d, T):
         errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(S_T, ref["S_T"], 2),
                     A=slab_rel_err(A_T, ref["A_T"], 2))
         assert max(errs.values()) <= TOL["f32"], (mode, errs)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,B,H,T", [(64, 7, 43, 40),      # 301 heads: two heads per workgroup, one spare wave pair
+                                     (64, 16, 64, 21),     # 1024 heads: whole rounds of two-head workgroups
+                                     (32, 11, 101, 35),    # 1111 heads: four heads per workgroup, one spare wave
+                                     (32, 8, 256, 17)])    # 2048 heads
+def test_many_small_heads_share_a_workgroup(d, B, H, T, dtype):
+    """Launches large enough for the block kernel that puts several heads on one workgroup (d = 32, 64):
+    ragged last block, head counts that do not fill the last workgroup, given initial state."""
+    rng = np.random.default_rng(d + B)
+    q, k, v = vla_inputs.gaussian_qkv(B, H, T, d, seed=3000 + d + B)
+    k[:, :, 3] = 0.0
+    S0 = rng.standard_normal((B, H, d, d)).astype(np.float32)
+    m = rng.standard_normal((B, H, d, d)).astype(np.float32) / np.sqrt(d)
+    A0 = np.eye(d, dtype=np.float32) * 3.0 + m @ m.transpose(0, 1, 3, 2)
+    A0 = 0.5 * (A0 + A0.transpose(0, 1, 3, 2))
+    errs, _, _ = check_parity(q, k, v, S0, A0, dtype=dtype, mode=2)
+    print(d, B * H, T, dtype, errs)
+    errs, _, _ = check_parity(q[:, :, :16], k[:, :, :16], v[:, :, :16], dtype=dtype, mode=2)
+    print(d, B * H, 16, dtype, errs)
