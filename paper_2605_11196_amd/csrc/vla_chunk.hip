@@ -40,9 +40,15 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   constexpr int NB = D / 16;       // 16-row blocks over the whole head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
   constexpr int NT = 64 * NW;
-  constexpr int EPT = C * D / NT;  // staged elements per thread per tensor
-  constexpr int TPR = D / EPT;     // threads per token row
-  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
+  // Staging: a token row is split over TPR threads of EPT elements each.  For the power-of-two head sizes every
+  // thread stages; at d = 96 a row takes 6 threads of 16 elements in a group of 8 (two lanes of each group and
+  // the third wave stage nothing), so that a row never straddles a wave and sums with a power-of-two shuffle.
+  constexpr int TPR0 = NT / C;                   // thread slots per row when every thread stages
+  constexpr bool PADDED = (TPR0 & (TPR0 - 1)) != 0;
+  constexpr int EPT = PADDED ? 16 : C * D / NT;  // staged elements per thread per tensor
+  constexpr int TPR = PADDED ? 8 : D / EPT;      // thread slots per token row
+  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0 && C * TPR <= NT && D % EPT == 0 &&
+                D / EPT <= TPR, "staging layout");
 
   __shared__ __align__(16) float Ksb[2][C * LD];      // K^  [t][j], double-buffered over blocks
   __shared__ __align__(16) float Qsb[2][C * LD];      // Q   [t][j]
@@ -106,6 +112,8 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   // staging role of this thread: token row and column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
+  const bool stager = !PADDED || (tid < C * TPR && sseg < D);    // this thread holds a row segment
+  const bool stage_wave = !PADDED || tid < C * TPR;              // uniform per wave
   const int vcol = col0 + c;  // first column this lane touches in accumulator layout
 
   RawRow<IO, EPT> kpre, qpre;
@@ -114,10 +122,12 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   // Loads never branch or wait: rows past the end are read from the last valid row and replaced by
   // zeros when the registers are consumed (later).  Offsets are 32-bit from the per-head base pointers.
   auto load_kq = [&](int t0) {
-    const int tr = t0 + srow;
-    const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
-    kpre.load(kh + koff);
-    qpre.load(qh + koff);
+    if (stager) {
+      const int tr = t0 + srow;
+      const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+      kpre.load(kh + koff);
+      qpre.load(qh + koff);
+    }
   };
   auto load_v = [&](int t0) {
 #pragma unroll
@@ -130,15 +140,21 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   };
   // normalise this thread's share of the keys of the block starting at t0 and put K^, Q into LDS half `buf`
   auto stage = [&](int t0, int buf) {
+    if (!stage_wave) return;
     float kx[EPT];
     const bool ragged = t0 + C > T;   // uniform: only the last block can hold rows past the end
-    const bool live = t0 + srow < T;  // rows past the end of the sequence become zero tokens
-    kpre.unpack(kx);
+    const bool live = t0 + srow < T && stager;  // rows past the end of the sequence become zero tokens
+    if (stager) {
+      kpre.unpack(kx);
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) kx[e] = 0.0f;
+    }
     if constexpr (FMAP) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
     }
-    if (ragged) {
+    if (ragged || PADDED) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
     }
@@ -147,7 +163,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
     // the TPR = 16 threads of a token row are one DPP row; 1 / max(||k||, eps) = rsqrt(max(||k||^2, eps^2)),
     // hardware reciprocal square root refined by one Newton step
-    static_assert(TPR == 16 || TPR < 16, "a token row within one DPP row");
     if constexpr (TPR == 16) {
       ss = row_sum16(ss);
     } else {
@@ -157,6 +172,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     const float sm = fmaxf(ss, eps * eps);
     float rn = __builtin_amdgcn_rsqf(sm);
     rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f);
+    if (!stager) return;
 #pragma unroll
     for (int e = 0; e < EPT; e += 4) {
       *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg + e]) =
@@ -492,7 +508,7 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-bool chunk_supported(int d) { return d == 32 || d == 64 || d == 128; }
+bool chunk_supported(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
 
 // Several heads per workgroup (vla_chunk_multihead.hip) or one?  Measured on one MI355X, T = 8192:
 //   d = 64 (two-wave workgroups here, four-wave ones of two heads there; both hold 1024 heads per chip at a
@@ -518,6 +534,7 @@ hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t s
   switch (d) {
     case 32: return bf ? launch<32, 1, uint16_t>(a, stream) : launch<32, 1, float>(a, stream);
     case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
+    case 96: return bf ? launch<96, 3, uint16_t>(a, stream) : launch<96, 3, float>(a, stream);
     case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;
   }

@@ -69,7 +69,12 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     # the feature map alone keeps the plain routing
     assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, feature_map=1) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_CHUNKED, feature_map=1) == -1
+    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == -1
+    # d = 96: the plain block kernel (with or without the feature map), no segment modes
+    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16) == vla.MODE_SCAN
 
 
 FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on these paths
@@ -133,7 +138,7 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(1, 16, 512, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_SCAN
+    assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED   # no segment modes at d = 96
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_SCAN      # d_k != d_v
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED) == -1
     assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == -1
