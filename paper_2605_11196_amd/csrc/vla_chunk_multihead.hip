@@ -34,40 +34,38 @@ __device__ __forceinline__ float row_bcast(float x) {
   return r;
 }
 
-template <int T_, int J_>
-__device__ __forceinline__ void chol_trailing(float (&m)[C], float nli, float li) {
-  if constexpr (J_ < C) {
-    fmac_row_bcast<J_>(m[J_], nli, li);            // M[c][j] -= L[j][t] L[c][t]
-    chol_trailing<T_, J_ + 1>(m, nli, li);
+// Cholesky of the symmetric positive definite matrix whose row c sits in lane c of every 16-lane row
+// (m[s] = M[c][s]) together with X = L^{-1} by forward substitution, columns on lanes.  On exit m[s] = L[c][s]
+// for s <= c (entries above the diagonal are not meaningful) and X[t] = L^{-1}[t][c].
+//   step t:  L[c][t] = M[c][t] / sqrt(pivot);  M[c][j] -= L[j][t] L[c][t] for j > t   (independent updates)
+//            X[t][c] = (delta_tc - sum_{s<t} L[t][s] X[s][c]) / L[t][t]               (one dependent chain)
+// L[j][t] and L[t][s] are another lane's registers of the same row: DPP row broadcasts folded into the
+// multiply-adds.  The two instruction streams of a step are interleaved so that the independent updates cover
+// the latency of the dependent chain.
+template <int T_, int I_>
+__device__ __forceinline__ void chol_linv_ops(float (&m)[C], float nli, float li, const float (&nl)[C],
+                                              const float (&X)[C], float& acc) {
+  if constexpr (I_ < C - 1) {
+    if constexpr (T_ + 1 + I_ < C) fmac_row_bcast<T_ + 1 + I_>(m[T_ + 1 + I_], nli, li);
+    if constexpr (I_ < T_) fmac_row_bcast<T_>(acc, nl[I_], X[I_]);
+    chol_linv_ops<T_, I_ + 1>(m, nli, li, nl, X, acc);
   }
 }
-// Cholesky of the symmetric positive definite matrix whose row c sits in lane c of every 16-lane row
-// (m[s] = M[c][s]); on exit m[s] = L[c][s] for s <= c (entries above the diagonal are not meaningful) and
-// ri[t] = 1 / L[t][t] in every lane.
 template <int T_>
-__device__ __forceinline__ void chol_rows(float (&m)[C], float (&ri)[C]) {
+__device__ __forceinline__ void chol_linv_rows(float (&m)[C], float (&nl)[C], float (&X)[C], int c) {
   if constexpr (T_ < C) {
     asm volatile("s_nop 1" : "+v"(m[T_]));         // a DPP read of a VGPR needs 2 wait states after its write
     const float p = row_bcast<T_>(m[T_]);          // pivot = delta_t >= 1
-    ri[T_] = __builtin_amdgcn_rsqf(p);             // 1 ulp; L only has to satisfy L L^T = I + G to rounding
-    const float li = m[T_] * ri[T_];               // lane c: L[c][t]
+    const float ri = __builtin_amdgcn_rsqf(p);     // 1 ulp; L only has to satisfy L L^T = I + G to rounding
+    const float li = m[T_] * ri;                   // lane c: L[c][t]
     m[T_] = li;
     float nli = -li;
     asm volatile("s_nop 1" : "+v"(nli));
-    chol_trailing<T_, T_ + 1>(m, nli, li);
-    chol_rows<T_ + 1>(m, ri);
-  }
-}
-
-// X = L^{-1} by forward substitution, columns on lanes: X[t] = L^{-1}[t][c] in lane c.
-// X[t][c] = (delta_tc - sum_{s<t} L[t][s] X[s][c]) / L[t][t]; L[t][s] is lane t's register, broadcast by DPP.
-template <int T_>
-__device__ __forceinline__ void linv_rows(const float (&nl)[C], const float (&ri)[C], float (&X)[C], int c) {
-  if constexpr (T_ < C) {
+    nl[T_] = nli;
     float acc = (c == T_) ? 1.0f : 0.0f;
-    ZRow<T_, 0>::run(nl, X, acc);
-    X[T_] = acc * ri[T_];
-    linv_rows<T_ + 1>(nl, ri, X, c);
+    chol_linv_ops<T_, 0>(m, nli, li, nl, X, acc);
+    X[T_] = acc * ri;
+    chol_linv_rows<T_ + 1>(m, nl, X, c);
   }
 }
 
@@ -300,7 +298,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
       r_pass();
       stage_next();
     } else {
-      float m[C], ri[C];
+      float m[C];
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
         f4 acc = lds4(&Gp[hrow][0][0][c * LT + s4]);
@@ -309,12 +307,8 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
 #pragma unroll
         for (int e = 0; e < 4; ++e) m[s4 + e] = acc[e] + ((s4 + e) == cc ? 1.0f : 0.0f);
       }
-      chol_rows<0>(m, ri);
       float nl[C], X[C];
-#pragma unroll
-      for (int s = 0; s < C; ++s) nl[s] = -m[s];
-      asm volatile("s_nop 1" : "+v"(nl[0]));
-      linv_rows<0>(nl, ri, X, cc);
+      chol_linv_rows<0>(m, nl, X, cc);
       if (g < HPW) {
 #pragma unroll
         for (int t = 0; t < C; ++t) Lis[hrow][t * LT + c] = X[t];
