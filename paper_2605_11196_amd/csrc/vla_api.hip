@@ -50,7 +50,8 @@ bool general_path(const vla_opts& o) { return needs_general_kernel(o) || o.featu
 // spread over d/16 times more workgroups than there are heads); otherwise the fused block kernel.
 int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
-  if (d != d_v || !vla::chunk_supported(d)) return VLA_MODE_SCAN;
+  if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
+  if (d != d_v) return needs_general_kernel(o) ? VLA_MODE_SCAN : VLA_MODE_CHUNKED;   // rectangular heads
   if (needs_general_kernel(o)) return vla::block_family_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
   if (!vla::block_family_supported(d)) return VLA_MODE_CHUNKED;   // d = 96: the plain block kernel only
   const long long heads = static_cast<long long>(B) * H;
@@ -62,7 +63,8 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
 
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernels are square only
-  if (d != d_v || !vla::chunk_supported(d)) return false;
+  if (!vla::chunk_supported(d, d_v)) return false;
+  if (d != d_v) return mode == VLA_MODE_CHUNKED && !needs_general_kernel(o);   // the plain block kernel only
   if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::block_family_supported(d);
   // the segment modes carry the feature map, no other option
   if (mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
@@ -175,7 +177,7 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
     case VLA_MODE_CHUNKED:
       err = needs_general_kernel(op)
                 ? vla::launch_chunk_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
-                : vla::launch_chunk(a, d_k, io_dtype, static_cast<hipStream_t>(stream));
+                : vla::launch_chunk(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_TWO_PHASE:
       err = vla::launch_two_phase(a, d_k, io_dtype, static_cast<hipStream_t>(stream));

@@ -33,10 +33,15 @@ namespace vla {
 namespace {
 
 // FMAP: q and k are replaced by ELU(x) + 1 while they are staged (the feature map of Section 3.3).
-template <int D, int NW, typename IO, bool FMAP>
+// DV: head size of v and o (rows of S); the wave that owns columns [SL w, SL w + SL) of A owns rows
+// [SLV w, SLV w + SLV) of S.
+template <int D, int DV, int NW, typename IO, bool FMAP>
 __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
-  constexpr int SL = D / NW;       // columns of A (rows of S) owned by one wave
-  constexpr int NJ = SL / 16;      // 16-wide tiles in a slab
+  constexpr int SL = D / NW;       // columns of A owned by one wave
+  constexpr int NJ = SL / 16;      // 16-wide tiles in a slab of A
+  constexpr int SLV = DV / NW;     // rows of S owned by one wave
+  constexpr int NJV = SLV / 16;    // 16-wide tiles in a slab of S^T
+  static_assert(SLV % 16 == 0 && NJV >= 1, "a wave owns whole tiles of S");
   constexpr int NB = D / 16;       // 16-row blocks over the whole head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
   constexpr int NT = 64 * NW;
@@ -70,20 +75,21 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   const int g = lane >> 4;
   const int T = a.T;
   const float eps = a.eps;
-  const int col0 = SL * w;  // first column of this wave's slab
+  const int col0 = SL * w;    // first column of this wave's slab of A
+  const int row0 = SLV * w;   // first row of this wave's slab of S
 
   // ---- resident state: accumulator tiles
   // At[b][jn][r] = A[16b + 4g + r][col0 + 16jn + c]
-  // St[b][jn][r] = S[col0 + 16jn + c][16b + 4g + r]      (i.e. tiles of S^T)
-  f4 At[NB][NJ], St[NB][NJ];
+  // St[b][jn][r] = S[row0 + 16jn + c][16b + 4g + r]      (i.e. tiles of S^T)
+  f4 At[NB][NJ], St[NB][NJV];
   {
     const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
-    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * DV * D : nullptr;
     const float diag = 1.0f / a.lambda0;
     const int arc = (4 * g) * D + col0 + c;  // A[4g][col0 + c]
-    const int src = (col0 + c) * D + 4 * g;  // S[col0 + c][4g]
+    const int src = (row0 + c) * D + 4 * g;  // S[row0 + c][4g]
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NB; ++b) {
 #pragma unroll
       for (int jn = 0; jn < NJ; ++jn) {
         if (A0) {
@@ -94,6 +100,9 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           for (int r = 0; r < 4; ++r)
             At[b][jn][r] = (16 * b + 4 * g + r == col0 + 16 * jn + c) ? diag : 0.0f;
         }
+      }
+#pragma unroll
+      for (int jn = 0; jn < NJV; ++jn) {
         if (S0) {
           const float4 x = *reinterpret_cast<const float4*>(S0 + src + 16 * jn * D + 16 * b);
           St[b][jn] = f4{x.x, x.y, x.z, x.w};
@@ -101,23 +110,25 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           St[b][jn] = f4{0, 0, 0, 0};
         }
       }
+    }
   }
 
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slab_v = static_cast<size_t>(head) * static_cast<size_t>(T) * DV;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
-  const IO* vh = static_cast<const IO*>(a.v) + slab;
-  IO* oh = static_cast<IO*>(a.o) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slab_v;
+  IO* oh = static_cast<IO*>(a.o) + slab_v;
 
   // staging role of this thread: token row and column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
   const bool stager = !PADDED || (tid < C * TPR && sseg < D);    // this thread holds a row segment
   const bool stage_wave = !PADDED || tid < C * TPR;              // uniform per wave
-  const int vcol = col0 + c;  // first column this lane touches in accumulator layout
+  const int vcol = row0 + c;  // first element of a v / o row this lane touches in accumulator layout
 
   RawRow<IO, EPT> kpre, qpre;
-  IO vpre[NJ][4];  // V^T in accumulator layout: V[t0 + 4g + r][col0 + 16jn + c]
+  IO vpre[NJV][4];  // V^T in accumulator layout: V[t0 + 4g + r][row0 + 16jn + c]
 
   // Loads never branch or wait: rows past the end are read from the last valid row and replaced by
   // zeros when the registers are consumed (later).  Offsets are 32-bit from the per-head base pointers.
@@ -133,9 +144,9 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int t = t0 + 4 * g + r;
-      const unsigned voff = static_cast<unsigned>((t < T ? t : T - 1) * D + vcol);
+      const unsigned voff = static_cast<unsigned>((t < T ? t : T - 1) * DV + vcol);
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) vpre[jn][r] = vh[voff + 16 * jn];
+      for (int jn = 0; jn < NJV; ++jn) vpre[jn][r] = vh[voff + 16 * jn];
     }
   };
   // normalise this thread's share of the keys of the block starting at t0 and put K^, Q into LDS half `buf`
@@ -218,14 +229,14 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         if (t0 + 2 * C < T) load_kq(t0 + 2 * C);
       }
     };
-    f4 ft[NJ];  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+    f4 ft[NJV];  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
 #pragma unroll
-    for (int jn = 0; jn < NJ; ++jn)
+    for (int jn = 0; jn < NJV; ++jn)
 #pragma unroll
       for (int r = 0; r < 4; ++r) ft[jn][r] = neg_widen(vpre[jn][r]);
     if (t0 + C > T) {  // uniform: rows past the end of the sequence are zero tokens
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn)
+      for (int jn = 0; jn < NJV; ++jn)
 #pragma unroll
         for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? ft[jn][r] : 0.0f;
     }
@@ -255,7 +266,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int jn = 0; jn < NJ; ++jn) ft[jn] = mfma16(ka[r], St[b][jn][r], ft[jn]);
+        for (int jn = 0; jn < NJV; ++jn) ft[jn] = mfma16(ka[r], St[b][jn][r], ft[jn]);
     }
     // ================= partial Gram matrices over this wave's columns (independent accumulators)
     {
@@ -293,17 +304,17 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     // L[j][t] serves the Cholesky trailing update and the forward substitution for L^{-1}.
     int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
     asm volatile("" : "+v"(cc));
-    f4 ot[NJ];  // R^T = Q S0^T, later O^T
+    f4 ot[NJV];  // R^T = Q S0^T, later O^T
     auto r_pass = [&]() {
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) ot[jn] = f4{0, 0, 0, 0};
+      for (int jn = 0; jn < NJV; ++jn) ot[jn] = f4{0, 0, 0, 0};
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-          for (int jn = 0; jn < NJ; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
+          for (int jn = 0; jn < NJV; ++jn) ot[jn] = mfma16(qa[r], St[b][jn][r], ot[jn]);
       }
     };
     if (w != sw) {  // the other waves use the matrix pipes while wave sw factorises
@@ -428,11 +439,11 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 
     // ================= -E^T = Z (-F^T), R^T = Q S0^T, O^T = R^T + (-NQ^T)(-E^T), store o;
     // ce = (-c) (-E^T) = diag(c) E^T
-    f4 ce[NJ];
+    f4 ce[NJV];
     {
       const f4 za = lds4(&Zs[c * LT + 4 * g]);
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) {
+      for (int jn = 0; jn < NJV; ++jn) {
         f4 et = f4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[jn][r], et);
@@ -442,7 +453,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
       const f4 cg = lds4(&cvec[4 * g]);
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) {
+      for (int jn = 0; jn < NJV; ++jn) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) ot[jn] = mfma16(nqa[r], ft[jn][r], ot[jn]);
         ce[jn] = ft[jn] * cg;
@@ -451,11 +462,11 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) {
         const int t = t0 + 4 * g + r;
         if (t < T) {
-          const unsigned ooff = static_cast<unsigned>(t * D + vcol);
+          const unsigned ooff = static_cast<unsigned>(t * DV + vcol);
 #pragma unroll
-          for (int jn = 0; jn + 1 < NJ; jn += 2)
+          for (int jn = 0; jn + 1 < NJV; jn += 2)
             io_store2(oh + ooff + 16 * jn, oh + ooff + 16 * jn + 16, ot[jn][r], ot[jn + 1][r]);
-          if (NJ % 2 == 1) io_store(oh + ooff + 16 * (NJ - 1), ot[NJ - 1][r]);
+          if (NJV % 2 == 1) io_store(oh + ooff + 16 * (NJV - 1), ot[NJV - 1][r]);
         }
       }
     }
@@ -468,7 +479,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int jn = 0; jn < NJ; ++jn) St[b][jn] = mfma16(wa[r], ce[jn][r], St[b][jn]);
+        for (int jn = 0; jn < NJV; ++jn) St[b][jn] = mfma16(wa[r], ce[jn][r], St[b][jn]);
     }
     if (w == sw2) update_A();
   }
@@ -476,34 +487,40 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   // ---- final state
   {
     float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
-    float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+    float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * DV * D : nullptr;
     int g2 = g;
     asm volatile("" : "+v"(g2));  // recompute the addresses here instead of carrying them over the loop
     const int arc = (4 * g2) * D + col0 + c;
-    const int src = (col0 + c) * D + 4 * g2;
+    const int src = (row0 + c) * D + 4 * g2;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NB; ++b) {
+      if (AT) {
 #pragma unroll
-      for (int jn = 0; jn < NJ; ++jn) {
-        if (AT) {
+        for (int jn = 0; jn < NJ; ++jn)
 #pragma unroll
           for (int r = 0; r < 4; ++r) AT[arc + (16 * b + r) * D + 16 * jn] = At[b][jn][r];
-        }
-        if (ST) {
+      }
+      if (ST) {
+#pragma unroll
+        for (int jn = 0; jn < NJV; ++jn)
           *reinterpret_cast<float4*>(ST + src + 16 * jn * D + 16 * b) =
               make_float4(St[b][jn][0], St[b][jn][1], St[b][jn][2], St[b][jn][3]);
-        }
       }
+    }
   }
 }
 
-template <int D, int NW, typename IO>
+template <int D, int DV, int NW, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  const void* fn = a.feature_map ? reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO, true>)
-                                 : reinterpret_cast<const void*>(&chunk_kernel<D, NW, IO, false>);
+  const void* fn = a.feature_map ? reinterpret_cast<const void*>(&chunk_kernel<D, DV, NW, IO, true>)
+                                 : reinterpret_cast<const void*>(&chunk_kernel<D, DV, NW, IO, false>);
   return hipLaunchKernel(fn, dim3(a.n_heads), dim3(64 * NW), params, 0, stream);
+}
+template <int D, int DV, int NW>
+hipError_t launch_io(const ForwardArgs& a, int io_dtype, hipStream_t stream) {
+  return io_dtype == 1 ? launch<D, DV, NW, uint16_t>(a, stream) : launch<D, DV, NW, float>(a, stream);
 }
 
 }  // namespace
@@ -528,14 +545,26 @@ bool prefer_multihead(int d, int n_heads) {
   return false;
 }
 
-hipError_t launch_chunk(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
-  const bool bf = io_dtype == 1;
-  if (prefer_multihead(d, a.n_heads)) return launch_chunk_multihead(a, d, io_dtype, stream);
-  switch (d) {
-    case 32: return bf ? launch<32, 1, uint16_t>(a, stream) : launch<32, 1, float>(a, stream);
-    case 64: return bf ? launch<64, 2, uint16_t>(a, stream) : launch<64, 2, float>(a, stream);
-    case 96: return bf ? launch<96, 3, uint16_t>(a, stream) : launch<96, 3, float>(a, stream);
-    case 128: return bf ? launch<128, 4, uint16_t>(a, stream) : launch<128, 4, float>(a, stream);
+// Value heads as wide as the key heads, or half or twice as wide (the wave that owns 32 columns of A then owns
+// 16 or 64 rows of S).
+bool chunk_supported(int d_k, int d_v) {
+  if (d_k == d_v) return chunk_supported(d_k);
+  return (d_k == 32 && (d_v == 16 || d_v == 64)) || (d_k == 64 && (d_v == 32 || d_v == 128)) ||
+         (d_k == 128 && d_v == 64);
+}
+
+hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
+  if (d_k == d_v && prefer_multihead(d_k, a.n_heads)) return launch_chunk_multihead(a, d_k, io_dtype, stream);
+  switch (d_k * 1000 + d_v) {
+    case 32032: return launch_io<32, 32, 1>(a, io_dtype, stream);
+    case 64064: return launch_io<64, 64, 2>(a, io_dtype, stream);
+    case 96096: return launch_io<96, 96, 3>(a, io_dtype, stream);
+    case 128128: return launch_io<128, 128, 4>(a, io_dtype, stream);
+    case 32016: return launch_io<32, 16, 1>(a, io_dtype, stream);
+    case 32064: return launch_io<32, 64, 1>(a, io_dtype, stream);
+    case 64032: return launch_io<64, 32, 2>(a, io_dtype, stream);
+    case 64128: return launch_io<64, 128, 2>(a, io_dtype, stream);
+    case 128064: return launch_io<128, 64, 4>(a, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }

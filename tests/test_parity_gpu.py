@@ -349,12 +349,27 @@ def test_value_heads_half_or_twice_as_wide_as_key_heads(dk, dv, dtype):
     dev = torch.device("cuda:0")
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     tq, tk, tv = (torch.from_numpy(x).to(dev).to(tdt) for x in (q, k, v))
-    o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1)
-    torch.cuda.synchronize()
-    assert tuple(o.shape) == (B, H, T, dv) and tuple(S_T.shape) == (B, H, dv, dk) and tuple(A_T.shape) == (B, H, dk, dk)
-    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
-                A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
-    assert max(errs.values()) <= TOL[dtype], errs
+    io = vla.VLA_F32 if dtype == "f32" else vla.VLA_BF16
+    modes = [m for m in (None, 1, 2) if m is None or vla.resolve_mode(B, H, T, dk, dv, io, mode=m) == m]
+    assert 1 in modes and ((2 in modes) == (dk >= 32))       # the block kernel needs whole 32-column slabs of A
+    assert vla.resolve_mode(B, H, T, dk, dv, io) == (2 if dk >= 32 else 1)
+    for mode in modes:
+        o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1, mode=mode)
+        torch.cuda.synchronize()
+        assert tuple(o.shape) == (B, H, T, dv) and tuple(S_T.shape) == (B, H, dv, dk)
+        assert tuple(A_T.shape) == (B, H, dk, dk)
+        errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                    A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+        print(dk, dv, dtype, mode, errs)
+        assert max(errs.values()) <= TOL[dtype], (mode, errs)
+    if dk >= 32:   # the block kernel carries the feature map for these shapes too
+        ref = oracle.forward(q, k, v, S0, None, lambda0=0.1, feature_map=True)
+        o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1,
+                                      feature_map=True)
+        torch.cuda.synchronize()
+        errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                    A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+        assert max(errs.values()) <= TOL[dtype], ("feature map", errs)
 
 
 @pytest.mark.parametrize("d,T", [(64, 32768), (128, 16384), (96, 16384)])
