@@ -201,7 +201,7 @@ int vla_decode_step(const void* q, const void* k, const void* v, float* S, float
   const vla_opts op = resolve_opts(opts);
   const int st = check_shape(B, H, 1, d_k, d_v, io_dtype, op);
   if (st != VLA_OK) return st;
-  if (d_k != d_v) return VLA_ERR_UNSUPPORTED;
+  if (!vla::decode_supported(d_k, d_v, general_path(op))) return VLA_ERR_UNSUPPORTED;
   if (q == nullptr || k == nullptr || v == nullptr || S == nullptr || A == nullptr || o == nullptr) {
     return VLA_ERR_INVALID_ARG;
   }
@@ -216,7 +216,7 @@ int vla_decode_step(const void* q, const void* k, const void* v, float* S, float
   fa.refresh_period = op.refresh_period; fa.refresh_eta = op.refresh_eta; fa.step_offset = op.step_offset;
   fa.normalise_output = op.normalise_output; fa.feature_map = op.feature_map;
   fa.zkey0 = op.zkey0; fa.zkey_T = op.zkey_T;
-  const hipError_t err = vla::launch_decode(q, k, v, S, A, o, B * H, d_k, io_dtype, fa,
+  const hipError_t err = vla::launch_decode(q, k, v, S, A, o, B * H, d_k, d_v, io_dtype, fa,
                                             static_cast<hipStream_t>(stream));
   if (err != hipSuccess) {
     fprintf(stderr, "libvla: kernel launch failed: %s (%d)\n", hipGetErrorString(err),

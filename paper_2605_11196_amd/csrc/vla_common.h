@@ -98,8 +98,11 @@ hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t
 
 
 // One decode step for every head, state updated in place (vla_decode.hip).  `opt` carries eps and the
-// optional lines of Algorithm 1 (u, refresh schedule, read-out normaliser, feature map, key sum).
+// optional lines of Algorithm 1 (u, refresh schedule, read-out normaliser, feature map, key sum).  Value heads
+// half or twice as wide as the key heads run on the plain kernel only (no options).
+bool decode_supported(int d_k, int d_v, bool options);
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
-                         int n_heads, int d, int io_dtype, const ForwardArgs& opt, hipStream_t stream);
+                         int n_heads, int d_k, int d_v, int io_dtype, const ForwardArgs& opt,
+                         hipStream_t stream);
 
 }  // namespace vla

@@ -82,11 +82,15 @@ struct DecodeArgs {
   float* zkey_T;
 };
 
-template <int D, typename IO>
+// DV: head size of v and o (rows of S); the waves split the DV rows of S as they split the D rows of A.
+template <int D, int DV, typename IO>
 __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs a) {
   constexpr int EPL = D / 16;                 // floats per lane per row
-  constexpr int ROWS_W = D >= 32 ? 32 : D;    // rows of each matrix per wave
-  constexpr int NP = ROWS_W / 4;              // passes: a wave instruction covers four rows
+  constexpr int ROWS_W = D >= 32 ? 32 : D;    // rows of A per wave
+  constexpr int ROWS_WV = ROWS_W * DV / D;    // rows of S per wave
+  constexpr int NP = ROWS_W / 4;              // passes over A: a wave instruction covers four rows
+  constexpr int NPV = ROWS_WV / 4;            // passes over S
+  static_assert(ROWS_WV % 4 == 0 && NPV >= 1, "whole passes over S");
   __shared__ float zs[D];
 
   const int head = blockIdx.x;
@@ -95,26 +99,27 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
   const int c = lane & 15;
   const int g = lane >> 4;
   const int col0 = c * EPL;
-  const int row0 = ROWS_W * w + g;            // row of pass p: row0 + 4 p
+  const int row0 = ROWS_W * w + g;            // row of A in pass p: row0 + 4 p
+  const int row0v = ROWS_WV * w + g;          // row of S in pass p: row0v + 4 p
 
   float* Ah = a.A + static_cast<size_t>(head) * D * D;
-  float* Sh = a.S + static_cast<size_t>(head) * D * D;
+  float* Sh = a.S + static_cast<size_t>(head) * DV * D;
   const IO* qh = static_cast<const IO*>(a.q) + static_cast<size_t>(head) * D;
   const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * D;
-  const IO* vh = static_cast<const IO*>(a.v) + static_cast<size_t>(head) * D;
-  IO* oh = static_cast<IO*>(a.o) + static_cast<size_t>(head) * D;
+  const IO* vh = static_cast<const IO*>(a.v) + static_cast<size_t>(head) * DV;
+  IO* oh = static_cast<IO*>(a.o) + static_cast<size_t>(head) * DV;
 
   // everything is requested before anything is used
-  float Ar[NP][EPL], Sr[NP][EPL];
+  float Ar[NP][EPL], Sr[NPV][EPL];
 #pragma unroll
   for (int p = 0; p < NP; ++p) load_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
 #pragma unroll
-  for (int p = 0; p < NP; ++p) load_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
-  float kk[EPL], qq[EPL], vr[NP];
+  for (int p = 0; p < NPV; ++p) load_seg<EPL>(Sh + (row0v + 4 * p) * D + col0, Sr[p]);
+  float kk[EPL], qq[EPL], vr[NPV];
   load_io<EPL>(kh + col0, kk);
   load_io<EPL>(qh + col0, qq);
 #pragma unroll
-  for (int p = 0; p < NP; ++p) vr[p] = widen(vh[row0 + 4 * p]);
+  for (int p = 0; p < NPV; ++p) vr[p] = widen(vh[row0v + 4 * p]);
 
   const float eps = a.eps;
   const float rn = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(kk, kk))), eps);
@@ -150,14 +155,14 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
     store_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
   }
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
+  for (int p = 0; p < NPV; ++p) {
     const float sk = row_sum16(dot_seg<EPL>(Sr[p], kk));
     const float sq = row_sum16(dot_seg<EPL>(Sr[p], qq));
     const float er = vr[p] - sk;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) Sr[p][e] = fmaf(er, al[e], Sr[p][e]);
-    store_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
-    if (c == 0) io_store(oh + row0 + 4 * p, fmaf(er, aq, sq));
+    store_seg<EPL>(Sh + (row0v + 4 * p) * D + col0, Sr[p]);
+    if (c == 0) io_store(oh + row0v + 4 * p, fmaf(er, aq, sq));
   }
 }
 
@@ -289,24 +294,47 @@ hipError_t launch(const DecodeArgs& a, int n_heads, hipStream_t stream) {
   const bool general = a.u != nullptr || a.refresh != 0 || a.normalise_output != 0 || a.feature_map != 0 ||
                        a.zkey0 != nullptr || a.zkey_T != nullptr;
   const void* fn = general ? reinterpret_cast<const void*>(&decode_general_kernel<D, IO>)
-                           : reinterpret_cast<const void*>(&decode_kernel<D, IO>);
+                           : reinterpret_cast<const void*>(&decode_kernel<D, D, IO>);
+  return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
+}
+// value heads half or twice as wide as the key heads: the plain kernel only
+template <int D, int DV>
+hipError_t launch_rect(const DecodeArgs& a, int n_heads, int io_dtype, hipStream_t stream) {
+  DecodeArgs args = a;
+  void* params[] = {&args};
+  const void* fn = io_dtype == 1 ? reinterpret_cast<const void*>(&decode_kernel<D, DV, uint16_t>)
+                                 : reinterpret_cast<const void*>(&decode_kernel<D, DV, float>);
   return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
 }
 
 }  // namespace
 
+bool decode_supported(int d_k, int d_v, bool options) {
+  if (d_k == d_v) return d_k == 16 || d_k == 32 || d_k == 64 || d_k == 96 || d_k == 128;
+  const bool pow2 = (d_k == 16 || d_k == 32 || d_k == 64 || d_k == 128) &&
+                    (d_v == 16 || d_v == 32 || d_v == 64 || d_v == 128);
+  return !options && pow2 && (d_v == 2 * d_k || d_k == 2 * d_v);
+}
+
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
-                         int n_heads, int d, int io_dtype, const ForwardArgs& opt, hipStream_t stream) {
+                         int n_heads, int d, int d_v, int io_dtype, const ForwardArgs& opt,
+                         hipStream_t stream) {
   const bool refresh = opt.refresh_period > 0 && ((opt.step_offset + 1) % opt.refresh_period) == 0;
   const DecodeArgs a{q, k, v, S, A, o, opt.eps, opt.u, opt.u_scale, refresh ? 1 : 0, opt.refresh_eta,
                      opt.normalise_output, opt.feature_map, opt.zkey0, opt.zkey_T};
   const bool bf = io_dtype == 1;
-  switch (d) {
-    case 16: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);
-    case 32: return bf ? launch<32, uint16_t>(a, n_heads, stream) : launch<32, float>(a, n_heads, stream);
-    case 64: return bf ? launch<64, uint16_t>(a, n_heads, stream) : launch<64, float>(a, n_heads, stream);
-    case 96: return bf ? launch<96, uint16_t>(a, n_heads, stream) : launch<96, float>(a, n_heads, stream);
-    case 128: return bf ? launch<128, uint16_t>(a, n_heads, stream) : launch<128, float>(a, n_heads, stream);
+  switch (d * 1000 + d_v) {
+    case 16016: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);
+    case 32032: return bf ? launch<32, uint16_t>(a, n_heads, stream) : launch<32, float>(a, n_heads, stream);
+    case 64064: return bf ? launch<64, uint16_t>(a, n_heads, stream) : launch<64, float>(a, n_heads, stream);
+    case 96096: return bf ? launch<96, uint16_t>(a, n_heads, stream) : launch<96, float>(a, n_heads, stream);
+    case 128128: return bf ? launch<128, uint16_t>(a, n_heads, stream) : launch<128, float>(a, n_heads, stream);
+    case 16032: return launch_rect<16, 32>(a, n_heads, io_dtype, stream);
+    case 32016: return launch_rect<32, 16>(a, n_heads, io_dtype, stream);
+    case 32064: return launch_rect<32, 64>(a, n_heads, io_dtype, stream);
+    case 64032: return launch_rect<64, 32>(a, n_heads, io_dtype, stream);
+    case 64128: return launch_rect<64, 128>(a, n_heads, io_dtype, stream);
+    case 128064: return launch_rect<128, 64>(a, n_heads, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -120,7 +120,8 @@ def decode_call(**kw):
     (dict(B=0), 1), (dict(io_dtype=3), 1), (dict(eps=0.0), 1),
     (dict(S=0), 1), (dict(A=0), 1), (dict(o=0), 1), (dict(k=0), 1),     # the state is required here
     (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
-    (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=64), 2),
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=128), 2),
+    (dict(d_k=32, d_v=64, refresh_period=2), 2), (dict(d_k=64, d_v=32, feature_map=1), 2),   # rectangular: no options
     (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1), (dict(refresh_period=-2), 1),   # option arguments are checked too
 ])
 def test_decode_step_host_side_validation(kw, status):

@@ -134,3 +134,40 @@ def test_decode_steps_with_the_optional_lines_of_algorithm_1(d, name, dtype):
     if zkey is not None:
         errs["zkey"] = slab_rel_err(to_np(zkey), ref["zkey_T"], 1)
     assert max(errs.values()) <= TOL[dtype], errs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dk,dv", [(16, 32), (32, 16), (32, 64), (64, 32), (64, 128), (128, 64)])
+def test_decode_steps_with_value_heads_half_or_twice_as_wide(dk, dv, dtype):
+    """d_k != d_v in the decode step: S is d_v x d_k, A is d_k x d_k; options are refused for these shapes."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, steps = 2, 3, 20
+    rng = np.random.default_rng(dk * 7 + dv)
+    q, k = (rng.standard_normal((B, H, steps, dk)).astype(np.float32) for _ in range(2))
+    v = rng.standard_normal((B, H, steps, dv)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
+    if dtype == "bf16":
+        q, k, v = (vla_inputs.round_to_bf16(x) for x in (q, k, v))
+    ref = oracle.forward(q, k, v, S0, None, lambda0=0.1)
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tq, tk, tv = (torch.from_numpy(x).to(dev).to(tdt) for x in (q, k, v))
+    S = torch.from_numpy(S0).to(dev)
+    A = (torch.eye(dk, device=dev) * (1.0 / np.float32(0.1))).repeat(B, H, 1, 1).contiguous()
+    outs = []
+    for t in range(steps):
+        outs.append(vla.vla_decode_step(tq[:, :, t].contiguous(), tk[:, :, t].contiguous(),
+                                        tv[:, :, t].contiguous(), S, A))
+    torch.cuda.synchronize()
+    o = to_np(torch.stack(outs, dim=2))
+    assert o.shape == (B, H, steps, dv)
+    errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(to_np(S), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A), ref["A_T"], 2))
+    assert max(errs.values()) <= TOL[dtype], errs
+    with pytest.raises(vla.VlaError) as e:
+        vla.vla_decode_step(tq[:, :, 0].contiguous(), tk[:, :, 0].contiguous(), tv[:, :, 0].contiguous(), S, A,
+                            feature_map=True)
+    assert e.value.status == 2
