@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     # (B, H, T, d_h, io dtype, resolved mode): bytes per launch --
     # profiles/chunk_kernel_large_batch_hbm_traffic.txt
-    (64, 32, 8192, 128, "bf16", 2): 17049094 * 1024,
+    (64, 32, 8192, 128, "bf16", 2): 17044037 * 1024,
 }
 
 
