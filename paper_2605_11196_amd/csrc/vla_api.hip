@@ -56,8 +56,9 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (!vla::block_family_supported(d)) return VLA_MODE_CHUNKED;   // d = 96: the plain block kernel only
   const long long heads = static_cast<long long>(B) * H;
   // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
-  // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0)
-  const long long few = d >= 128 ? 64 : 128;
+  // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0), 256 heads at d = 32 (2.7 against
+  // 4.5 ms; 512 heads 5.1 against 4.5)
+  const long long few = d >= 128 ? 64 : (d >= 64 ? 128 : 256);
   return (heads <= few && T >= 1024) ? VLA_MODE_TIME_PARALLEL : VLA_MODE_CHUNKED;
 }
 
