@@ -139,7 +139,10 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(1, 1, 8, 48, 48, vla.VLA_F32) == -1
     assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
-    assert vla.resolve_mode(1, 16, 512, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 16, 512, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL   # few heads: from T = 512
+    assert vla.resolve_mode(1, 16, 500, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 128, 512, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 128, 1024, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED   # no segment modes at d = 96
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_CHUNKED   # d_k != d_v: plain kernels
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
