@@ -133,8 +133,8 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may alias S0
  *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may alias A0
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
- *   d_k == d_v in {16, 32, 64, 96, 128}  (CHUNKED covers 32, 64, 96, 128 -- with options other than
- *          feature_map 32, 64, 128 --, TWO_PHASE and TIME_PARALLEL 32, 64, 128), or d_k, d_v in
+ *   d_k == d_v in {16, 32, 64, 96, 128}  (CHUNKED covers 32, 64, 96, 128, TWO_PHASE and TIME_PARALLEL
+ *          32, 64, 128), or d_k, d_v in
  *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN, and CHUNKED for d_k >= 32; no options
  *          other than feature_map, which only CHUNKED carries for these shapes)
  *   opts   host pointer or NULL

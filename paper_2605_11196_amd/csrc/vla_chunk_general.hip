@@ -64,8 +64,13 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
   constexpr int NB = D / 16;       // 16-row blocks over the head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
-  constexpr int EPT = 4;           // staged elements per thread per tensor
-  constexpr int TPR = D / EPT;     // threads per token row (8, 16 or 32: inside one wave)
+  // Staging: a token row is split over thread slots of EPT elements.  At the power-of-two head sizes every
+  // thread stages 4 elements; at d = 96 a row takes 12 threads of 8 elements in a group of 16 (the other four
+  // lanes of the group and the last two waves stage nothing), so that a row sums with a power-of-two shuffle.
+  constexpr bool PADDED = (D & (D - 1)) != 0;
+  constexpr int EPT = PADDED ? 8 : 4;           // staged elements per thread per tensor
+  constexpr int TPR = PADDED ? 16 : D / EPT;    // thread slots per token row (inside one wave)
+  static_assert(D % EPT == 0 && D / EPT <= TPR && C * TPR <= 4 * D, "staging layout");
   constexpr int UROWS = FULL ? C : 1;
   // Y = X: the Gram matrices that differ only in u against k^ coincide
   constexpr int iGK = FULL ? kGK : kG;
@@ -146,6 +151,8 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   // staging role of this thread: token row and 4-element column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
+  const bool stager = !PADDED || (tid < C * TPR && sseg < D);   // this thread holds a row segment
+  const bool stage_wave = !PADDED || tid < C * TPR;             // uniform per wave
   const int vcol = col0 + c;
 
   RawRow<IO, EPT> kpre, qpre, upre;
@@ -153,11 +160,13 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 
   // Loads never branch on the row: rows past the end read the last valid row and are zeroed when consumed.
   auto load_kqu = [&](int t0) {
-    const int tr = t0 + srow;
-    const unsigned off = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
-    kpre.load(kh + off);
-    qpre.load(qh + off);
-    if (has_u) upre.load(uh + off);
+    if (stager) {
+      const int tr = t0 + srow;
+      const unsigned off = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+      kpre.load(kh + off);
+      qpre.load(qh + off);
+      if (has_u) upre.load(uh + off);
+    }
   };
   auto load_v = [&](int t0) {
 #pragma unroll
@@ -180,9 +189,15 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   // this thread's share of a block of `len` live tokens whose first token has step index idx0 (1-based, counted
   // over the whole sequence): K^, Q (and U) into LDS half `buf`, and the refresh counts of the block
   auto stage = [&](int len, int idx0, int buf) {
-    const bool live = srow < len;
-    float x[EPT];
-    kpre.unpack(x);
+    if (!stage_wave) return;
+    const bool live = srow < len && stager;
+    float x[EPT], kn[EPT];
+    if (stager) {
+      kpre.unpack(x);
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) x[e] = 0.0f;
+    }
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       if (fmap) x[e] = elu_plus_one(x[e]);
@@ -193,8 +208,36 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     for (int e = 0; e < EPT; ++e) ss = fmaf(x[e], x[e], ss);
     float sm;
     const float rn = inv_norm(row_total(ss), sm);
-    const f4 kn = f4{x[0] * rn, x[1] * rn, x[2] * rn, x[3] * rn};
-    *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg]) = kn;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) kn[e] = x[e] * rn;
+    float us[EPT];
+    float su = 0.0f;
+    if constexpr (FULL) {
+      if (has_u) {
+        if (stager) {
+          upre.unpack(us);
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) us[e] = 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) us[e] = live ? us[e] : 0.0f;
+        float uu = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) uu = fmaf(us[e], us[e], uu);
+        float um;
+        su = a.u_scale * inv_norm(row_total(uu), um);
+      }
+      if (tid <= C) {  // multiples of the period among the step indices idx0 .. idx0 + tid - 1
+        const int n = period > 0 ? (idx0 - 1 + tid) / period - (idx0 - 1) / period : 0;
+        ens[buf][tid] = eta * static_cast<float>(n);
+      }
+    }
+    if (!stager) return;
+#pragma unroll
+    for (int e = 0; e < EPT; e += 4) {
+      *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg + e]) = f4{kn[e], kn[e + 1], kn[e + 2], kn[e + 3]};
+    }
     if (sseg == 0) nks[buf][srow] = sm * rn;  // max(||k||, eps)
     qpre.unpack(x);
 #pragma unroll
@@ -202,24 +245,16 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       if (fmap) x[e] = elu_plus_one(x[e]);
       x[e] = live ? x[e] : 0.0f;
     }
-    *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg]) = f4{x[0], x[1], x[2], x[3]};
+#pragma unroll
+    for (int e = 0; e < EPT; e += 4) {
+      *reinterpret_cast<f4*>(&Qsb[buf][srow * LD + sseg + e]) = f4{x[e], x[e + 1], x[e + 2], x[e + 3]};
+    }
     if constexpr (FULL) {
-      if (has_u) {
-        upre.unpack(x);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) x[e] = live ? x[e] : 0.0f;
-        float uu = 0.0f;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) uu = fmaf(x[e], x[e], uu);
-        float um;
-        const float su = a.u_scale * inv_norm(row_total(uu), um);
-        *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = f4{x[0] * su, x[1] * su, x[2] * su, x[3] * su};
-      } else {
-        *reinterpret_cast<f4*>(&Usb[srow * LD + sseg]) = kn;   // u = k^
-      }
-      if (tid <= C) {  // multiples of the period among the step indices idx0 .. idx0 + tid - 1
-        const int n = period > 0 ? (idx0 - 1 + tid) / period - (idx0 - 1) / period : 0;
-        ens[buf][tid] = eta * static_cast<float>(n);
+      for (int e = 0; e < EPT; e += 4) {
+        *reinterpret_cast<f4*>(&Usb[srow * LD + sseg + e]) =
+            has_u ? f4{us[e] * su, us[e + 1] * su, us[e + 2] * su, us[e + 3] * su}
+                  : f4{kn[e], kn[e + 1], kn[e + 2], kn[e + 3]};   // u = k^ without a separate direction
       }
     }
   };
@@ -562,6 +597,7 @@ hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipSt
   switch (d) {
     case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
     case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
+    case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);
     case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }

@@ -63,14 +63,14 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
 // half or twice as wide as the key heads (key heads of 32, 64 or 128).
 bool chunk_supported(int d);
 bool chunk_supported(int d_k, int d_v);
-// Head sizes of the other block-form kernels (general block kernel, two-phase and time-parallel modes).
+// Head sizes of the two-phase and time-parallel modes.
 inline bool block_family_supported(int d) { return d == 32 || d == 64 || d == 128; }
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream);
 // Same block form, several heads per workgroup (vla_chunk_multihead.hip); head sizes 32 and 64.
 // launch_chunk picks it by head size and head count (prefer_multihead).
 bool prefer_multihead(int d, int n_heads);
 hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
-// Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); same head sizes.
+// Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); head sizes 32, 64, 96, 128.
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
