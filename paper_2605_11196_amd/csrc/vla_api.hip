@@ -52,8 +52,8 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
   if (d != d_v) return needs_general_kernel(o) ? VLA_MODE_SCAN : VLA_MODE_CHUNKED;   // rectangular heads
-  if (needs_general_kernel(o)) return VLA_MODE_CHUNKED;
-  if (!vla::block_family_supported(d)) return VLA_MODE_CHUNKED;   // d = 96: no segment modes
+  if (needs_general_kernel(o)) return vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
+  if (!vla::block_family_supported(d)) return VLA_MODE_CHUNKED;   // d = 16, 96: no segment modes
   const long long heads = static_cast<long long>(B) * H;
   // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
   // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0), 256 heads at d = 32 (2.7 against
@@ -68,7 +68,7 @@ bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernels are square only
   if (!vla::chunk_supported(d, d_v)) return false;
   if (d != d_v) return mode == VLA_MODE_CHUNKED && !needs_general_kernel(o);   // the plain block kernel only
-  if (mode == VLA_MODE_CHUNKED) return true;
+  if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::general_block_supported(d);
   // the segment modes carry the feature map, no other option
   if (mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
     return !needs_general_kernel(o) && vla::block_family_supported(d);

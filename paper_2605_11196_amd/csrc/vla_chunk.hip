@@ -52,7 +52,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   constexpr bool PADDED = (TPR0 & (TPR0 - 1)) != 0;
   constexpr int EPT = PADDED ? 16 : C * D / NT;  // staged elements per thread per tensor
   constexpr int TPR = PADDED ? 8 : D / EPT;      // thread slots per token row
-  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0 && C * TPR <= NT && D % EPT == 0 &&
+  static_assert(EPT % 4 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0 && C * TPR <= NT && D % EPT == 0 &&
                 D / EPT <= TPR, "staging layout");
 
   __shared__ __align__(16) float Ksb[2][C * LD];      // K^  [t][j], double-buffered over blocks
@@ -525,7 +525,7 @@ hipError_t launch_io(const ForwardArgs& a, int io_dtype, hipStream_t stream) {
 
 }  // namespace
 
-bool chunk_supported(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
+bool chunk_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
 
 // Several heads per workgroup (vla_chunk_multihead.hip) or one?  Measured on one MI355X, T = 8192:
 //   d = 64 (two-wave workgroups here, four-wave ones of two heads there; both hold 1024 heads per chip at a
@@ -556,6 +556,7 @@ bool chunk_supported(int d_k, int d_v) {
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
   if (d_k == d_v && prefer_multihead(d_k, a.n_heads)) return launch_chunk_multihead(a, d_k, io_dtype, stream);
   switch (d_k * 1000 + d_v) {
+    case 16016: return launch_io<16, 16, 1>(a, io_dtype, stream);
     case 32032: return launch_io<32, 32, 1>(a, io_dtype, stream);
     case 64064: return launch_io<64, 64, 2>(a, io_dtype, stream);
     case 96096: return launch_io<96, 96, 3>(a, io_dtype, stream);

@@ -59,8 +59,8 @@ hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hip
 hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
-// Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 32, 64, 96 and 128, and value heads
-// half or twice as wide as the key heads (key heads of 32, 64 or 128).
+// Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 16, 32, 64, 96 and 128, and value
+// heads half or twice as wide as the key heads (key heads of 32, 64 or 128).
 bool chunk_supported(int d);
 bool chunk_supported(int d_k, int d_v);
 // Head sizes of the two-phase and time-parallel modes.
@@ -71,6 +71,7 @@ hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hi
 bool prefer_multihead(int d, int n_heads);
 hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 // Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); head sizes 32, 64, 96, 128.
+inline bool general_block_supported(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 

@@ -75,7 +75,8 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
-    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16) == vla.MODE_SCAN
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16) == vla.MODE_CHUNKED     # plain block kernel at d = 16
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, refresh_period=5) == vla.MODE_SCAN
 
 
 FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on these paths
