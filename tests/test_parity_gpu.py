@@ -378,7 +378,7 @@ def test_block_modes_hold_the_float32_tolerance_on_long_sequences(d, T):
     persist while A shrinks like 1/(lambda0 + t/d), so the relative error grows with T.  The block forms subtract a
     whole W W^T per 16 tokens and stay two orders below the tolerance; the time-parallel mode restarts every
     segment from a float64 inverse.  (The token-by-token kernel reaches about 2e-4 here: it is AUTO's choice only
-    for head sizes without a block kernel.)"""
+    for shapes without a block kernel.)"""
     q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=9)
     ref = oracle.forward(q, k, v, lambda0=0.1)
     for mode in ((2, 3, 4) if d != 96 else (2,)):
