@@ -135,8 +135,8 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
  *   d_k == d_v in {16, 32, 64, 96, 128}  (CHUNKED covers all of them -- with options other than
  *          feature_map all but 16 --, TWO_PHASE and TIME_PARALLEL 32, 64, 128), or d_k, d_v in
- *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN, and CHUNKED for d_k >= 32; no options
- *          other than feature_map, which only CHUNKED carries for these shapes)
+ *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN and CHUNKED; no options other than
+ *          feature_map, which only CHUNKED carries for these shapes)
  *   opts   host pointer or NULL
  *   workspace, workspace_bytes: device scratch of at least
  *          vla_forward_workspace_bytes(...) bytes (may be NULL/0 when that is 0)

@@ -549,8 +549,8 @@ bool prefer_multihead(int d, int n_heads) {
 // 16 or 64 rows of S).
 bool chunk_supported(int d_k, int d_v) {
   if (d_k == d_v) return chunk_supported(d_k);
-  return (d_k == 32 && (d_v == 16 || d_v == 64)) || (d_k == 64 && (d_v == 32 || d_v == 128)) ||
-         (d_k == 128 && d_v == 64);
+  return (d_k == 16 && d_v == 32) || (d_k == 32 && (d_v == 16 || d_v == 64)) ||
+         (d_k == 64 && (d_v == 32 || d_v == 128)) || (d_k == 128 && d_v == 64);
 }
 
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
@@ -561,6 +561,7 @@ hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hi
     case 64064: return launch_io<64, 64, 2>(a, io_dtype, stream);
     case 96096: return launch_io<96, 96, 3>(a, io_dtype, stream);
     case 128128: return launch_io<128, 128, 4>(a, io_dtype, stream);
+    case 16032: return launch_io<16, 32, 1>(a, io_dtype, stream);
     case 32016: return launch_io<32, 16, 1>(a, io_dtype, stream);
     case 32064: return launch_io<32, 64, 1>(a, io_dtype, stream);
     case 64032: return launch_io<64, 32, 2>(a, io_dtype, stream);

@@ -60,7 +60,7 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
 
 
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 16, 32, 64, 96 and 128, and value
-// heads half or twice as wide as the key heads (key heads of 32, 64 or 128).
+// heads half or twice as wide as the key heads.
 bool chunk_supported(int d);
 bool chunk_supported(int d_k, int d_v);
 // Head sizes of the two-phase and time-parallel modes.

@@ -101,7 +101,7 @@ def call(**kw):
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=64), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
-    (dict(d_k=16, d_v=32, mode=2), 2), (dict(d_k=64, d_v=128, refresh_period=4), 2),   # rectangular: plain kernels only
+    (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4), 2),   # rectangular: plain kernels only
     (dict(d_k=64, d_v=128, mode=3), 2), (dict(d_k=128, d_v=64, mode=4), 2),
 ])
 def test_host_side_validation_returns_status_without_launch(kw, status):
@@ -149,8 +149,8 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_CHUNKED   # d_k != d_v: plain kernels
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
-    assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16) == vla.MODE_SCAN
-    assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16, mode=vla.MODE_CHUNKED) == -1
+    assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 16, 64, vla.VLA_BF16) == -1
     assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == -1
 
 
