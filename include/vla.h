@@ -41,8 +41,8 @@ extern "C" {
 typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
- *   AUTO     : the library picks: SCAN when the shape has no block kernel; CHUNKED when an option
- *              of Algorithm 1 other than feature_map is switched on; else TIME_PARALLEL for few heads
+ *   AUTO     : the library picks: CHUNKED when an option of Algorithm 1 other than feature_map is
+ *              switched on or the shape has no segment kernels; else TIME_PARALLEL for few heads
  *              (B*H <= 64 at d = 128, 128 at d = 64, 256 at d = 32) and T >= 1024 if the caller passed the
  *              workspace vla_forward_workspace_bytes() asks for (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
@@ -133,8 +133,8 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may alias S0
  *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may alias A0
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
- *   d_k == d_v in {16, 32, 64, 96, 128}  (CHUNKED covers all of them -- with options other than
- *          feature_map all but 16 --, TWO_PHASE and TIME_PARALLEL 32, 64, 128), or d_k, d_v in
+ *   d_k == d_v in {16, 32, 64, 96, 128}  (SCAN and CHUNKED cover all of them, TWO_PHASE and
+ *          TIME_PARALLEL 32, 64, 128), or d_k, d_v in
  *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN and CHUNKED; no options other than
  *          feature_map, which only CHUNKED carries for these shapes)
  *   opts   host pointer or NULL

@@ -595,6 +595,7 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
   const bool bf = io_dtype == 1;
   switch (d) {
+    case 16: return bf ? launch<16, uint16_t>(a, stream) : launch<16, float>(a, stream);
     case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
     case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
     case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);

@@ -70,8 +70,8 @@ hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hi
 // launch_chunk picks it by head size and head count (prefer_multihead).
 bool prefer_multihead(int d, int n_heads);
 hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
-// Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); head sizes 32, 64, 96, 128.
-inline bool general_block_supported(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
+// Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); every head size.
+inline bool general_block_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 

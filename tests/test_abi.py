@@ -57,7 +57,7 @@ def test_opts_struct_layout_matches_the_header():
 def test_options_run_on_the_block_kernel_or_the_scan_family():
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
     for d, want in ((128, vla.MODE_CHUNKED), (64, vla.MODE_CHUNKED), (32, vla.MODE_CHUNKED),
-                    (96, vla.MODE_CHUNKED), (16, vla.MODE_SCAN)):
+                    (96, vla.MODE_CHUNKED), (16, vla.MODE_CHUNKED)):
         assert vla.resolve_mode(2, 2, 64, d, d, vla.VLA_BF16, refresh_period=20) == want
     # few heads on a long sequence: still the block kernel, the segment modes carry no options
     assert vla.resolve_mode(1, 4, 65536, 64, 64, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
@@ -70,13 +70,13 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, feature_map=1) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == -1
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
     # d = 96: the plain block kernel (with or without the feature map), no segment modes
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
     assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16) == vla.MODE_CHUNKED     # plain block kernel at d = 16
-    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, refresh_period=5) == vla.MODE_SCAN
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, refresh_period=5) == vla.MODE_CHUNKED
 
 
 FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on these paths
@@ -97,7 +97,7 @@ def call(**kw):
     (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
     (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(step_offset=2**31 - 20, refresh_period=4), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
     (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, normalise_output=1), 2),
-    (dict(mode=2, d_k=16, d_v=16, refresh_period=3), 2),
+    (dict(mode=3, d_k=16, d_v=16), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=64), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),

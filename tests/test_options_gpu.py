@@ -16,7 +16,7 @@ SCAN, BLOCK = 1, 2
 
 
 def modes_for(d):
-    return [SCAN, BLOCK] if d in (32, 64, 96, 128) else [SCAN]
+    return [SCAN, BLOCK]
 
 
 def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, mode=None, **opt):

@@ -20,11 +20,9 @@ def draw_cases(n, seed):
     cases = []
     for i in range(n):
         d = int(rng.choice([16, 32, 64, 96, 128], p=[0.1, 0.25, 0.3, 0.1, 0.25]))
-        block_ok = d in (32, 64, 128)
+        segment_modes = d in (32, 64, 128)
         with_opts = bool(rng.random() < 0.5)
-        if not block_ok:
-            mode = SCAN
-        elif with_opts:
+        if with_opts or not segment_modes:
             mode = int(rng.choice([SCAN, BLOCK], p=[0.25, 0.75]))
         else:
             mode = int(rng.choice([SCAN, BLOCK, TWO_PHASE, TIME_PARALLEL], p=[0.1, 0.3, 0.2, 0.4]))
