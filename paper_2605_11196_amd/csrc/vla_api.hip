@@ -44,10 +44,10 @@ bool needs_general_kernel(const vla_opts& o) {
 // feature map by itself)
 bool general_path(const vla_opts& o) { return needs_general_kernel(o) || o.feature_map != 0; }
 
-// AUTO: head sizes without a block kernel -> scan family; options other than the feature map -> the block
-// kernel that carries them;
-// few heads on a long sequence -> time-parallel (segments of the sequence run concurrently and the S rows
-// spread over d/16 times more workgroups than there are heads); otherwise the fused block kernel.
+// AUTO: options other than the feature map -> the block kernel that carries them; few heads on a long
+// sequence -> time-parallel (segments of the sequence run concurrently and the S rows spread over d/16 times
+// more workgroups than there are heads); otherwise the fused block kernel.  Every supported shape has a block
+// kernel; the scan family is the fallback should one be missing.
 int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
