@@ -34,8 +34,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large_batch",
                     choices=["tiny", "norm_growth", "recall", "long_context", "large_batch"])
     ap.add_argument("--T", type=int, default=None, help="sequence length override (long_context)")
