@@ -507,3 +507,68 @@ def test_full_algorithm1_tiny_with_every_switch():
         z = z + kf
         assert np.abs(r["o"][0, 0, t] - S @ qf / max(z @ qf, 1e-4)).max() < 1e-11
     assert np.abs(r["A_T"][0, 0] - A).max() < 1e-10 and np.abs(r["S_T"][0, 0] - S).max() < 1e-11
+
+
+# ---------------------------------------------------------------- the refresh schedule across split calls
+# Algorithm 1 refreshes when the 1-based step count is a multiple of the period.  For period 4 and a call of
+# 11 tokens that starts after `offset` earlier tokens (its tokens are steps offset + 1 ... offset + 11), the
+# local 0-based indices that refresh, counted out by hand:
+REFRESH_STEPS_PERIOD4_T11 = {
+    0: [3, 7],          # steps 1..11:  4, 8
+    1: [2, 6, 10],      # steps 2..12:  4, 8, 12
+    2: [1, 5, 9],       # steps 3..13:  4, 8, 12
+    3: [0, 4, 8],       # steps 4..14:  4, 8, 12
+    4: [3, 7],          # steps 5..15:  8, 12
+    7: [0, 4, 8],       # steps 8..18:  8, 12, 16
+    18: [1, 5, 9],      # steps 19..29: 20, 24, 28
+}
+
+
+@pytest.mark.parametrize("offset", sorted(REFRESH_STEPS_PERIOD4_T11))
+def test_step_offset_shifts_the_refresh_schedule(offset):
+    """A call with step_offset = k refreshes at the steps of the table above; A_t is recomputed with
+    fresh inverses (no rank-1 recursion), eta I added at exactly the listed tokens."""
+    d, T, lam, period, eta = 4, 11, 0.25, 4, 5e-2
+    refresh_at = REFRESH_STEPS_PERIOD4_T11[offset]
+    rng = RNG(50 + offset)
+    q = rng.standard_normal((T, d)); k = rng.standard_normal((T, d)); v = rng.standard_normal((T, d))
+    r = oracle.forward(q[None, None], k[None, None], v[None, None], lambda0=lam, refresh_period=period,
+                       refresh_eta=eta, step_offset=offset)
+    A = np.eye(d) / lam; S = np.zeros((d, d))
+    for t in range(T):
+        kh = k[t] / np.linalg.norm(k[t])
+        A = np.linalg.inv(np.linalg.inv(A) + np.outer(kh, kh))
+        if t in refresh_at:
+            A = A + eta * np.eye(d)
+        a = A @ kh; a /= np.linalg.norm(a)
+        S = S + np.outer(v[t] - S @ kh, a)
+        assert np.abs(r["o"][0, 0, t] - S @ q[t]).max() < 1e-11, t
+    assert np.abs(r["A_T"][0, 0] - A).max() < 1e-11 and np.abs(r["S_T"][0, 0] - S).max() < 1e-11
+    # a schedule shifted by one token is a different result (so the comparison above can tell them apart)
+    other = oracle.forward(q[None, None], k[None, None], v[None, None], lambda0=lam, refresh_period=period,
+                           refresh_eta=eta, step_offset=offset + 1)
+    assert np.abs(other["A_T"] - r["A_T"]).max() > 1e-4
+
+
+@pytest.mark.parametrize("T1", [5, 8, 13, 1, 19])
+def test_split_call_with_refresh_reproduces_one_call_bitwise(T1):
+    """Running [0, T1) and then [T1, T) with step_offset = T1 and the carried S, A and key sum is the single
+    call over [0, T), bit for bit, whether or not T1 is a multiple of the period (period 4), with every option
+    on; without the offset the second half refreshes at the wrong steps."""
+    d_k, d_v, T, period = 6, 5, 20, 4
+    rng = RNG(60)
+    q = rng.standard_normal((2, 1, T, d_k)); k = rng.standard_normal((2, 1, T, d_k))
+    v = rng.standard_normal((2, 1, T, d_v)); u = rng.standard_normal((2, 1, T, d_k))
+    opt = dict(lambda0=0.2, refresh_period=period, refresh_eta=1e-2, normalise_output=True, feature_map=True,
+               u_scale=0.5)
+    full = oracle.forward(q, k, v, u=u, **opt)
+    a = oracle.forward(q[:, :, :T1], k[:, :, :T1], v[:, :, :T1], u=u[:, :, :T1], **opt)
+    b = oracle.forward(q[:, :, T1:], k[:, :, T1:], v[:, :, T1:], a["S_T"], a["A_T"], u=u[:, :, T1:],
+                       step_offset=T1, zkey0=a["zkey_T"], **opt)
+    assert np.array_equal(np.concatenate([a["o"], b["o"]], axis=2), full["o"])
+    for name in ("S_T", "A_T", "zkey_T"):
+        assert np.array_equal(b[name], full[name]), name
+    if T1 % period:
+        wrong = oracle.forward(q[:, :, T1:], k[:, :, T1:], v[:, :, T1:], a["S_T"], a["A_T"], u=u[:, :, T1:],
+                               zkey0=a["zkey_T"], **opt)
+        assert np.abs(wrong["A_T"] - full["A_T"]).max() > 1e-4
