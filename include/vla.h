@@ -23,8 +23,11 @@
  * allocates, frees or retains memory: the caller owns every buffer for the
  * duration of the call's execution on `stream`.  Calls are asynchronous with
  * respect to the host (kernels are enqueued on `stream`, no host synchronisation)
- * and re-entrant.  All validation happens on the host before anything is enqueued;
- * on any error nothing has been launched and no output has been touched.
+ * and re-entrant.  All validation happens on the host before anything is enqueued: with
+ * VLA_ERR_INVALID_ARG, VLA_ERR_UNSUPPORTED or VLA_ERR_WORKSPACE nothing has been launched and no
+ * output has been touched.  VLA_ERR_HIP reports a launch the HIP runtime refused; in the modes
+ * that run several kernels back to back, earlier kernels of the call may already be enqueued
+ * then and the outputs and the workspace hold unspecified values.
  */
 #ifndef VLA_H_
 #define VLA_H_
@@ -130,9 +133,13 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *   S0     [B, H, d_v, d_k] float32 row-major, or NULL for S_0 = 0     (Algorithm 1)
  *   A0     [B, H, d_k, d_k] float32 row-major, or NULL for I / lambda0 (Algorithm 1).
  *          Must be symmetric positive definite (precondition, not checked).
- *   o      [B, H, T, d_v]   io_dtype, written; must not overlap any input
- *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may alias S0
- *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may alias A0
+ *   o      [B, H, T, d_v]   io_dtype, written
+ *   S_T    [B, H, d_v, d_k] float32, written; NULL if not wanted; may be S0 itself
+ *   A_T    [B, H, d_k, d_k] float32, written; NULL if not wanted; may be A0 itself
+ *          No written buffer (o, S_T, A_T, opts->zkey_T, the workspace) may overlap another buffer of
+ *          the call, in whole or in part -- the byte ranges are compared on the host and an overlap
+ *          returns VLA_ERR_INVALID_ARG -- with three exceptions: S_T == S0, A_T == A0 and
+ *          zkey_T == zkey0 (the same pointer: the state is then updated in place).
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
  *   d_k == d_v in {16, 32, 64, 96, 128}  (SCAN and CHUNKED cover all of them, TWO_PHASE and
  *          TIME_PARALLEL 32, 64, 128), or d_k, d_v in

@@ -163,6 +163,8 @@ def vla_decode_step(q, k, v, S, A, *, eps=None, stream=None, u=None, u_scale=Non
         o = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
         st = stream if stream is not None else torch.cuda.current_stream(q.device)
         handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
+        if isinstance(st, torch.cuda.Stream):
+            o.record_stream(st)
         extra = dict(u=p(u), u_scale=u_scale, refresh_period=refresh_period, refresh_eta=refresh_eta,
                      step_offset=step_offset,
                      normalise_output=None if normalise_output is None else int(bool(normalise_output)),
@@ -182,7 +184,8 @@ def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None,
     """Torch-tensor front end: q,k [B,H,T,d_k], v [B,H,T,d_v] on the GPU (float32 or bfloat16).
 
     Allocates o (and S_T, A_T, workspace) with torch, enqueues the kernels on `stream`
-    (default: torch's current stream) and returns (o, S_T, A_T).
+    (a torch.cuda.Stream; default: torch's current stream) and returns (o, S_T, A_T).  The outputs are ready
+    when the work on `stream` is: a caller that reads them on another stream orders the two itself.
     """
     import torch
 
@@ -206,29 +209,36 @@ def vla_forward(q, k, v, S0=None, A0=None, *, lambda0=None, eps=None, mode=None,
         if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != shape
                               or not s.is_contiguous() or s.device != dev):
             raise ValueError(f"{name} must be a contiguous float32 tensor of shape {shape} on {dev}")
+    st = stream if stream is not None else torch.cuda.current_stream(dev)
+    handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
+    p = lambda x: 0 if x is None else x.data_ptr()
+    if u is not None:
+        if u.dtype != q.dtype or tuple(u.shape) != tuple(q.shape) or u.device != dev:
+            raise ValueError("u must match q in dtype, shape and device")
+        u = u.contiguous()
+    if zkey0 is not None and (zkey0.dtype != torch.float32 or tuple(zkey0.shape) != (B, H, dk)
+                              or not zkey0.is_contiguous() or zkey0.device != dev):
+        raise ValueError(f"zkey0 must be a contiguous float32 tensor of shape {(B, H, dk)} on {dev}")
     with torch.cuda.device(dev):
         o = torch.empty((B, H, T, dv), dtype=q.dtype, device=dev)
         S_T = torch.empty((B, H, dv, dk), dtype=torch.float32, device=dev) if return_state else None
         A_T = torch.empty((B, H, dk, dk), dtype=torch.float32, device=dev) if return_state else None
-        need = vla_forward_workspace_bytes(B, H, T, dk, dv, io, lambda0=lambda0, eps=eps, mode=mode,
-                                           segments=segments)
-        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev) if need else None
-        st = stream if stream is not None else torch.cuda.current_stream(dev)
-        handle = st.cuda_stream if hasattr(st, "cuda_stream") else int(st)
-        p = lambda x: 0 if x is None else x.data_ptr()
-        if u is not None:
-            if u.dtype != q.dtype or tuple(u.shape) != tuple(q.shape) or u.device != dev:
-                raise ValueError("u must match q in dtype, shape and device")
-            u = u.contiguous()
-        if zkey0 is not None and (zkey0.dtype != torch.float32 or tuple(zkey0.shape) != (B, H, dk)
-                                  or not zkey0.is_contiguous() or zkey0.device != dev):
-            raise ValueError(f"zkey0 must be a contiguous float32 tensor of shape {(B, H, dk)} on {dev}")
         zkey_T = torch.empty((B, H, dk), dtype=torch.float32, device=dev) if return_zkey else None
         extra = dict(u=p(u) or None, u_scale=u_scale, refresh_period=refresh_period,
                      refresh_eta=refresh_eta, step_offset=step_offset,
                      normalise_output=None if normalise_output is None else int(bool(normalise_output)),
                      feature_map=None if feature_map is None else int(bool(feature_map)),
                      zkey0=p(zkey0) or None, zkey_T=p(zkey_T) or None, segments=segments)
+        # the same options as the call, so that the query resolves AUTO to the mode the call will run
+        need = vla_forward_workspace_bytes(B, H, T, dk, dv, io, lambda0=lambda0, eps=eps, mode=mode, **extra)
+        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev) if need else None
+        # These tensors come from the allocator of torch's current stream while the kernels run on `st`: tell the
+        # allocator, so that memory dropped here (the workspace when this function returns) is not handed to
+        # other work before the kernels on `st` are done with it.
+        if isinstance(st, torch.cuda.Stream):
+            for t in (o, S_T, A_T, zkey_T, ws):
+                if t is not None:
+                    t.record_stream(st)
         rc = vla_forward_raw(p(q), p(k), p(v), p(S0), p(A0), p(o), p(S_T), p(A_T), B, H, T, dk, dv,
                              io, lambda0=lambda0, eps=eps, mode=mode, workspace=p(ws),
                              workspace_bytes=need, stream=handle, **extra)

@@ -11,6 +11,37 @@ constexpr int kVersion = 500;  // 0.5.0
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// A caller buffer as a byte range; `written` marks what the kernels store to.
+struct Range {
+  const void* p;
+  size_t bytes;
+  bool written;
+};
+bool ranges_overlap(const Range& a, const Range& b) {
+  if (a.p == nullptr || b.p == nullptr || a.bytes == 0 || b.bytes == 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+  return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
+}
+// No written buffer may overlap any other buffer of the call, in whole or in part, except for the three exact
+// aliases the interface allows (the state and key-sum outputs written over their own inputs).
+bool buffers_disjoint(const Range* r, int n, const void* const (*alias)[2], int n_alias) {
+  for (int i = 0; i < n; ++i) {
+    if (!r[i].written) continue;
+    for (int j = 0; j < n; ++j) {
+      if (j == i || (r[j].written && j < i)) continue;   // written pairs are looked at once
+      if (!ranges_overlap(r[i], r[j])) continue;
+      bool allowed = false;
+      for (int a = 0; a < n_alias; ++a) {
+        allowed = allowed || (r[i].p == r[j].p && r[i].bytes == r[j].bytes &&
+                              ((r[i].p == alias[a][0] && r[j].p == alias[a][1]) ||
+                               (r[i].p == alias[a][1] && r[j].p == alias[a][0])));
+      }
+      if (!allowed) return false;
+    }
+  }
+  return true;
+}
+
 vla_opts resolve_opts(const vla_opts* o) {
   vla_opts r;
   vla_default_opts(&r);
@@ -76,6 +107,13 @@ bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   return false;
 }
 
+// The segment modes launch up to d/8 workgroups per (head, segment) pair and index pairs with 32-bit integers
+// (at most 256 segments per head).
+bool segment_grid_fits(int mode, long long heads, int d) {
+  if (mode != VLA_MODE_TWO_PHASE && mode != VLA_MODE_TIME_PARALLEL) return true;
+  return heads * 256 * (d / 8) <= 0x7fffffffLL;
+}
+
 }  // namespace
 
 extern "C" {
@@ -114,6 +152,7 @@ int vla_resolve_mode(int B, int H, int T, int d_k, int d_v, int io_dtype, const 
   const vla_opts o = resolve_opts(opts);
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return -1;
   const int mode = pick_mode(B, H, T, d_k, d_v, o);
+  if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return -1;
   return mode_available(mode, d_k, d_v, o) ? mode : -1;
 }
 
@@ -123,6 +162,7 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   if (check_shape(B, H, T, d_k, d_v, io_dtype, o) != VLA_OK) return 0;
   const int mode = pick_mode(B, H, T, d_k, d_v, o);
   if (!mode_available(mode, d_k, d_v, o)) return 0;
+  if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return 0;
   if (mode == VLA_MODE_TWO_PHASE) return vla::two_phase_workspace_bytes(B * H, T, d_k);
   if (mode == VLA_MODE_TIME_PARALLEL) return vla::time_parallel_workspace_bytes(B * H, T, d_k, o.segments);
   return 0;
@@ -142,10 +182,22 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   for (const void* p : ptrs) {
     if (p != nullptr && !aligned16(p)) return VLA_ERR_INVALID_ARG;
   }
-  if (T > 0 && (o == q || o == k || o == v)) return VLA_ERR_INVALID_ARG;
+  {
+    const size_t es = io_dtype == VLA_BF16 ? 2 : 4;
+    const size_t heads = static_cast<size_t>(B) * H;
+    const size_t nk = heads * T * d_k * es, nv = heads * T * d_v * es;
+    const size_t nS = heads * d_v * d_k * 4, nA = heads * d_k * d_k * 4, nz = heads * d_k * 4;
+    const Range r[] = {{q, nk, false},        {k, nk, false},         {v, nv, false},  {op.u, nk, false},
+                       {S0, nS, false},       {A0, nA, false},        {op.zkey0, nz, false},
+                       {o, nv, true},         {S_T, nS, true},        {A_T, nA, true}, {op.zkey_T, nz, true},
+                       {workspace, workspace_bytes, true}};
+    const void* const alias[][2] = {{S_T, S0}, {A_T, A0}, {op.zkey_T, op.zkey0}};
+    if (!buffers_disjoint(r, 12, alias, 3)) return VLA_ERR_INVALID_ARG;
+  }
 
   int mode = pick_mode(B, H, T, d_k, d_v, op);
   if (!mode_available(mode, d_k, d_v, op)) return VLA_ERR_UNSUPPORTED;
+  if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
     // AUTO never fails for want of a workspace: it falls back to the fused block kernel
@@ -166,9 +218,6 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   a.refresh_period = op.refresh_period; a.refresh_eta = op.refresh_eta; a.step_offset = op.step_offset;
   a.normalise_output = op.normalise_output; a.feature_map = op.feature_map;
   a.zkey0 = op.zkey0; a.zkey_T = op.zkey_T;
-#ifdef VLA_DEBUG_STAMPS
-  a.dbg = workspace_bytes >= (1u << 20) ? static_cast<long long*>(workspace) : nullptr;
-#endif
 
   hipError_t err = hipSuccess;
   switch (mode) {
@@ -212,7 +261,16 @@ int vla_decode_step(const void* q, const void* k, const void* v, float* S, float
   for (const void* p : ptrs) {
     if (p != nullptr && !aligned16(p)) return VLA_ERR_INVALID_ARG;
   }
-  if (o == q || o == k || o == v || o == op.u) return VLA_ERR_INVALID_ARG;
+  {
+    const size_t es = io_dtype == VLA_BF16 ? 2 : 4;
+    const size_t heads = static_cast<size_t>(B) * H;
+    const size_t nk = heads * d_k * es, nv = heads * d_v * es, nz = heads * d_k * 4;
+    const Range r[] = {{q, nk, false},          {k, nk, false}, {v, nv, false}, {op.u, nk, false},
+                       {op.zkey0, nz, false},   {o, nv, true},  {S, heads * d_v * d_k * 4, true},
+                       {A, heads * d_k * d_k * 4, true},        {op.zkey_T, nz, true}};
+    const void* const alias[][2] = {{op.zkey_T, op.zkey0}};
+    if (!buffers_disjoint(r, 9, alias, 1)) return VLA_ERR_INVALID_ARG;
+  }
   vla::ForwardArgs fa{};
   fa.eps = op.eps;
   fa.u = op.u; fa.u_scale = op.u_scale;

@@ -213,13 +213,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   __syncthreads();  // block 0 staged
 
   int blk = 0;
-#ifdef VLA_DEBUG_STAMPS
-#define VLA_STAMP(pt) do { if (a.dbg && head == 0 && lane == 0 && blk < 256) a.dbg[(blk * 8 + (pt)) * NW + w] = clock64(); } while (0)
-#else
-#define VLA_STAMP(pt) do { } while (0)
-#endif
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
-    VLA_STAMP(0);
     const float* Ks = Ksb[blk & 1];
     const float* Qs = Qsb[blk & 1];
     // staging of the next block (this thread's share): done where this wave is not on the critical path
@@ -241,7 +235,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int r = 0; r < 4; ++r) ft[jn][r] = (t0 + 4 * g + r < T) ? ft[jn][r] : 0.0f;
     }
     if (t0 + C < T) load_v(t0 + C);
-    VLA_STAMP(1);
 
     // ================= Y^T = K^ A0 (this wave's columns); Y^T goes to LDS for the Gram products
     f4 yt[NJ];
@@ -293,7 +286,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         Gp[w][1][(4 * g + r) * LT + c] = gq[0][r];
       }
     }
-    VLA_STAMP(2);
     __syncthreads();  // (2) partial Grams visible
 
     // ================= C x C factorisation, phase 1 (one wave): Cholesky of I + G and L^{-1}
@@ -352,7 +344,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           *reinterpret_cast<f4*>(&Lrs[c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
     }
-    VLA_STAMP(3);
     __syncthreads();  // (3) L^{-1} visible
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
@@ -373,7 +364,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
-    VLA_STAMP(4);
     __syncthreads();  // (4) W and the norm partials visible
 
     // ================= phase 2 (wave sw2): c_t, Z, NQ -- the other waves update A meanwhile
@@ -433,9 +423,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         NQs[c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
       }
     }
-    VLA_STAMP(5);
     __syncthreads();  // (5) Z, NQ, c visible
-    VLA_STAMP(6);
 
     // ================= -E^T = Z (-F^T), R^T = Q S0^T, O^T = R^T + (-NQ^T)(-E^T), store o;
     // ce = (-c) (-E^T) = diag(c) E^T
@@ -470,8 +458,6 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         }
       }
     }
-
-    VLA_STAMP(7);
     // ================= S^T += W diag(c) E^T  (and A -= W W^T on the wave that formed Z)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {

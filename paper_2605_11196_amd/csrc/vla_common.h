@@ -36,9 +36,6 @@ struct ForwardArgs {
   const float* seg_A = nullptr;   // [n_heads][n_seg][d][d]  A at the start of every segment
   const float* seg_S = nullptr;   // [n_heads][n_seg][d][d]  S at the start of every segment
   float* seg_PQ = nullptr;        // [n_heads][n_seg][2][d][d]  per-segment affine map of the S recurrence
-#ifdef VLA_DEBUG_STAMPS
-  long long* dbg = nullptr;  // development builds only: per-phase cycle stamps
-#endif
 };
 
 // bf16 <-> f32 helpers on raw bit patterns (bf16 is the upper half of an IEEE float32).

@@ -99,7 +99,9 @@ template <int EPT> struct RawRow<float, EPT> {
 #pragma unroll
     for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const float4*>(p + 4 * e);
   }
-  __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
+  // F = float, or double (every float32 value is a float64 value)
+  template <typename F>
+  __device__ __forceinline__ void unpack(F (&x)[EPT]) const {
 #pragma unroll
     for (int e = 0; e < EPT / 4; ++e) {
       x[4 * e] = v[e].x; x[4 * e + 1] = v[e].y; x[4 * e + 2] = v[e].z; x[4 * e + 3] = v[e].w;
@@ -116,7 +118,8 @@ template <int EPT> struct RawRow<uint16_t, EPT> {
 #pragma unroll
     for (int e = 0; e < NP; ++e) v[e] = *reinterpret_cast<const Piece*>(p + 2 * PW * e);
   }
-  __device__ __forceinline__ void unpack(float (&x)[EPT]) const {
+  template <typename F>
+  __device__ __forceinline__ void unpack(F (&x)[EPT]) const {
 #pragma unroll
     for (int e = 0; e < NP; ++e) {
 #pragma unroll

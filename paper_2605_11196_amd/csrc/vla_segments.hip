@@ -18,38 +18,6 @@ namespace {
 constexpr int kThreads = 256;
 
 // ------------------------------------------------------------------------------------------ Gram
-// Raw row fragment of EPT consecutive elements -> float64.
-template <typename IO, int EPT> struct RawFrag;
-template <int EPT> struct RawFrag<float, EPT> {
-  static_assert(EPT % 4 == 0, "16-byte pieces");
-  float4 v[EPT / 4];
-  __device__ __forceinline__ void load(const float* p) {
-#pragma unroll
-    for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const float4*>(p + 4 * e);
-  }
-  __device__ __forceinline__ void widen(double (&x)[EPT]) const {
-#pragma unroll
-    for (int e = 0; e < EPT / 4; ++e) {
-      x[4 * e] = v[e].x; x[4 * e + 1] = v[e].y; x[4 * e + 2] = v[e].z; x[4 * e + 3] = v[e].w;
-    }
-  }
-};
-template <int EPT> struct RawFrag<uint16_t, EPT> {
-  static_assert(EPT % 4 == 0, "8-byte pieces");
-  uint2 v[EPT / 4];
-  __device__ __forceinline__ void load(const uint16_t* p) {
-#pragma unroll
-    for (int e = 0; e < EPT / 4; ++e) v[e] = *reinterpret_cast<const uint2*>(p + 4 * e);
-  }
-  __device__ __forceinline__ void widen(double (&x)[EPT]) const {
-#pragma unroll
-    for (int e = 0; e < EPT / 4; ++e) {
-      x[4 * e] = __uint_as_float(v[e].x << 16);     x[4 * e + 1] = __uint_as_float(v[e].x & 0xffff0000u);
-      x[4 * e + 2] = __uint_as_float(v[e].y << 16); x[4 * e + 3] = __uint_as_float(v[e].y & 0xffff0000u);
-    }
-  }
-};
-
 typedef double d4 __attribute__((ext_vector_type(4)));
 
 // One workgroup (4 waves) per (head, segment); the last segment's matrix is never needed.  Tokens are
@@ -99,17 +67,17 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
   // Fragments of the next PF tiles are kept in flight in raw form (a few registers each): with a thousand
   // workgroups streaming at once the memory latency is several tiles' worth of work.
   constexpr int PF = D >= 128 ? 2 : 4;   // what the register file allows next to 128 accumulator registers
-  RawFrag<IO, EPT> raw[PF];
-  auto fetch = [&](int t0, RawFrag<IO, EPT>& o) {
+  RawRow<IO, EPT> raw[PF];
+  auto fetch = [&](int t0, RawRow<IO, EPT>& o) {
     const int t = t0 + srow;
     o.load(kh + static_cast<size_t>(t < te ? t : te - 1) * D + scol);
   };
   // stage: k^ = k / max(||k||, eps) in float64; rows past the end are zero.  1 / ||k|| is a float32
   // reciprocal square root refined by one Newton step in float64 (relative error ~1e-14).
-  auto stage = [&](int t0, const RawFrag<IO, EPT>& o, double* kt) {
+  auto stage = [&](int t0, const RawRow<IO, EPT>& o, double* kt) {
     const int t = t0 + srow;
     double x[EPT];
-    o.widen(x);
+    o.unpack(x);
     if (a.feature_map) {   // ELU(x) + 1 in float32, as the kernels that run the recurrence apply it
 #pragma unroll
       for (int e = 0; e < EPT; ++e) x[e] = static_cast<double>(elu_plus_one(static_cast<float>(x[e])));

@@ -26,22 +26,6 @@ namespace {
 
 constexpr int SMB = 3 * C * C + C;  // floats of small matrices per (head, block)
 
-// Four consecutive elements of q in raw form.
-template <typename IO> struct Raw4;
-template <> struct Raw4<float> {
-  float4 v;
-  __device__ __forceinline__ void load(const float* p) { v = *reinterpret_cast<const float4*>(p); }
-  __device__ __forceinline__ void unpack(float (&x)[4]) const { x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w; }
-};
-template <> struct Raw4<uint16_t> {
-  uint2 v;
-  __device__ __forceinline__ void load(const uint16_t* p) { v = *reinterpret_cast<const uint2*>(p); }
-  __device__ __forceinline__ void unpack(float (&x)[4]) const {
-    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
-    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
-  }
-};
-
 __host__ __device__ constexpr size_t head_stride(int nblk, int D) {
   return static_cast<size_t>(nblk) * (2 * C * D + SMB);
 }
@@ -429,7 +413,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   // operands of one block, in MFMA operand layout, straight from global memory
   struct Ops {
     f4 ka[NB], wa[NB];
-    Raw4<IO> qa[NB];
+    RawRow<IO, 4> qa[NB];
     f4 za, nqa, ncg;
     IO v[4];
   };
@@ -551,8 +535,10 @@ hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
   void* params[] = {&args};
   constexpr int kDepth = D <= 64 ? 2 : 1;  // register budget: three operand sets only fit up to d = 64
   constexpr int kWph = (MAP ? 2 : 1) * (D / 16);
-  const int hs = a.n_heads * a.n_seg;
-  const unsigned grid = static_cast<unsigned>((hs + 7) / 8) * 8u * kWph;
+  const long long hs = static_cast<long long>(a.n_heads) * a.n_seg;
+  const long long wgs = (hs + 7) / 8 * 8 * kWph;
+  if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+  const unsigned grid = static_cast<unsigned>(wgs);
   return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_kernel<D, kDepth, IO, MAP>), dim3(grid),
                          dim3(64), params, 0, stream);
 }
@@ -640,7 +626,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const bool do_c = tid < 4;                   // -c
   struct Regs {
     f4 kx, wx, sx, cx;
-    Raw4<IO> qx;
+    RawRow<IO, 4> qx;
     IO v[4];
   };
   auto fetch = [&](int blk, Regs& r) {
@@ -784,8 +770,10 @@ template <int D, int NW, typename IO>
 hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  const int hs = a.n_heads * a.n_seg;
-  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>), dim3(hs),
+  const long long hs = static_cast<long long>(a.n_heads) * a.n_seg;
+  if (hs * (D / 8) > 0x7fffffffLL) return hipErrorInvalidValue;   // the largest grid below: 2 D/16 waves per pair
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
+                                   dim3(static_cast<unsigned>(hs)),
                                    dim3(64 * NW), params, 0, stream);
   if (err != hipSuccess) return err;
   const int nblk = (a.T + C - 1) / C;

@@ -100,6 +100,16 @@ def call(**kw):
     (dict(mode=3, d_k=16, d_v=16), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q
+    (dict(o=FAKE + 0x100), 1),               # o starts inside q (512 bytes at FAKE)
+    (dict(o=FAKE + 0x1000 - 0x100), 1),      # o ends inside k
+    (dict(u=FAKE + 0x3000 - 0x100), 1),      # the penalty directions end inside o
+    (dict(zkey0=FAKE + 0x3000 + 0x1f0, normalise_output=1), 1),   # the carried key sum starts inside o
+    (dict(S0=FAKE + 0x5000, S_T=FAKE + 0x5100), 1),   # S_T may be S0 itself, not a shifted copy of it
+    (dict(A0=FAKE + 0x5000, A_T=FAKE + 0x4f00), 1),
+    (dict(A_T=FAKE + 0x3100), 1),            # a state output inside o
+    (dict(S_T=FAKE + 0x6000, A_T=FAKE + 0x6200), 1),  # the two state outputs inside each other
+    (dict(zkey0=FAKE + 0x7000, zkey_T=FAKE + 0x7010, normalise_output=1), 1),
+    (dict(mode=3, d_k=64, d_v=64, workspace=FAKE + 0x2800, workspace_bytes=1 << 20), 1),   # workspace over v and o
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=64), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
     (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4), 2),   # rectangular: plain kernels only
     (dict(d_k=64, d_v=128, mode=3), 2), (dict(d_k=128, d_v=64, mode=4), 2),
@@ -122,6 +132,8 @@ def decode_call(**kw):
     (dict(B=0), 1), (dict(io_dtype=3), 1), (dict(eps=0.0), 1),
     (dict(S=0), 1), (dict(A=0), 1), (dict(o=0), 1), (dict(k=0), 1),     # the state is required here
     (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
+    (dict(o=FAKE + 0x1000 + 0x20), 1), (dict(A=FAKE + 0x4100), 1),      # o inside k; A inside S (1024 bytes)
+    (dict(o=FAKE + 0x4000 + 0x3f0), 1), (dict(u=FAKE + 0x3000 - 0x10), 1),   # o inside S; u ends inside o
     (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=128), 2),
     (dict(d_k=32, d_v=64, refresh_period=2), 2), (dict(d_k=64, d_v=32, feature_map=1), 2),   # rectangular: no options
     (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1), (dict(refresh_period=-2), 1),   # option arguments are checked too

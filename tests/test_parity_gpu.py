@@ -184,19 +184,61 @@ def test_zero_keys_small_keys_and_large_values(mode):
     assert np.count_nonzero(S_T[0, 3]) == 0 and np.count_nonzero(o[0, 3]) == 0
 
 
+def plain_float32_recurrence(q, k, v, lambda0=0.1, eps=1e-4):
+    """The recurrence of Section 3.3 token by token with every intermediate rounded to float32 (numpy, CPU):
+    what float32 state costs by itself on a given input, whatever the kernel.  Not an oracle: the error of
+    this run against the float64 oracle is the yardstick the ill-conditioned case below is held to."""
+    f = np.float32
+    B, H, T, d = q.shape
+    o = np.zeros(v.shape, f)
+    S_T = np.zeros((B, H, v.shape[-1], d), f)
+    A_T = np.zeros((B, H, d, d), f)
+    for b in range(B):
+        for h in range(H):
+            A = (np.eye(d, dtype=f) / f(lambda0)).astype(f)
+            S = np.zeros((v.shape[-1], d), f)
+            for t in range(T):
+                kt = k[b, h, t].astype(f)
+                kh = (kt / max(np.sqrt((kt * kt).sum(dtype=f)), f(eps))).astype(f)
+                z = (A @ kh).astype(f)
+                A = (A - np.outer(z, z) / (f(1) + kh @ z)).astype(f)
+                a = (A @ kh).astype(f)
+                a = (a / max(np.sqrt((a * a).sum(dtype=f)), f(eps))).astype(f)
+                S = (S + np.outer((v[b, h, t] - S @ kh).astype(f), a)).astype(f)
+                o[b, h, t] = S @ q[b, h, t]
+            S_T[b, h], A_T[b, h] = S, A
+    return o, S_T, A_T
+
+
 @pytest.mark.parametrize("mode", ALL_MODES)
 def test_repeated_key_is_overwritten_each_step(mode):
     """One key presented T times: every write replaces the previous value (S_t k^ = v_t).
-    cond(A_t) grows like (lambda0 + t)/lambda0 and z = A k^ is formed by cancellation, so float32
-    state carries ~1e-7 * cond relative error in the write direction whatever the kernel; the bound
-    here is 50x the float32-inherent error of a plain float32 run of the same recurrence (4e-4)."""
+
+    A_t = I/lambda0 - (1/lambda0 - 1/(lambda0 + t)) k^ k^T, so cond(A_t) = (lambda0 + t)/lambda0 (961 at
+    t = 96) and z = A k^, of size 1/(lambda0 + t), is what is left of entries of size 1/lambda0: float32 state
+    gives the write direction a relative error of about 6e-8 cond(A_t), whatever the kernel, and that error
+    lands in S.  What stays well conditioned is held to the usual tolerance -- A_T itself (1e-4) and the stored
+    value S_T k^ = v_T (1e-5: the error of the write direction is orthogonal to k^) -- and o and S_T are held to
+    4x the error of a plain float32 run of the same recurrence on the same input.  Measured (d = 64; o / S_T):
+    plain float32 1.8e-4 / 7.4e-4, scan 2.3e-4 / 8.7e-4, block 1.4e-4 / 3.1e-4, two-phase 1.3e-4 / 3.3e-4,
+    time-parallel 1.1e-4 / 3.2e-4; A_T 1.1e-6 and the stored value 2e-7 ... 6e-7 in every mode."""
     d, T = 64, 96
     skip_unless_mode(d, mode)
     q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=301)
     k[0, :, :] = k[0, :, :1]
-    errs, ref, (o, S_T, A_T) = check_parity(q, k, v, mode=mode, tol=2e-2)
-    kh = k[0, 0, 0] / np.linalg.norm(k[0, 0, 0])
-    assert np.abs(S_T[0, 0] @ kh - v[0, 0, -1]).max() <= 1e-3 * np.abs(v[0, 0, -1]).max()
+    ref = oracle.forward(q, k, v, lambda0=0.1)
+    o32, S32, A32 = plain_float32_recurrence(q, k, v)
+    floor_o, floor_S = slab_rel_err(o32, ref["o"], 2), slab_rel_err(S32, ref["S_T"], 2)
+    assert 1e-5 < floor_o < 1e-3 and 1e-4 < floor_S < 3e-3      # the yardstick itself is where the text says
+    o, S_T, A_T = gpu_forward(q, k, v, mode=mode)
+    errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(S_T, ref["S_T"], 2),
+                A=slab_rel_err(A_T, ref["A_T"], 2))
+    print(f"repeated key, mode {mode}: {errs}; plain float32: o {floor_o:.2e} S {floor_S:.2e}")
+    assert errs["A"] <= 1e-4, errs
+    assert errs["o"] <= 4 * floor_o and errs["S"] <= 4 * floor_S, (errs, floor_o, floor_S)
+    for h in range(2):
+        kh = k[0, h, 0] / np.linalg.norm(k[0, h, 0])
+        assert np.abs(S_T[0, h] @ kh - v[0, h, -1]).max() <= 1e-5 * np.abs(v[0, h, -1]).max()
 
 
 @pytest.mark.parametrize("mode", ALL_MODES)
