@@ -160,6 +160,29 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
                 void* stream);
 
 /*
+ * vla_forward_static -- vla_forward for callers that cannot allocate device memory or have none to pass as a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same results as vla_forward, without the workspace pair: the modes that need
+ * a workspace (TWO_PHASE, TIME_PARALLEL, and AUTO where it resolves to them) use an array of
+ * 64 MiB (67,108,864 bytes) that is part of the library's device image -- every GPU the library runs on holds
+ * its own copy from the first use of the library on it until the process ends.  The call allocates and frees
+ * nothing.
+ *
+ *   - A request whose vla_forward_workspace_bytes() exceeds 64 MiB returns VLA_ERR_WORKSPACE (with a
+ *     message on stderr) when TWO_PHASE or TIME_PARALLEL was asked for by name; AUTO runs CHUNKED instead,
+ *     as vla_forward does when it is given no workspace.
+ *   - The device that owns the buffers and `stream` must be the current device.  The first call on a device
+ *     looks the array's address up once (hipGetSymbolAddress; VLA_ERR_HIP if that fails): make that call
+ *     before a stream capture begins.
+ *   - All calls on one GPU share that GPU's array: two calls that need it and may overlap in time (different
+ *     streams, or graphs replayed concurrently) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array has to start at zero and nothing is kept in it between calls.
+ */
+int vla_forward_static(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                       void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                       int io_dtype, const vla_opts* opts, void* stream);
+
+/*
  * vla_decode_step -- one token of the same recurrence for every head, on a state that stays where it is
  * (generation: Section 7.4, the fixed-size state S, A is the whole memory).  Equivalent to vla_forward with
  * T = 1, S0 = S_T = S and A0 = A_T = A, but organised for the memory traffic that dominates a single step

@@ -13,7 +13,7 @@ _LIB_NAME = "libvla.so"
 VLA_F32, VLA_BF16 = 0, 1
 MODE_AUTO, MODE_SCAN, MODE_CHUNKED, MODE_TWO_PHASE, MODE_TIME_PARALLEL = 0, 1, 2, 3, 4
 
-EXPORTS = ("vla_default_opts", "vla_forward_workspace_bytes", "vla_forward",
+EXPORTS = ("vla_default_opts", "vla_forward_workspace_bytes", "vla_forward", "vla_forward_static",
            "vla_decode_step", "vla_status_string", "vla_version", "vla_resolve_mode")
 
 
@@ -62,6 +62,8 @@ def load_library():
     lib.vla_forward_workspace_bytes.restype = ctypes.c_size_t
     lib.vla_forward.argtypes = [P] * 8 + [I] * 6 + [OP, P, ctypes.c_size_t, P]
     lib.vla_forward.restype = I
+    lib.vla_forward_static.argtypes = [P] * 8 + [I] * 6 + [OP, P]
+    lib.vla_forward_static.restype = I
     lib.vla_decode_step.argtypes = [P] * 6 + [I] * 5 + [OP, P]
     lib.vla_decode_step.restype = I
     lib.vla_status_string.argtypes = [I]
@@ -120,6 +122,15 @@ def vla_forward_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *
     return int(load_library().vla_forward(n(q), n(k), n(v), n(S0), n(A0), n(o), n(S_T), n(A_T),
                                           B, H, T, d_k, d_v, io_dtype, ctypes.byref(op),
                                           n(workspace), int(workspace_bytes), n(stream)))
+
+
+def vla_forward_static_raw(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, *, lambda0=None,
+                           eps=None, mode=None, stream=0, **extra) -> int:
+    """vla_forward_raw without a workspace: the library's static array serves the modes that need one."""
+    op = _opts(lambda0, eps, mode, extra)
+    n = lambda x: ctypes.c_void_p(int(x) if x else None)
+    return int(load_library().vla_forward_static(n(q), n(k), n(v), n(S0), n(A0), n(o), n(S_T), n(A_T),
+                                                 B, H, T, d_k, d_v, io_dtype, ctypes.byref(op), n(stream)))
 
 
 def vla_decode_step_raw(q, k, v, S, A, o, B, H, d_k, d_v, io_dtype, *, eps=None, stream=0, **extra) -> int:

@@ -5,9 +5,44 @@
 
 #include <stdio.h>
 
+#include <mutex>
+
+// Workspace of vla_forward_static: one array per GPU, part of the library's device image, held until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress; the kernels get the
+// device address that call returns.
+constexpr size_t kScratchBytes = size_t{64} << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
-constexpr int kVersion = 500;  // 0.5.0
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, looked up once
+
+// Address of the current device's copy of `scratch` (nullptr and a message on failure).
+void* scratch_of_current_device() {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fprintf(stderr, "libvla: vla_forward_static: no usable current device (%s, device %d)\n",
+            hipGetErrorString(err), dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || p == nullptr) {
+      fprintf(stderr, "libvla: vla_forward_static: hipGetSymbolAddress failed on device %d: %s\n", dev,
+              hipGetErrorString(err));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+constexpr int kVersion = 600;  // 0.6.0
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -168,10 +203,16 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   return 0;
 }
 
-int vla_forward(const void* q, const void* k, const void* v, const float* S0, const float* A0,
-                void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
-                int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
-                void* stream) {
+}  // extern "C"
+
+namespace {
+
+// vla_forward and vla_forward_static.  `own_scratch`: the workspace is the library's static array, looked up
+// only once the request is known to be valid and to need one.
+int forward_impl(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                 void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                 int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
+                 bool own_scratch, void* stream) {
   const vla_opts op = resolve_opts(opts);
   const int st = check_shape(B, H, T, d_k, d_v, io_dtype, op);
   if (st != VLA_OK) return st;
@@ -199,9 +240,21 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
   if (!mode_available(mode, d_k, d_v, op)) return VLA_ERR_UNSUPPORTED;
   if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return VLA_ERR_UNSUPPORTED;
   const size_t need = vla_forward_workspace_bytes(B, H, T, d_k, d_v, io_dtype, &op);
+  if (own_scratch && need > 0 && need <= kScratchBytes) {
+    workspace = scratch_of_current_device();
+    if (workspace == nullptr) return VLA_ERR_HIP;
+    workspace_bytes = kScratchBytes;
+  }
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
     // AUTO never fails for want of a workspace: it falls back to the fused block kernel
-    if (op.mode != VLA_MODE_AUTO) return VLA_ERR_WORKSPACE;
+    if (op.mode != VLA_MODE_AUTO) {
+      if (own_scratch) {
+        fprintf(stderr, "libvla: vla_forward_static: this call needs %zu bytes of workspace, the static "
+                        "array holds %zu; use vla_forward with a workspace of the caller's\n",
+                need, kScratchBytes);
+      }
+      return VLA_ERR_WORKSPACE;
+    }
     mode = VLA_MODE_CHUNKED;
   }
   if (T == 0 && S_T == nullptr && A_T == nullptr && op.zkey_T == nullptr) return VLA_OK;  // nothing to do
@@ -246,6 +299,25 @@ int vla_forward(const void* q, const void* k, const void* v, const float* S0, co
     return VLA_ERR_HIP;
   }
   return VLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vla_forward(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                int io_dtype, const vla_opts* opts, void* workspace, size_t workspace_bytes,
+                void* stream) {
+  return forward_impl(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, opts, workspace,
+                      workspace_bytes, false, stream);
+}
+
+int vla_forward_static(const void* q, const void* k, const void* v, const float* S0, const float* A0,
+                       void* o, float* S_T, float* A_T, int B, int H, int T, int d_k, int d_v,
+                       int io_dtype, const vla_opts* opts, void* stream) {
+  return forward_impl(q, k, v, S0, A0, o, S_T, A_T, B, H, T, d_k, d_v, io_dtype, opts, nullptr, 0, true,
+                      stream);
 }
 
 int vla_decode_step(const void* q, const void* k, const void* v, float* S, float* A, void* o, int B,

@@ -197,3 +197,35 @@ def test_torch_front_end_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 4, 16)
     with pytest.raises(ValueError):
         vla.vla_forward(x, x, x)
+
+
+def test_device_image_exports_the_static_workspace_symbol():
+    """vla_forward_static finds its array through hipGetSymbolAddress, which looks the name up in the device
+    code object: the array has to be a global, defined symbol of 64 MiB there (a file-scope static that the
+    compiler kept local would only show as a failure on the GPU)."""
+    import shutil
+    import subprocess
+    import tempfile
+
+    readelf = "/opt/rocm/llvm/bin/llvm-readelf"
+    bundler = "/opt/rocm/llvm/bin/clang-offload-bundler"
+    if not (os.path.exists(readelf) and os.path.exists(bundler) and shutil.which("objcopy")):
+        pytest.skip("binutils / ROCm LLVM tools not present")
+    with tempfile.TemporaryDirectory() as tmp:
+        fat = os.path.join(tmp, "fatbin")
+        subprocess.run(["objcopy", "-O", "binary", "--only-section=.hip_fatbin", vla.lib_path(), fat], check=True)
+        blob = open(fat, "rb").read()
+        magic = b"__CLANG_OFFLOAD_BUNDLE__"
+        starts = [i for i in range(len(blob)) if blob.startswith(magic, i)]
+        assert starts
+        found = []
+        for n, (a, b) in enumerate(zip(starts, starts[1:] + [len(blob)])):
+            piece, elf = os.path.join(tmp, f"b{n}"), os.path.join(tmp, f"b{n}.elf")
+            open(piece, "wb").write(blob[a:b])
+            subprocess.run([bundler, "--unbundle", "--type=o", f"--input={piece}",
+                            "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={elf}"], check=True,
+                           capture_output=True)
+            syms = subprocess.run([readelf, "-sW", elf], capture_output=True, text=True).stdout
+            found += [l.split() for l in syms.splitlines() if l.strip().endswith("scratch") or "7scratch" in l]
+    assert found, "no scratch symbol in any device code object"
+    assert any(f[2] == str(64 << 20) and f[3] == "OBJECT" and f[4] == "GLOBAL" and f[6] != "UND" for f in found), found
