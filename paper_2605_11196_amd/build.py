@@ -71,6 +71,39 @@ def build(verbose: bool = False, extra=(), incremental: bool = False, jobs: int 
     return OUT
 
 
+def resource_usage(src, extra=()):
+    """The compiler's own resource report for every kernel of one source (device pass only, nothing is
+    written next to the library): {demangled kernel name: {"VGPRs": n, "AGPRs": n, "ScratchSize": bytes per
+    lane, "VGPRSpill": n, "SGPRSpill": n, "Occupancy": waves per SIMD, "LDSSize": bytes, ...}}."""
+    import re
+    import tempfile
+
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [HIPCC] + FLAGS + list(extra) + ["--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                                               "-c", src, "-o", os.path.join(tmp, "dev.o")]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise subprocess.CalledProcessError(r.returncode, cmd)
+    out, cur = {}, None
+    keys = {"TotalSGPRs": "SGPRs", "VGPRs": "VGPRs", "AGPRs": "AGPRs", "ScratchSize [bytes/lane]": "ScratchSize",
+            "Occupancy [waves/SIMD]": "Occupancy", "SGPRs Spill": "SGPRSpill", "VGPRs Spill": "VGPRSpill",
+            "LDS Size [bytes/block]": "LDSSize"}
+    for line in (r.stdout + r.stderr).splitlines():
+        m = re.search(r"remark: (?:\S+: )?\s*Function Name: (\S+)", line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark: (?:\S+: )?\s*([A-Za-z][A-Za-z /\[\]]*?): (\d+)", line)
+        if m and cur is not None and m.group(1).strip() in keys:
+            cur[keys[m.group(1).strip()]] = int(m.group(2))
+    names = list(out)
+    if names:
+        dem = subprocess.run(["c++filt"] + names, capture_output=True, text=True).stdout.split("\n")
+        out = {d.strip() or n: out[n] for n, d in zip(names, dem)}
+    return out
+
+
 if __name__ == "__main__":
     args = sys.argv[1:]
     inc = "--incremental" in args

@@ -474,10 +474,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   {
     float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
     float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * DV * D : nullptr;
-    int g2 = g;
-    asm volatile("" : "+v"(g2));  // recompute the addresses here instead of carrying them over the loop
-    const int arc = (4 * g2) * D + col0 + c;
-    const int src = (row0 + c) * D + 4 * g2;
+    int g2 = g, c2 = c;
+    asm volatile("" : "+v"(g2), "+v"(c2));  // recompute the addresses here instead of carrying them over the loop
+    const int arc = (4 * g2) * D + col0 + c2;
+    const int src = (row0 + c2) * D + 4 * g2;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (AT) {

@@ -4,16 +4,17 @@
 // (S_t[i,:] = S_{t-1}[i,:] + e_t[i] alpha^_t^T) and are spread over many more workgroups than heads.
 //
 // Same block form (16 tokens) and notation as vla_chunk.hip.  Per (head, block) the workspace holds
-//   K^  [16][D]      normalised keys (token-major)
+//   RN  [16]         1 / max(||k_t||, eps) per token (0 for rows past the end): the S recurrence re-forms
+//                    k^_t = k_t * RN[t] from the raw keys, so the normalised keys never travel through memory
 //   W   [D][16]      w_t = z_t / sqrt(delta_t), tokens contiguous
-//   SM  [784]        phase 1 writes L | L^{-1} | GQ | ||w_t||^2 ; phase 1b turns them in place into
-//                    Z | L^{-1} | -NQ^T | -c_t  (all 16x16 row-major, vectors of 16)
+//   SM  [528]        Z | -NQ^T | -c_t  (two 16x16 row-major matrices and a vector of 16)
 //
-//   phase 1  (a_scan_kernel):  one workgroup per head, the A chain of the block form
-//   phase 1b (zc_kernel):      one wave per (head, block), the C x C work the S recurrence needs
-//   phase 2  (s_rows_kernel):  one wave per (head, 16-row slab of S); operands come straight from
-//                              global memory in MFMA operand layout, no LDS and no barriers
-//            (s_rows_lds_kernel, many heads): one workgroup per head, operands shared through LDS
+//   phase 1 (a_scan_kernel):  one workgroup per head, the A chain of the block form; the C x C work the S
+//                             recurrence needs (c_t, Z, NQ) is done one block behind by a wave that would
+//                             otherwise wait for the factorisation of the next block
+//   phase 2 (s_rows_kernel):  one wave per (head, 16-row slab of S); operands come straight from
+//                             global memory in MFMA operand layout, no LDS and no barriers
+//           (s_rows_lds_kernel, many heads): one workgroup per head, operands shared through LDS
 //
 // Every kernel also takes a time segment of the sequence instead of the whole of it: the time-parallel mode
 // (driver at the end of this file, boundary states in vla_segments.hip) runs the segments concurrently.
@@ -24,19 +25,21 @@
 namespace vla {
 namespace {
 
-constexpr int SMB = 3 * C * C + C;  // floats of small matrices per (head, block)
+constexpr int SMB = 2 * C * C + C;  // floats of small matrices per (head, block)
 
 __host__ __device__ constexpr size_t head_stride(int nblk, int D) {
-  return static_cast<size_t>(nblk) * (2 * C * D + SMB);
+  return static_cast<size_t>(nblk) * (C + C * D + SMB);
 }
 // sub-array offsets inside one head's workspace (floats)
-__device__ __forceinline__ size_t off_kh(int /*nblk*/, int /*D*/) { return 0; }
-__device__ __forceinline__ size_t off_wt(int nblk, int D) { return static_cast<size_t>(nblk) * C * D; }
-__device__ __forceinline__ size_t off_sm(int nblk, int D) { return static_cast<size_t>(nblk) * 2 * C * D; }
+__host__ __device__ constexpr size_t off_rn(int /*nblk*/, int /*D*/) { return 0; }
+__host__ __device__ constexpr size_t off_wt(int nblk, int /*D*/) { return static_cast<size_t>(nblk) * C; }
+__host__ __device__ constexpr size_t off_sm(int nblk, int D) { return static_cast<size_t>(nblk) * (C + C * D); }
 
 // ------------------------------------------------------------------------------------------ phase 1
+// Two-wave workgroups (d <= 64) are compiled for three waves per SIMD.
 template <int D, int NW, typename IO>
-__global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
+__global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(ForwardArgs a) {
+  static_assert(NW >= 2, "the C x C pass of the previous block runs on a second wave");
   constexpr int SL = D / NW;
   constexpr int NJ = SL / 16;
   constexpr int NB = D / 16;
@@ -44,14 +47,18 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int EPT = C * D / NT;
   constexpr int TPR = D / EPT;
-  static_assert(EPT % 8 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
+  static_assert(EPT % 4 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
 
   __shared__ __align__(16) float Ks[C * LD];
   __shared__ __align__(16) float Qs[C * LD];
   __shared__ __align__(16) float Ys[C * LD];
   __shared__ __align__(16) float Wb[D * LT];
   __shared__ __align__(16) float Gp[NW][2][C * LT];
-  __shared__ __align__(16) float Lis[C * LT];
+  // kept for one more block (two copies, by block parity): the wave that turns them into c, Z, NQ reads the
+  // previous block's while the factorisation of the current block writes its own
+  __shared__ __align__(16) float Lis[2][C * LT];   // L^{-1} [t][s]
+  __shared__ __align__(16) float Lrs[2][C * LT];   // L [t][s]
+  __shared__ __align__(16) float GQs[2][C * LT];   // GQ [s][t]
   __shared__ __align__(16) float wn2p[NW][C];
 
   // One workgroup per (head, time segment); with a single segment it walks the whole sequence.
@@ -70,7 +77,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   const int nblk = (a.T + C - 1) / C;                                      // blocks of the whole sequence
 
   float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
-  float* KH = wsh + off_kh(nblk, D);
+  float* RN = wsh + off_rn(nblk, D);
   float* WT = wsh + off_wt(nblk, D);
   float* SMp = wsh + off_sm(nblk, D);
 
@@ -110,9 +117,57 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   };
   if (tb < T) prefetch(tb);
 
+  int cc = c;  // opaque copy: keeps the (c == t) masks from being hoisted into 16 registers
+  asm volatile("" : "+v"(cc));
+
+  // c_t, Z = (I + strict_lower(L) diag(c))^{-1} and -NQ^T of one block from what its factorisation left in LDS
+  // copy `pb`; one wave.  Results go to the block's record in the workspace.
+  auto cz_pass = [&](int pb, float* smb) {
+    float m[C];  // lane c: row c of L
+#pragma unroll
+    for (int s4 = 0; s4 < C; s4 += 4) {
+      const f4 lr = lds4(&Lrs[pb][c * LT + s4]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) m[s4 + e] = lr[e];
+    }
+    const float dl = Lrs[pb][c * LT + c];  // L_cc
+    float wn2 = 0.0f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
+    // hardware reciprocal and square root (1 ulp): c_t only scales the write direction
+    const float rdl = __builtin_amdgcn_rcpf(dl);
+    const float an = __builtin_amdgcn_sqrtf(wn2) * rdl;                // ||A_t k^_t|| = ||w_t|| / L_tt
+    const float cs = rdl * __builtin_amdgcn_rcpf(fmaxf(an, eps));      // alpha^_t = c_t w_t
+    float nm[C], Zr[C];
+    float ncs = -cs;
+    asm volatile("s_nop 1" : "+v"(ncs));   // a DPP read of a VGPR needs 2 wait states after its write
+    scale_cols<0>(m, nm, ncs);             // lane t: -L[t][s] c_s
+    asm volatile("s_nop 1" : "+v"(nm[0]));
+    z_rows<0>(nm, Zr, cc);
+    const f4 la = lds4(&Lis[pb][c * LT + 4 * g]);
+    f4 hq = f4{0, 0, 0, 0};   // H = L^{-1} GQ
+#pragma unroll
+    for (int r = 0; r < 4; ++r) hq = mfma16(la[r], GQs[pb][(4 * g + r) * LT + c], hq);
+    f4 nq;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int sidx = 4 * g + r;
+      const float csr = __shfl(cs, sidx);
+      nq[r] = (sidx <= c) ? -(csr * hq[r]) : 0.0f;
+    }
+    if (g == 0) {
+#pragma unroll
+      for (int t = 0; t < C; ++t) smb[t * C + c] = Zr[t];
+      smb[2 * C * C + c] = -cs;
+    }
+    *reinterpret_cast<f4*>(smb + C * C + c * C + 4 * g) = nq;  // -NQ^T[t = c][s = 4g + r]
+  };
+
   int blk = seg * a.seg_blocks;
-  for (int t0 = tb; t0 < T; t0 += C, ++blk) {
-    // ---- stage K^ (LDS and workspace) and Q (LDS)
+  int it = 0;   // blocks done by this workgroup
+  for (int t0 = tb; t0 < T; t0 += C, ++blk, ++it) {
+    const int pb = it & 1;
+    // ---- stage K^ and Q (LDS); 1 / max(||k||, eps) per token goes to the workspace
     {
       float kx[EPT];
       const bool live = t0 + srow < T;
@@ -132,12 +187,11 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
       const float sm = fmaxf(ss, eps * eps);
       float rn = __builtin_amdgcn_rsqf(sm);
       rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f);
-      float* kg = KH + static_cast<size_t>(t0 + srow) * D + sseg;
+      if (sseg == 0) RN[t0 + srow] = live ? rn : 0.0f;   // rows past the end: zero keys
 #pragma unroll
       for (int e = 0; e < EPT; e += 4) {
-        const f4 kv = f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
-        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) = kv;
-        *reinterpret_cast<f4*>(kg + e) = kv;
+        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) =
+            f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
       }
       qpre.unpack(kx);
       if (fmap) {
@@ -191,12 +245,11 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
     }
     __syncthreads();  // (2)
 
-    // ---- Cholesky of I + G and L^{-1} (lanes <32 rows of L, lanes >=32 columns of L^{-1})
-    float* smb = SMp + static_cast<size_t>(blk) * SMB;
-    const int sw = blk % NW;
+    // ---- one wave: Cholesky of I + G and L^{-1} (lanes <32 rows of L, lanes >=32 columns of L^{-1});
+    //      another wave meanwhile: c, Z, NQ of the previous block
+    const int sw = it % NW;
+    const int sw2 = (it + 1) % NW;
     if (w == sw) {
-      int cc = c;
-      asm volatile("" : "+v"(cc));
       const bool lower = lane < 32;
       float m[C];
 #pragma unroll
@@ -208,7 +261,7 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
           acc += lds4(&Gp[ww][0][c * LT + s4]);
           acq += lds4(&Gp[ww][1][c * LT + s4]);
         }
-        if (g == 1) *reinterpret_cast<f4*>(smb + 2 * C * C + c * C + s4) = acq;  // GQ
+        if (g == 1) *reinterpret_cast<f4*>(&GQs[pb][c * LT + s4]) = acq;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           m[s4 + e] = (lower ? acc[e] : 0.0f) + ((s4 + e) == cc ? 1.0f : 0.0f);
@@ -225,20 +278,19 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
       if (g == 0) {  // rows of L
 #pragma unroll
         for (int s4 = 0; s4 < C; s4 += 4)
-          *reinterpret_cast<f4*>(smb + c * C + s4) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
+          *reinterpret_cast<f4*>(&Lrs[pb][c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
       if (g == 2) {  // columns of L^{-1}
 #pragma unroll
-        for (int t = 0; t < C; ++t) {
-          Lis[t * LT + c] = m[t];
-          smb[C * C + t * C + c] = m[t];
-        }
+        for (int t = 0; t < C; ++t) Lis[pb][t * LT + c] = m[t];
       }
+    } else if (w == sw2 && it > 0) {
+      cz_pass(pb ^ 1, SMp + static_cast<size_t>(blk - 1) * SMB);
     }
     __syncthreads();  // (3)
 
     // ---- W^T = L^{-1} Y^T -> LDS and workspace; partial norms
-    const f4 la = lds4(&Lis[c * LT + 4 * g]);
+    const f4 la = lds4(&Lis[pb][c * LT + 4 * g]);
     f4 nwt[NJ];
     {
       f4 n2 = f4{0, 0, 0, 0};
@@ -254,20 +306,11 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
         *reinterpret_cast<f4*>(wg + (col0 + 16 * jn + c) * C + 4 * g) = acc;
       }
 #pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) n2[r] += __shfl_xor(n2[r], off);
-      }
+      for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
     __syncthreads();  // (4)
 
-    if (w == sw && g == 0) {
-      float wn2 = 0.0f;
-#pragma unroll
-      for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
-      smb[3 * C * C + c] = wn2;
-    }
     // ---- A -= W W^T
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -278,12 +321,14 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
         for (int jn = 0; jn < NJ; ++jn) At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
     }
   }
+  // c, Z, NQ of the last block: everything it needs was written before the last barrier
+  if (it > 0 && w == it % NW) cz_pass((it - 1) & 1, SMp + static_cast<size_t>(blk - 1) * SMB);
 
   if (a.A_T && seg == a.n_seg - 1) {
     float* AT = a.A_T + static_cast<size_t>(head) * D * D;
-    int g2 = g;
-    asm volatile("" : "+v"(g2));
-    const int arc = (4 * g2) * D + col0 + c;
+    int g2 = g, c2 = c;
+    asm volatile("" : "+v"(g2), "+v"(c2));
+    const int arc = (4 * g2) * D + col0 + c2;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -293,67 +338,11 @@ __global__ void __launch_bounds__(64 * NW) a_scan_kernel(ForwardArgs a) {
   }
 }
 
-// ------------------------------------------------------------------------------------------ phase 1b
-// One wave per (head, block): c_t, Z = (I + strict_lower(L) diag(c))^{-1}, -NQ^T, in place.
-__global__ void __launch_bounds__(256) zc_kernel(float* ws, int n_heads, int nblk, int D, float eps) {
-  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
-  if (wave >= n_heads * nblk) return;
-  const int head = wave / nblk, blk = wave - head * nblk;
-  const int lane = threadIdx.x & 63;
-  const int c = lane & 15;
-  const int g = lane >> 4;
-  float* smb = ws + static_cast<size_t>(head) * head_stride(nblk, D) +
-               static_cast<size_t>(nblk) * 2 * C * D + static_cast<size_t>(blk) * SMB;
-
-  float m[C];  // lane c: row c of L
-#pragma unroll
-  for (int s4 = 0; s4 < C; s4 += 4) {
-    const f4 lr = *reinterpret_cast<const f4*>(smb + c * C + s4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) m[s4 + e] = lr[e];
-  }
-  const f4 la = *reinterpret_cast<const f4*>(smb + C * C + c * C + 4 * g);  // L^{-1}[c][4g..]
-  float gqv[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) gqv[r] = smb[2 * C * C + (4 * g + r) * C + c];
-  const float wn2 = smb[3 * C * C + c];
-  float dl = m[0];
-#pragma unroll
-  for (int s = 1; s < C; ++s) dl = (c == s) ? m[s] : dl;
-  // hardware reciprocal and square root (1 ulp): c_t only scales the write direction
-  const float rdl = __builtin_amdgcn_rcpf(dl);
-  const float an = __builtin_amdgcn_sqrtf(wn2) * rdl;
-  const float cs = rdl * __builtin_amdgcn_rcpf(fmaxf(an, eps));
-
-  float nm[C], Zr[C];
-  float ncs = -cs;
-  asm volatile("s_nop 1" : "+v"(ncs));   // a DPP read of a VGPR needs 2 wait states after its write
-  scale_cols<0>(m, nm, ncs);             // lane t: -L[t][s] c_s
-  asm volatile("s_nop 1" : "+v"(nm[0]));
-  z_rows<0>(nm, Zr, c);
-  f4 hq = f4{0, 0, 0, 0};
-#pragma unroll
-  for (int r = 0; r < 4; ++r) hq = mfma16(la[r], gqv[r], hq);
-  f4 nq;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int s = 4 * g + r;
-    const float csr = __shfl(cs, s);
-    nq[r] = (s <= c) ? -(csr * hq[r]) : 0.0f;
-  }
-  // every value read above is in registers; now overwrite in place
-  if (g == 0) {
-#pragma unroll
-    for (int t = 0; t < C; ++t) smb[t * C + c] = Zr[t];
-    smb[3 * C * C + c] = -cs;
-  }
-  *reinterpret_cast<f4*>(smb + 2 * C * C + c * C + 4 * g) = nq;  // -NQ^T[t = c][s = 4g + r]
-}
-
 // ------------------------------------------------------------------------------------------ phase 2
 // One wave per (head, time segment, 16-row slab of S), no LDS and no barriers: the most waves when heads are
-// few.  st[b][r] = S[row0 + c][16b + 4g + r]; the operands of a block (K^, W, Z, -NQ^T, -c, q) come straight
-// from global memory in MFMA operand layout.
+// few.  st[b][r] = S[row0 + c][16b + 4g + r]; the operands of a block (W, Z, -NQ^T, -c from the workspace, the raw
+// k and q, and 1 / ||k|| per token, from which k^ is re-formed) come straight from global memory in MFMA operand
+// layout.
 //
 // MAP = false: the recurrence proper: reads q, writes o.
 // MAP = true:  the affine map S_end = S_start P + Q of one segment, for the time-parallel mode.  Rows of S
@@ -387,12 +376,13 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   if (MAP && seg == a.n_seg - 1) return;             // nothing follows the last segment
 
   const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
-  const float* KH = wsh;
-  const float* WT = wsh + static_cast<size_t>(nblk) * C * D;
-  const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
+  const float* RN = wsh + off_rn(nblk, D);
+  const float* WT = wsh + off_wt(nblk, D);
+  const float* SMp = wsh + off_sm(nblk, D);
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
-  const bool fmap = a.feature_map != 0;   // q is replaced by ELU(x) + 1 as it is consumed
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are consumed
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -412,33 +402,34 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
 
   // operands of one block, in MFMA operand layout, straight from global memory
   struct Ops {
-    f4 ka[NB], wa[NB];
-    RawRow<IO, 4> qa[NB];
+    f4 wa[NB];
+    RawRow<IO, 4> ka[NB], qa[NB];
+    float rn;           // 1 / max(||k||, eps) of token row c (0 past the end)
     f4 za, nqa, ncg;
     IO v[4];
   };
   // Addresses are a per-block uniform base (scalar registers) plus lane-constant 32-bit offsets, so that a
   // load costs no vector address arithmetic; only the ragged last block clamps its token rows.
-  const unsigned ko = static_cast<unsigned>(c * D + 4 * g);   // K^ row c
   const unsigned wo = static_cast<unsigned>(c * C + 4 * g);   // W row c of a 16-column slice; Z / NQ row c
   const unsigned vo = static_cast<unsigned>(4 * g * D + row0 + c);  // v and o: token 4g, column row0 + c
   auto load_ops = [&](int blk, Ops& o) {
-    const float* kb = KH + static_cast<size_t>(blk) * (C * D);
+    const IO* kb = kh + static_cast<size_t>(blk) * (C * D);
     const float* wb = WT + static_cast<size_t>(blk) * (D * C);
     const float* sp = SMp + static_cast<size_t>(blk) * SMB;
     const IO* qb = qh + static_cast<size_t>(blk) * (C * D);
     const IO* vb = vh + static_cast<size_t>(blk) * (C * D);
     const int lim = T - 1 - blk * C;                          // last live token row of this block
-    const unsigned qo = static_cast<unsigned>(min(c, lim) * D + 4 * g);
+    const unsigned qo = static_cast<unsigned>(min(c, lim) * D + 4 * g);   // rows past the end: a copy of the last
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      o.ka[b] = *reinterpret_cast<const f4*>(kb + ko + 16 * b);
+      o.ka[b].load(kb + qo + 16 * b);
       o.wa[b] = *reinterpret_cast<const f4*>(wb + wo + 16 * b * C);
       if constexpr (!MAP) o.qa[b].load(qb + qo + 16 * b);
     }
+    o.rn = RN[blk * C + c];
     o.za = *reinterpret_cast<const f4*>(sp + wo);
-    if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + 2 * C * C + wo);
-    o.ncg = *reinterpret_cast<const f4*>(sp + 3 * C * C + 4 * g);
+    if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + C * C + wo);
+    o.ncg = *reinterpret_cast<const f4*>(sp + 2 * C * C + 4 * g);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       o.v[r] = vb[static_cast<unsigned>(min(4 * g + r, lim) * D + row0 + c)];
@@ -454,7 +445,14 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(cur.v[r]) : 0.0f;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      float qx[4];
+      float kx[4], qx[4];
+      cur.ka[b].unpack(kx);
+      if (fmap) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) kx[r] = elu_plus_one(kx[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) kx[r] *= cur.rn;   // the same product the A scan formed k^ with
       if constexpr (!MAP) {
         cur.qa[b].unpack(qx);
         if (fmap) {
@@ -464,7 +462,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        ft = mfma16(cur.ka[b][r], st[b][r], ft);
+        ft = mfma16(kx[r], st[b][r], ft);
         if constexpr (!MAP) ot = mfma16(qx[r], st[b][r], ot);
       }
     }
@@ -589,12 +587,13 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const int T = min(a.T, be * C);
 
   const float* wsh = a.ws + static_cast<size_t>(head) * head_stride(nblk, D);
-  const float* KH = wsh;
-  const float* WT = wsh + static_cast<size_t>(nblk) * C * D;
-  const float* SMp = wsh + static_cast<size_t>(nblk) * 2 * C * D;
+  const float* RN = wsh + off_rn(nblk, D);
+  const float* WT = wsh + off_wt(nblk, D);
+  const float* SMp = wsh + off_sm(nblk, D);
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
-  const bool fmap = a.feature_map != 0;   // q is replaced by ELU(x) + 1 as it is consumed
+  const IO* kh = static_cast<const IO*>(a.k) + slab;
+  const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are consumed
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -613,7 +612,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   }
 
   // ---- this thread's share of a block's operands
-  // big operands: piece `pc` of K^ and of q (row pc / (D/4), columns 4 (pc % (D/4)) ..) and of W (row
+  // big operands: piece `pc` of k and of q (row pc / (D/4), columns 4 (pc % (D/4)) ..) and of W (row
   // pc / 4 of [D][16], columns 4 (pc % 4) ..); in the map pass the first half of the threads carries K^ and
   // the second half W.  small operands: Z (64 pieces), -NQ^T (64), -c (4) on the first threads.
   const int pc = MAP ? tid % CH : tid;
@@ -621,29 +620,40 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const bool do_w = !MAP || tid >= CH;
   const int krow = pc / (D / 4), kcol = 4 * (pc % (D / 4));
   const int wrow = pc / 4, wcol = 4 * (pc % 4);
-  const int sm_src = tid < 64 ? 4 * tid : 2 * C * C + 4 * (tid - 64);
+  const int sm_src = tid < 64 ? 4 * tid : C * C + 4 * (tid - 64);
   const bool do_sm = tid < (MAP ? 64 : 128);   // Z on threads 0-63, -NQ^T on 64-127 (not in the map pass)
   const bool do_c = tid < 4;                   // -c
   struct Regs {
-    f4 kx, wx, sx, cx;
-    RawRow<IO, 4> qx;
+    f4 wx, sx, cx;
+    RawRow<IO, 4> kx, qx;
+    float krn;          // 1 / max(||k||, eps) of token row krow (0 past the end)
     IO v[4];
   };
   auto fetch = [&](int blk, Regs& r) {
-    if (do_k) r.kx = *reinterpret_cast<const f4*>(KH + static_cast<size_t>(blk) * (C * D) + krow * D + kcol);
+    const int lim = T - 1 - blk * C;   // last live token row of the block
+    const size_t kq = static_cast<size_t>(blk) * (C * D) + min(krow, lim) * D + kcol;   // past the end: the last row
+    if (do_k) {
+      r.kx.load(kh + kq);
+      r.krn = RN[blk * C + krow];
+    }
     if (do_w) r.wx = *reinterpret_cast<const f4*>(WT + static_cast<size_t>(blk) * (D * C) + wrow * C + wcol);
     if (do_sm) r.sx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + sm_src);
-    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 3 * C * C + 4 * tid);
-    const int lim = T - 1 - blk * C;   // last live token row of the block
-    if constexpr (!MAP) {
-      r.qx.load(qh + static_cast<size_t>(blk) * (C * D) + min(krow, lim) * D + kcol);
-    }
+    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
+    if constexpr (!MAP) r.qx.load(qh + kq);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       r.v[i] = vh[static_cast<size_t>(blk) * (C * D) + min(4 * g + i, lim) * D + row0 + c];
   };
   auto put = [&](const Regs& r, Stage& s) {
-    if (do_k) *reinterpret_cast<f4*>(&s.Ks[krow * LD + kcol]) = r.kx;
+    if (do_k) {   // k^ = k / max(||k||, eps): the same product the A scan formed it with
+      float x[4];
+      r.kx.unpack(x);
+      if (fmap) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = elu_plus_one(x[i]);
+      }
+      *reinterpret_cast<f4*>(&s.Ks[krow * LD + kcol]) = f4{x[0] * r.krn, x[1] * r.krn, x[2] * r.krn, x[3] * r.krn};
+    }
     if (do_w) *reinterpret_cast<f4*>(&s.Wb[wrow * LT + wcol]) = r.wx;
     if (do_sm) {
       // Z and -NQ^T rows are 16 floats in the workspace and LT in LDS
@@ -765,7 +775,7 @@ hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
                          dim3(a.n_heads * a.n_seg), dim3(64 * (D / 16) * (MAP ? 2 : 1)), params, 0, stream);
 }
 
-// Phase 1, 1b and 2 over every (head, segment) of `a`.
+// Phase 1 and 2 over every (head, segment) of `a`.
 template <int D, int NW, typename IO>
 hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
@@ -776,17 +786,6 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
                                    dim3(static_cast<unsigned>(hs)),
                                    dim3(64 * NW), params, 0, stream);
   if (err != hipSuccess) return err;
-  const int nblk = (a.T + C - 1) / C;
-  const long long waves = static_cast<long long>(a.n_heads) * nblk;
-  if (waves > 0) {
-    float* ws = a.ws;
-    int nh = a.n_heads, nb = nblk, d = D;
-    float eps = a.eps;
-    void* p2[] = {&ws, &nh, &nb, &d, &eps};
-    err = hipLaunchKernel(reinterpret_cast<const void*>(&zc_kernel),
-                          dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), p2, 0, stream);
-    if (err != hipSuccess) return err;
-  }
   // With enough (head, segment) pairs to fill the chip the block operands are shared through LDS by a
   // workgroup per pair; with few, one wave per slab of S and deep register prefetch give the most waves.
   const bool shared = hs >= 256;
@@ -815,7 +814,7 @@ namespace {
 hipError_t dispatch_phases(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
   const bool bf = io_dtype == 1;
   switch (d) {
-    case 32: return bf ? launch_phases<32, 1, uint16_t>(a, stream) : launch_phases<32, 1, float>(a, stream);
+    case 32: return bf ? launch_phases<32, 2, uint16_t>(a, stream) : launch_phases<32, 2, float>(a, stream);
     case 64: return bf ? launch_phases<64, 2, uint16_t>(a, stream) : launch_phases<64, 2, float>(a, stream);
     case 128: return bf ? launch_phases<128, 4, uint16_t>(a, stream) : launch_phases<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;

@@ -167,12 +167,13 @@ def test_workspace_query_and_mode_resolution():
 
 
 def test_time_parallel_workspace_follows_the_segment_plan():
-    """Workspace = the two-phase region + per (head, segment) one float64 and four float32 d x d matrices
-    (Gram, A start, P, Q, S start); one segment needs nothing beyond the two-phase region."""
+    """Workspace = the two-phase region (per 16-token block: 16 reciprocal key norms, W [d][16], Z and -NQ^T
+    [16][16] and 16 write strengths) + per (head, segment) one float64 and four float32 d x d matrices (Gram,
+    A start, P, Q, S start); one segment needs nothing beyond the two-phase region."""
     B, H, T, d = 1, 16, 8192, 64
     two = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
     nblk = T // 16
-    assert two == B * H * nblk * (2 * 16 * d + 784) * 4
+    assert two == B * H * nblk * (16 + 16 * d + 528) * 4
     tp = lambda s: vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16,
                                                    mode=vla.MODE_TIME_PARALLEL, segments=s)
     assert tp(1) == two
@@ -182,10 +183,10 @@ def test_time_parallel_workspace_follows_the_segment_plan():
     assert tp(100) == two + B * H * 86 * d * d * 4 * 6
     # never more segments than blocks, never more than 256
     assert vla.vla_forward_workspace_bytes(1, 1, 64, d, d, vla.VLA_F32, mode=vla.MODE_TIME_PARALLEL,
-                                           segments=99) == 4 * (2 * 16 * d + 784) * 4 + 4 * d * d * 24
+                                           segments=99) == 4 * (16 + 16 * d + 528) * 4 + 4 * d * d * 24
     big = vla.vla_forward_workspace_bytes(1, 1, 16 * 4096, d, d, vla.VLA_F32,
                                           mode=vla.MODE_TIME_PARALLEL, segments=100000)
-    assert big == 4096 * (2 * 16 * d + 784) * 4 + 256 * d * d * 24
+    assert big == 4096 * (16 + 16 * d + 528) * 4 + 256 * d * d * 24
     # the library's own choice: about 1024 (head, segment) pairs, segments of at least 16 blocks
     auto = tp(0)
     assert auto == two + B * H * 32 * d * d * 24          # 512 blocks / 16 = 32 < 1024 / 16 heads = 64

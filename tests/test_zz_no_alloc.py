@@ -90,7 +90,7 @@ def test_request_beyond_the_static_array_is_refused_or_rerouted():
     import paper_2605_11196_amd as vla
 
     dev = torch.device("cuda:0")
-    B, H, T, d = 1, 8, 16384, 64
+    B, H, T, d = 1, 8, 32768, 64
     assert vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE) > STATIC_BYTES
     q, k, v = vla_inputs.device_gaussian(B, H, T, d, 5, 1.0, torch.bfloat16)
     o = torch.empty_like(v)
