@@ -27,7 +27,7 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 // holds at most 16 result tiles: up to D = 64 every wave covers the whole matrix and the waves take the
 // tokens of a tile in turn (summed through LDS at the end); at D = 128 each wave owns two tile rows.
 template <int D, typename IO>
-__global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double* G) {
+__global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(ForwardArgs a, double* G) {
   constexpr int NTI = D / 16;                                // tiles per side
   constexpr int TR = NTI * NTI <= 16 ? NTI : 16 / NTI;       // tile rows per wave
   constexpr int RGW = NTI / TR;                              // waves across the rows
@@ -38,8 +38,12 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
   constexpr int EPT = TT * D / kThreads;                     // elements of the tile each thread stages
   constexpr int TPR = D / EPT;                               // threads per token row (8)
   static_assert(RGW * NGW * 64 == kThreads && KS % NGW == 0 && TPR == 8, "layout");
+  // The sum of k^ k^T is symmetric: where a wave covers the whole matrix it forms the tiles on and above the
+  // diagonal only (10 of 16 at d = 64).
+  constexpr bool SYM = RGW == 1;
   __shared__ double ktb[2][TT * LDK];   // double-buffered: one barrier per tile
-  __shared__ double red[NGW > 1 ? D * D : 1];
+  static_assert(NGW == 1 || 2 * TT * LDK >= D * D, "the final sum over the waves reuses the tile buffers");
+  double* const red = &ktb[0][0];
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
@@ -107,7 +111,7 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
       for (int i = 0; i < TR; ++i) {
         const double av = RGW == 1 ? bv[i] : row[16 * (rgw * TR + i)];
 #pragma unroll
-        for (int j = 0; j < NTI; ++j)
+        for (int j = (SYM ? i : 0); j < NTI; ++j)   // SYM: tiles below the diagonal are mirrored at the end
           acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[j], acc[i][j], 0, 0, 0);
       }
     }
@@ -137,16 +141,21 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
 #pragma unroll
     for (int i = 0; i < TR; ++i)
 #pragma unroll
-      for (int j = 0; j < NTI; ++j)
+      for (int j = (SYM ? i : 0); j < NTI; ++j)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) Gh[(16 * (rgw * TR + i) + g + 4 * r) * D + 16 * j + c] = acc[i][j][r];
+        for (int r = 0; r < 4; ++r) {
+          const int row = 16 * (rgw * TR + i) + g + 4 * r, col = 16 * j + c;
+          Gh[row * D + col] = acc[i][j][r];
+          if (SYM && j > i) Gh[col * D + row] = acc[i][j][r];
+        }
   } else {
+    __syncthreads();   // every wave is done with the tile buffers
     for (int gi = 0; gi < NGW; ++gi) {
       if (tgrp == gi) {
 #pragma unroll
         for (int i = 0; i < TR; ++i)
 #pragma unroll
-          for (int j = 0; j < NTI; ++j)
+          for (int j = (SYM ? i : 0); j < NTI; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const int o = (16 * (rgw * TR + i) + g + 4 * r) * D + 16 * j + c;
@@ -155,7 +164,10 @@ __global__ void __launch_bounds__(kThreads, 2) gram_kernel(ForwardArgs a, double
       }
       __syncthreads();
     }
-    for (int o = tid; o < D * D; o += kThreads) Gh[o] = red[o];
+    for (int o = tid; o < D * D; o += kThreads) {
+      const int row = o / D, col = o - row * D;
+      Gh[o] = (SYM && row / 16 > col / 16) ? red[col * D + row] : red[o];   // tile below the diagonal: mirror
+    }
   }
 }
 
