@@ -44,11 +44,10 @@ extern "C" {
 typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 
 /* Which kernel family runs the recurrence.
- *   AUTO     : the library picks: CHUNKED when an option of Algorithm 1 other than feature_map is
- *              switched on or the shape has no segment kernels; else TIME_PARALLEL for few heads
- *              (B*H <= 64 at d = 128, 128 at d = 64, 256 at d = 32) and T >= 1024 (T >= 512 for half as
- *              many heads) if the caller passed the workspace vla_forward_workspace_bytes() asks for
- *              (else CHUNKED); CHUNKED otherwise.
+ *   AUTO     : the library picks: CHUNKED when the identity refresh is switched on or the shape has no
+ *              segment kernels; else TIME_PARALLEL for few heads (B*H <= 64 at d = 128, 128 at d = 64,
+ *              256 at d = 32) and T >= 1024 (T >= 512 for half as many heads) if the caller passed the
+ *              workspace vla_forward_workspace_bytes() asks for (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
  *              resident in registers (FP32 vector ALU).
  *   CHUNKED  : tokens are processed in blocks; the block form of the same
@@ -60,11 +59,13 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
  *              over several workgroups (for small B*H).  Allowed because A never
  *              reads S (eq. (sm)); Algorithm 2 takes k^, alpha^ as given inputs.
  *   TIME_PARALLEL: TWO_PHASE with the sequence cut into segments that run concurrently (for small
- *              B*H and long T).  With u = k^ and no refresh, A at a segment boundary is the explicit
- *              inverse (A_0^{-1} + sum of k^ k^T up to there)^{-1} of Section 3.2, computed in float64
- *              from one Gram matrix per segment; S at a boundary follows by composing the per-segment
- *              affine maps S -> S P + Q of eq. (s-update).  Inside a segment the recurrence is the
- *              same exact block form.  Same result up to float32 rounding.
+ *              B*H and long T).  Without the refresh, A at a segment boundary is the explicit
+ *              inverse (A_0^{-1} + sum of u u^T up to there)^{-1} of Section 3.2 / eq. (penalty) (u = k^
+ *              unless opts->u is given), computed in float64 from one Gram matrix per segment; S at a
+ *              boundary follows by composing the per-segment affine maps S -> S P + Q of
+ *              eq. (s-update); the key sum of the normalised read-out at a boundary is a prefix sum.
+ *              Inside a segment the recurrence is the same exact block form.  Same result up to float32
+ *              rounding.
  */
 typedef enum {
   VLA_MODE_AUTO = 0,
@@ -86,9 +87,10 @@ typedef enum {
  * vla_default_opts() and then change fields: later library versions may append fields.
  *
  * The fields after `mode` switch on the remaining lines of Algorithm 1 (paper, pseudocode appendix).
- * With any of them except feature_map set, the SCAN and CHUNKED kernel families apply (AUTO selects
- * CHUNKED where the head size has a block kernel; asking for TWO_PHASE or TIME_PARALLEL returns
- * VLA_ERR_UNSUPPORTED).  feature_map on its own is carried by every mode and changes no routing. */
+ * SCAN and CHUNKED carry all of them; TWO_PHASE and TIME_PARALLEL carry all but the identity refresh
+ * (asking for them with refresh_period > 0 returns VLA_ERR_UNSUPPORTED, and AUTO then selects CHUNKED): with
+ * the refresh A_t is no longer the inverse of a prefix sum, which the segment boundaries rest on.
+ * feature_map on its own changes no routing. */
 typedef struct vla_opts {
   float lambda0; /* [0.1]  A_0 = I / lambda0, used only when A0 == NULL (Section 3.2) */
   float eps;     /* [1e-4] floor of every denominator: ||k||, delta, ||A k^||, ||u|| and the

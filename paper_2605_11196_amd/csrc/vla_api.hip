@@ -118,8 +118,12 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
   if (d != d_v) return needs_general_kernel(o) ? VLA_MODE_SCAN : VLA_MODE_CHUNKED;   // rectangular heads
-  if (needs_general_kernel(o)) return vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
-  if (!vla::block_family_supported(d)) return VLA_MODE_CHUNKED;   // d = 16, 96: no segment modes
+  const int with_options = vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
+  // the identity refresh breaks A_t = M_t^{-1}, which the segment boundaries rest on
+  if (o.refresh_period > 0) return with_options;
+  if (!vla::block_family_supported(d)) {   // d = 16, 96: no segment modes
+    return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
+  }
   const long long heads = static_cast<long long>(B) * H;
   // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
   // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0), 256 heads at d = 32 (2.7 against
@@ -127,7 +131,8 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   const long long few = d >= 128 ? 64 : (d >= 64 ? 128 : 256);
   // short sequences: 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads 0.19 against 0.17
   const bool long_enough = T >= 1024 || (T >= 512 && 2 * heads <= few);
-  return (heads <= few && long_enough) ? VLA_MODE_TIME_PARALLEL : VLA_MODE_CHUNKED;
+  if (heads <= few && long_enough) return VLA_MODE_TIME_PARALLEL;
+  return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
 }
 
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
@@ -135,9 +140,10 @@ bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   if (!vla::chunk_supported(d, d_v)) return false;
   if (d != d_v) return mode == VLA_MODE_CHUNKED && !needs_general_kernel(o);   // the plain block kernel only
   if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::general_block_supported(d);
-  // the segment modes carry the feature map, no other option
+  // the segment modes carry every option but the identity refresh (A at a segment boundary is the explicit
+  // inverse of a prefix sum only without it)
   if (mode == VLA_MODE_TWO_PHASE || mode == VLA_MODE_TIME_PARALLEL) {
-    return !needs_general_kernel(o) && vla::block_family_supported(d);
+    return o.refresh_period == 0 && vla::block_family_supported(d);
   }
   return false;
 }

@@ -59,7 +59,11 @@ enum GramTile {
 };
 
 // FULL: Y and X differ (a separate u, or a refresh period): two sweeps of A and five Gram matrices.
-template <int D, typename IO, bool FULL>
+// SCAN: phase 1 of the two-phase and time-parallel modes: one workgroup per (head, time segment) runs the A
+//       chain only, from the A the segment starts with, and writes what the S recurrence needs into the
+//       workspace (the layout of vla_mfma_util.h: 1 / ||k_t||, the write directions alpha_t in W's place, Z,
+//       -NQ^T, -c_t and the reciprocal read-out denominators); S, v and o are not touched.
+template <int D, typename IO, bool FULL, bool SCAN>
 __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
   constexpr int NB = D / 16;       // 16-row blocks over the head dimension
@@ -96,13 +100,15 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   __shared__ __align__(16) float zks[D];              // running key sum (each wave touches its own columns)
   __shared__ __align__(16) float ens[2][C + 4];       // eta n_i, i = 0..C: refresh steps among a block's first i tokens
 
-  const int head = blockIdx.x;
+  const int head = SCAN ? blockIdx.x / a.n_seg : blockIdx.x;
+  const int seg = SCAN ? blockIdx.x - head * a.n_seg : 0;
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
-  const int T = a.T;
+  const int tb = SCAN ? seg * a.seg_blocks * C : 0;                 // first token of this workgroup's range
+  const int T = SCAN ? min(a.T, tb + a.seg_blocks * C) : a.T;       // one past its last token
   const float eps = a.eps;
   const int col0 = 16 * w;
   const int period = a.refresh_period;
@@ -117,8 +123,9 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
   // ---- resident state: At[b][r] = A[16b + 4g + r][col0 + c],  St[b][r] = S[col0 + c][16b + 4g + r]
   f4 At[NB], St[NB];
   {
-    const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
-    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* A0 = (SCAN && a.seg_A) ? a.seg_A + static_cast<size_t>(blockIdx.x) * D * D
+                                        : (a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr);
+    const float* S0 = (!SCAN && a.S0) ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
     const float diag = 1.0f / a.lambda0;
     const int arc = (4 * g) * D + col0 + c;
     const int src = (col0 + c) * D + 4 * g;
@@ -139,9 +146,19 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       }
     }
   }
-  if (lane < 16) zks[col0 + lane] = a.zkey0 ? a.zkey0[static_cast<size_t>(head) * D + col0 + lane] : 0.0f;
+  if (lane < 16) {   // key sum entering this range: the caller's, or the one the segment starts with
+    const float* z0 = (SCAN && a.seg_zkey) ? a.seg_zkey + static_cast<size_t>(blockIdx.x) * D
+                                           : (a.zkey0 ? a.zkey0 + static_cast<size_t>(head) * D : nullptr);
+    zks[col0 + lane] = z0 ? z0[col0 + lane] : 0.0f;
+  }
+  // workspace records of this head (SCAN)
+  const int nblk_all = (a.T + C - 1) / C;
+  float* wsh = SCAN ? a.ws + static_cast<size_t>(head) * head_stride(nblk_all, D) : nullptr;
+  float* RN = SCAN ? wsh + off_rn(nblk_all, D) : nullptr;
+  float* WT = SCAN ? wsh + off_wt(nblk_all, D) : nullptr;
+  float* SMp = SCAN ? wsh + off_sm(nblk_all, D) : nullptr;
 
-  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const IO* vh = static_cast<const IO*>(a.v) + slab;
@@ -186,9 +203,9 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     const float rn = __builtin_amdgcn_rsqf(clamped);
     return rn * fmaf(-0.5f * clamped * rn, rn, 1.5f);
   };
-  // this thread's share of a block of `len` live tokens whose first token has step index idx0 (1-based, counted
-  // over the whole sequence): K^, Q (and U) into LDS half `buf`, and the refresh counts of the block
-  auto stage = [&](int len, int idx0, int buf) {
+  // this thread's share of the block of `len` live tokens that starts at token tfirst (step index idx0, 1-based,
+  // counted over the whole sequence): K^, Q (and U) into LDS half `buf`, and the refresh counts of the block
+  auto stage = [&](int len, int idx0, int buf, int tfirst) {
     if (!stage_wave) return;
     const bool live = srow < len && stager;
     float x[EPT], kn[EPT];
@@ -238,7 +255,10 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     for (int e = 0; e < EPT; e += 4) {
       *reinterpret_cast<f4*>(&Ksb[buf][srow * LD + sseg + e]) = f4{kn[e], kn[e + 1], kn[e + 2], kn[e + 3]};
     }
-    if (sseg == 0) nks[buf][srow] = sm * rn;  // max(||k||, eps)
+    if (sseg == 0) {
+      nks[buf][srow] = sm * rn;  // max(||k||, eps)
+      if constexpr (SCAN) RN[tfirst + srow] = live ? rn : 0.0f;   // rows past the end: zero keys
+    }
     qpre.unpack(x);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
@@ -259,16 +279,16 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     }
   };
 
-  if (T > 0) {
-    load_kqu(0);
-    load_v(0);
-    stage(T < C ? T : C, a.step_offset + 1, 0);
-    if (C < T) load_kqu(C);
+  if (tb < T) {
+    load_kqu(tb);
+    if constexpr (!SCAN) load_v(tb);
+    stage(T - tb < C ? T - tb : C, a.step_offset + tb + 1, 0, tb);
+    if (tb + C < T) load_kqu(tb + C);
   }
-  __syncthreads();  // block 0 staged, zks initialised
+  __syncthreads();  // first block staged, zks initialised
 
   int blk = 0;
-  for (int t0 = 0; t0 < T; t0 += C, ++blk) {
+  for (int t0 = tb; t0 < T; t0 += C, ++blk) {
     const float* Ks = Ksb[blk & 1];
     const float* Qs = Qsb[blk & 1];
     const float* en = ens[blk & 1];
@@ -277,17 +297,19 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     const int tn = t0 + C;                           // start of the next block
     auto stage_next = [&]() {
       if (tn < T) {
-        stage(T - tn < C ? T - tn : C, a.step_offset + tn + 1, (blk + 1) & 1);
+        stage(T - tn < C ? T - tn : C, a.step_offset + tn + 1, (blk + 1) & 1, tn);
         if (tn + C < T) load_kqu(tn + C);
       }
     };
     int cc = c;  // opaque copy: keeps lane-dependent masks from being hoisted out of the loop
     asm volatile("" : "+v"(cc));
 
-    f4 ft;  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+    f4 ft = f4{0, 0, 0, 0};  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+    if constexpr (!SCAN) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) ft[r] = (4 * g + r < len) ? neg_widen(vpre[r]) : 0.0f;
-    if (tn < T) load_v(tn);
+      for (int r = 0; r < 4; ++r) ft[r] = (4 * g + r < len) ? neg_widen(vpre[r]) : 0.0f;
+      if (tn < T) load_v(tn);
+    }
 
     // ================= Y^T = U A0, X^T = K^ A0 (this wave's columns) -> LDS;  -F^T = K^ S0^T - V^T
     f4 yt = f4{0, 0, 0, 0}, xt = f4{0, 0, 0, 0};
@@ -304,8 +326,10 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) yt = mfma16(ka[r], At[b][r], yt);
       }
+      if constexpr (!SCAN) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], St[b][r], ft);
+        for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], St[b][r], ft);
+      }
     }
     if constexpr (FULL) {
       if (period > 0) {  // y'_t = y_t + eta n_t u_t,  x'_t = x_t + eta n'_t k^_t  (n'_t = n_{t+1})
@@ -376,7 +400,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       }
     };
     if (w != sw) {
-      r_pass();
+      if constexpr (!SCAN) r_pass();
       stage_next();
     } else {
       // Lanes 0-31 hold rows of I + G (-> rows of L), lanes 32-63 columns of the identity (-> columns of
@@ -437,7 +461,11 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
-      *reinterpret_cast<f4*>(&Ab[(col0 + c) * LT + 4 * g]) = at;
+      if constexpr (SCAN) {
+        *reinterpret_cast<f4*>(WT + (static_cast<size_t>(t0 / C) * D + col0 + c) * C + 4 * g) = at;
+      } else {
+        *reinterpret_cast<f4*>(&Ab[(col0 + c) * LT + 4 * g]) = at;
+      }
     }
     __syncthreads();  // (4) W, Alpha and the norm partials visible
 
@@ -467,7 +495,11 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
       const float cs = __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(wn2), eps));  // alpha^_t = c_t alpha_t
-      if (g == 0) cvec[c] = -cs;
+      float* smb = SCAN ? SMp + static_cast<size_t>(t0 / C) * SMB : nullptr;   // this block's record
+      if (g == 0) {
+        if constexpr (SCAN) smb[2 * C * C + c] = -cs;
+        else cvec[c] = -cs;
+      }
       // P and AQ in accumulator layout [s = 4g + r][t = c]
       f4 pt, aq;
       f4 nhq = f4{0, 0, 0, 0};
@@ -499,14 +531,20 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
       z_rows<0>(nm, Zr, cc);
       if (g == 0) {
 #pragma unroll
-        for (int t = 0; t < C; ++t) Zs[t * LT + c] = Zr[t];
+        for (int t = 0; t < C; ++t) {
+          if constexpr (SCAN) smb[t * C + c] = Zr[t];
+          else Zs[t * LT + c] = Zr[t];
+        }
       }
+      f4 nq;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int s = 4 * g + r;
         const float csr = __shfl(cs, s);
-        NQs[c * LT + s] = (s <= c) ? -(csr * aq[r]) : 0.0f;
+        nq[r] = (s <= c) ? -(csr * aq[r]) : 0.0f;
+        if constexpr (!SCAN) NQs[c * LT + s] = nq[r];
       }
+      if constexpr (SCAN) *reinterpret_cast<f4*>(smb + C * C + c * C + 4 * g) = nq;  // -NQ^T[t = c][s = 4g + r]
       if (norm_out) {  // q_t . zkey_t for t = 4g + r: key-sum part + in-block part over s = c <= t
         const float nk = nks[blk & 1][c];
         f4 den;
@@ -518,12 +556,16 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) den[r] = 1.0f / fmaxf(den[r], eps);
-        if (c == 0) *reinterpret_cast<f4*>(&rdens[4 * g]) = den;
+        if (c == 0) {
+          if constexpr (SCAN) *reinterpret_cast<f4*>(smb + 2 * C * C + C + 4 * g) = den;
+          else *reinterpret_cast<f4*>(&rdens[4 * g]) = den;
+        }
       }
     }
-    __syncthreads();  // (5) Z, NQ, c, denominators visible
+    __syncthreads();  // (5) Z, NQ, c, denominators visible; the next block is staged in full
 
     // ================= -E^T = Z (-F^T), O^T = Q S0^T + (-NQ^T)(-E^T), store o;  ce = diag(c) E^T
+    if constexpr (!SCAN) {
     f4 ce;
     {
       const f4 za = lds4(&Zs[c * LT + 4 * g]);
@@ -549,6 +591,7 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) St[b] = mfma16(aa[r], ce[r], St[b]);
     }
+    }  // !SCAN
     if (w == sw2) update_A();
     if (key_sum && lane < 16) {  // zkey += sum over the block's tokens of ||k_s|| k^_s, this wave's columns
       float zk = zks[col0 + lane];
@@ -558,10 +601,10 @@ __global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
     }
   }
 
-  // ---- final state
-  {
+  // ---- final state (SCAN: A and the key sum after the last segment; S belongs to phase 2)
+  if (!SCAN || seg == a.n_seg - 1) {
     float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
-    float* ST = a.S_T ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+    float* ST = (!SCAN && a.S_T) ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
     const int arc = (4 * g) * D + col0 + c;
     const int src = (col0 + c) * D + 4 * g;
 #pragma unroll
@@ -585,9 +628,21 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
   const bool full = a.u != nullptr || a.refresh_period > 0;
-  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true>)
-                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false>);
+  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true, false>)
+                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false, false>);
   return hipLaunchKernel(fn, dim3(a.n_heads), dim3(4 * D), params, 0, stream);
+}
+// phase 1 of the two-phase and time-parallel modes with options: one workgroup per (head, segment)
+template <int D, typename IO>
+hipError_t launch_scan(const ForwardArgs& a, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args};
+  const bool full = a.u != nullptr || a.refresh_period > 0;
+  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true, true>)
+                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false, true>);
+  const long long wgs = static_cast<long long>(a.n_heads) * a.n_seg;
+  if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+  return hipLaunchKernel(fn, dim3(static_cast<unsigned>(wgs)), dim3(4 * D), params, 0, stream);
 }
 
 }  // namespace
@@ -600,6 +655,16 @@ hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipSt
     case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
     case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);
     case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 32: return bf ? launch_scan<32, uint16_t>(a, stream) : launch_scan<32, float>(a, stream);
+    case 64: return bf ? launch_scan<64, uint16_t>(a, stream) : launch_scan<64, float>(a, stream);
+    case 128: return bf ? launch_scan<128, uint16_t>(a, stream) : launch_scan<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }

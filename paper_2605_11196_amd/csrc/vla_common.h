@@ -36,6 +36,7 @@ struct ForwardArgs {
   const float* seg_A = nullptr;   // [n_heads][n_seg][d][d]  A at the start of every segment
   const float* seg_S = nullptr;   // [n_heads][n_seg][d][d]  S at the start of every segment
   float* seg_PQ = nullptr;        // [n_heads][n_seg][2][d][d]  per-segment affine map of the S recurrence
+  const float* seg_zkey = nullptr;  // [n_heads][n_seg][d]  key sum at the start of every segment (normalised read-out)
 };
 
 // bf16 <-> f32 helpers on raw bit patterns (bf16 is the upper half of an IEEE float32).
@@ -70,6 +71,9 @@ hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hip
 // Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); every head size.
 inline bool general_block_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+// Its A chain alone, one workgroup per (head, time segment), writing the workspace records of the two-phase and
+// time-parallel modes (head sizes 32, 64, 128).
+hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 
 // Two-phase split (vla_two_phase.hip): A recurrence first, then the rows of S on many workgroups.
@@ -87,12 +91,17 @@ size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_se
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream);
 // Boundary kernels (vla_segments.hip).  All buffers are device memory inside the caller's workspace.
-//   gram:      G[h][s] = sum over the tokens of segments 0..s of k^ k^T, float64 [d][d]
+//   gram:      G[h][s] = sum over the tokens of segments 0..s of u u^T (u = k^ unless the caller supplies
+//              penalty directions), float64 [d][d]
 //   boundary:  seg_A[h][s] = inverse(inverse(A0[h]) + G[h][s-1]) rounded to float32
 //   combine:   seg_S[h][0] = S0[h];  seg_S[h][s+1] = seg_S[h][s] P[h][s] + Q[h][s]
 hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hipStream_t stream);
 hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* seg_A, hipStream_t stream);
 hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t stream);
+//   key sums:  seg_zkey[h][s] = zkey0[h] + sum of the keys (after the feature map) of every token before segment s;
+//              `part` [n_heads][n_seg][d] float64 is scratch
+hipError_t launch_keysum(const ForwardArgs& a, int d, int io_dtype, double* part, float* seg_zkey,
+                         hipStream_t stream);
 
 
 // One decode step for every head, state updated in place (vla_decode.hip).  `opt` carries eps and the

@@ -10,6 +10,20 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int C = 16;       // tokens per block
 constexpr int LT = C + 4;   // row stride (floats) of the 16-column LDS arrays: conflict-free b128 rows
 
+// Workspace of the two-phase and time-parallel modes, per head and 16-token block (floats):
+//   RN  [16]       1 / max(||k_t||, eps) per token, 0 for rows past the end (k^_t = k_t * RN[t])
+//   WT  [D][16]    the write directions before their scaling by c_t (w_t; alpha_t with a separate u)
+//   SM  [544]      Z [16][16] | -NQ^T [16][16] | -c_t [16] | 1 / max(q_t . zkey_t, eps) [16] (normalised
+//                  read-out only)
+// each as one array over all blocks of the head.
+constexpr int SMB = 2 * C * C + 2 * C;
+__host__ __device__ constexpr size_t head_stride(int nblk, int D) {
+  return static_cast<size_t>(nblk) * (C + C * D + SMB);
+}
+__host__ __device__ constexpr size_t off_rn(int /*nblk*/, int /*D*/) { return 0; }
+__host__ __device__ constexpr size_t off_wt(int nblk, int /*D*/) { return static_cast<size_t>(nblk) * C; }
+__host__ __device__ constexpr size_t off_sm(int nblk, int D) { return static_cast<size_t>(nblk) * (C + C * D); }
+
 __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }

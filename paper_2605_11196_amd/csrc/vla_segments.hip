@@ -1,11 +1,12 @@
 // State at the boundaries of time segments, for the time-parallel mode.
 //
-// With u_t = k^_t the inverse penalty matrix is an explicit inverse (paper Section 3.2, eq. (sm) is the
-// Sherman-Morrison form of it):  A_t = (A_0^{-1} + sum_{s<=t} k^_s k^_s^T)^{-1}.  The sum is a plain prefix sum,
-// so A at the start of every segment follows from one Gram matrix per segment and one d x d inversion, all
+// Without the identity refresh the inverse penalty matrix is an explicit inverse (paper Section 3.2 and
+// eq. (penalty); eq. (sm) is the Sherman-Morrison form of it):  A_t = (A_0^{-1} + sum_{s<=t} u_s u_s^T)^{-1}, with
+// u_s = k^_s by default or the caller's penalty directions, normalised and scaled.  The sum is a plain prefix
+// sum, so A at the start of every segment follows from one Gram matrix per segment and one d x d inversion, all
 // independent of each other; the segments then run the exact rank-1 recurrence concurrently.  The paper
-// treats the A loop as sequential (Section 3.4); this goes beyond it and is only valid without the identity
-// refresh and with u = k^.  Everything here is float64 so that the boundary matrices are at least as accurate
+// treats the A loop as sequential (Section 3.4); this goes beyond it and is not valid with the identity
+// refresh.  Everything here is float64 so that the boundary matrices are at least as accurate
 // as the float32 chain they replace (a product of two float32 numbers is exact in float64).
 //
 // The S recurrence is affine in S (eq. (s-update)): S_end = S_start P + Q per segment.  P and Q come from the
@@ -57,8 +58,11 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   const int tgrp = w / RGW;     // which k-steps
   const int tb = seg * a.seg_blocks * C;
   const int te = min(a.T, tb + a.seg_blocks * C);
-  const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
+  // the directions the penalty matrix accumulates: the caller's u (scaled after normalisation), else the keys
+  const bool has_u = a.u != nullptr;
+  const IO* kh = static_cast<const IO*>(has_u ? a.u : a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const double eps = static_cast<double>(a.eps);
+  const double scale = has_u ? static_cast<double>(a.u_scale) : 1.0;
   const int srow = tid / TPR;
   const int scol = (tid % TPR) * EPT;
 
@@ -82,7 +86,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     const int t = t0 + srow;
     double x[EPT];
     o.unpack(x);
-    if (a.feature_map) {   // ELU(x) + 1 in float32, as the kernels that run the recurrence apply it
+    if (a.feature_map && !has_u) {   // ELU(x) + 1 on keys, in float32, as the kernels that run the recurrence apply it
 #pragma unroll
       for (int e = 0; e < EPT; ++e) x[e] = static_cast<double>(elu_plus_one(static_cast<float>(x[e])));
     }
@@ -96,7 +100,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
     const double y = static_cast<double>(__builtin_amdgcn_rsqf(static_cast<float>(ss)));
     const double yn = y * fma(-0.5 * ss * y, y, 1.5);
-    const double rn = ss > eps * eps ? yn : 1.0 / eps;
+    const double rn = (ss > eps * eps ? yn : 1.0 / eps) * scale;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) kt[srow * LDK + scol + e] = x[e] * rn;
   };
@@ -183,6 +187,50 @@ __global__ void __launch_bounds__(kThreads) gram_prefix_kernel(double* G, int n_
   for (int s = 0; s + 1 < n_seg; ++s) {
     run += p[static_cast<size_t>(s) * dd];
     p[static_cast<size_t>(s) * dd] = run;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ key sums
+// Normalised read-out (eq. (output)): zkey_t = zkey_0 + sum_{s<=t} k_s with k_s the key as used before its L2
+// normalisation (after the feature map).  Per (head, segment) the sum of its keys, in float64; thread (rg, j)
+// adds column j of every RG-th token.
+template <int D, typename IO>
+__global__ void __launch_bounds__(D * (256 / D)) keysum_kernel(ForwardArgs a, double* part) {
+  constexpr int RG = 256 / D;
+  __shared__ double red[RG][D];
+  const int head = blockIdx.x / a.n_seg;
+  const int seg = blockIdx.x - head * a.n_seg;
+  const int j = threadIdx.x % D;
+  const int rg = threadIdx.x / D;
+  const int tb = seg * a.seg_blocks * C;
+  const int te = min(a.T, tb + a.seg_blocks * C);
+  const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
+  double sum = 0.0;
+  for (int t = tb + rg; t < te; t += RG) {
+    float x = widen(kh[static_cast<size_t>(t) * D + j]);
+    if (a.feature_map) x = elu_plus_one(x);
+    sum += static_cast<double>(x);
+  }
+  red[rg][j] = sum;
+  __syncthreads();
+  if (rg == 0) {
+#pragma unroll
+    for (int r = 1; r < RG; ++r) sum += red[r][j];
+    part[static_cast<size_t>(blockIdx.x) * D + j] = sum;
+  }
+}
+// seg_zkey[h][s] = zkey0[h] + the sums of the segments before s, one thread per (head, column)
+__global__ void __launch_bounds__(kThreads) keysum_prefix_kernel(const double* part, const float* zkey0,
+                                                                 float* seg_zkey, int n_heads, int n_seg, int d) {
+  const long long e = static_cast<long long>(blockIdx.x) * kThreads + threadIdx.x;
+  if (e >= static_cast<long long>(n_heads) * d) return;
+  const int head = static_cast<int>(e / d);
+  const int j = static_cast<int>(e - static_cast<long long>(head) * d);
+  double run = zkey0 ? static_cast<double>(zkey0[e]) : 0.0;
+  for (int s = 0; s < n_seg; ++s) {
+    const size_t o = (static_cast<size_t>(head) * n_seg + s) * d + j;
+    seg_zkey[o] = static_cast<float>(run);
+    run += part[o];
   }
 }
 
@@ -396,6 +444,39 @@ hipError_t launch_combine_d(const ForwardArgs& a, float* seg_S, hipStream_t stre
 }
 
 }  // namespace
+
+namespace {
+template <int D, typename IO>
+hipError_t launch_keysum_d(const ForwardArgs& a, double* part, float* seg_zkey, hipStream_t stream) {
+  ForwardArgs args = a;
+  void* params[] = {&args, &part};
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&keysum_kernel<D, IO>),
+                                   dim3(a.n_heads * a.n_seg), dim3(D * (256 / D)), params, 0, stream);
+  if (err != hipSuccess) return err;
+  const double* cpart = part;
+  const float* z0 = a.zkey0;
+  int nh = a.n_heads, ns = a.n_seg, d = D;
+  void* p2[] = {&cpart, &z0, &seg_zkey, &nh, &ns, &d};
+  const long long elems = static_cast<long long>(nh) * d;
+  return hipLaunchKernel(reinterpret_cast<const void*>(&keysum_prefix_kernel),
+                         dim3(static_cast<unsigned>((elems + kThreads - 1) / kThreads)), dim3(kThreads), p2, 0,
+                         stream);
+}
+}  // namespace
+
+hipError_t launch_keysum(const ForwardArgs& a, int d, int io_dtype, double* part, float* seg_zkey,
+                         hipStream_t stream) {
+  const bool bf = io_dtype == 1;
+  switch (d) {
+    case 32: return bf ? launch_keysum_d<32, uint16_t>(a, part, seg_zkey, stream)
+                       : launch_keysum_d<32, float>(a, part, seg_zkey, stream);
+    case 64: return bf ? launch_keysum_d<64, uint16_t>(a, part, seg_zkey, stream)
+                       : launch_keysum_d<64, float>(a, part, seg_zkey, stream);
+    case 128: return bf ? launch_keysum_d<128, uint16_t>(a, part, seg_zkey, stream)
+                        : launch_keysum_d<128, float>(a, part, seg_zkey, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hipStream_t stream) {
   const bool bf = io_dtype == 1;

@@ -7,7 +7,8 @@
 //   RN  [16]         1 / max(||k_t||, eps) per token (0 for rows past the end): the S recurrence re-forms
 //                    k^_t = k_t * RN[t] from the raw keys, so the normalised keys never travel through memory
 //   W   [D][16]      w_t = z_t / sqrt(delta_t), tokens contiguous
-//   SM  [528]        Z | -NQ^T | -c_t  (two 16x16 row-major matrices and a vector of 16)
+//   SM  [544]        Z | -NQ^T | -c_t | 1 / max(q_t . zkey_t, eps)  (two 16x16 row-major matrices and two vectors of
+//                    16; the last one only with the normalised read-out)
 //
 //   phase 1 (a_scan_kernel):  one workgroup per head, the A chain of the block form; the C x C work the S
 //                             recurrence needs (c_t, Z, NQ) is done one block behind by a wave that would
@@ -24,16 +25,6 @@
 
 namespace vla {
 namespace {
-
-constexpr int SMB = 2 * C * C + C;  // floats of small matrices per (head, block)
-
-__host__ __device__ constexpr size_t head_stride(int nblk, int D) {
-  return static_cast<size_t>(nblk) * (C + C * D + SMB);
-}
-// sub-array offsets inside one head's workspace (floats)
-__host__ __device__ constexpr size_t off_rn(int /*nblk*/, int /*D*/) { return 0; }
-__host__ __device__ constexpr size_t off_wt(int nblk, int /*D*/) { return static_cast<size_t>(nblk) * C; }
-__host__ __device__ constexpr size_t off_sm(int nblk, int D) { return static_cast<size_t>(nblk) * (C + C * D); }
 
 // ------------------------------------------------------------------------------------------ phase 1
 // Two-wave workgroups (d <= 64) are compiled for three waves per SIMD.
@@ -383,6 +374,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are consumed
+  const bool norm_out = a.normalise_output != 0;   // o_t is divided by max(q_t . zkey_t, eps)
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -406,6 +398,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     RawRow<IO, 4> ka[NB], qa[NB];
     float rn;           // 1 / max(||k||, eps) of token row c (0 past the end)
     f4 za, nqa, ncg;
+    f4 rd;              // 1 / max(q_t . zkey_t, eps) for t = 4g + r (normalised read-out only)
     IO v[4];
   };
   // Addresses are a per-block uniform base (scalar registers) plus lane-constant 32-bit offsets, so that a
@@ -430,6 +423,9 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     o.za = *reinterpret_cast<const f4*>(sp + wo);
     if constexpr (!MAP) o.nqa = *reinterpret_cast<const f4*>(sp + C * C + wo);
     o.ncg = *reinterpret_cast<const f4*>(sp + 2 * C * C + 4 * g);
+    if constexpr (!MAP) {
+      if (norm_out) o.rd = *reinterpret_cast<const f4*>(sp + 2 * C * C + C + 4 * g);
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       o.v[r] = vb[static_cast<unsigned>(min(4 * g + r, lim) * D + row0 + c)];
@@ -472,6 +468,7 @@ __global__ void __launch_bounds__(64) s_rows_kernel(ForwardArgs a) {
     if constexpr (!MAP) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(cur.nqa[r], et[r], ot);
+      if (norm_out) ot *= cur.rd;
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
         io_store2(ob + vo, ob + vo + D, ot[0], ot[1]);
         io_store2(ob + vo + 2 * D, ob + vo + 3 * D, ot[2], ot[3]);
@@ -567,6 +564,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     float Zs[C * LT];      // Z  [t][s]
     float NQs[C * LT];     // -NQ^T [t][s]
     float cv[C];           // -c_t
+    float rd[C];           // 1 / max(q_t . zkey_t, eps) (normalised read-out only)
   };
   __shared__ __align__(16) Stage stg[NST];
 
@@ -594,6 +592,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are consumed
+  const bool norm_out = a.normalise_output != 0;   // o_t is divided by max(q_t . zkey_t, eps)
   const IO* vh = static_cast<const IO*>(a.v) + slab;
   IO* oh = static_cast<IO*>(a.o) + slab;
 
@@ -624,7 +623,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const bool do_sm = tid < (MAP ? 64 : 128);   // Z on threads 0-63, -NQ^T on 64-127 (not in the map pass)
   const bool do_c = tid < 4;                   // -c
   struct Regs {
-    f4 wx, sx, cx;
+    f4 wx, sx, cx, rdx;
     RawRow<IO, 4> kx, qx;
     float krn;          // 1 / max(||k||, eps) of token row krow (0 past the end)
     IO v[4];
@@ -638,7 +637,11 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     }
     if (do_w) r.wx = *reinterpret_cast<const f4*>(WT + static_cast<size_t>(blk) * (D * C) + wrow * C + wcol);
     if (do_sm) r.sx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + sm_src);
-    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
+    if (do_c) {
+      r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
+      if (!MAP && norm_out)
+        r.rdx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + C + 4 * tid);
+    }
     if constexpr (!MAP) r.qx.load(qh + kq);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -660,7 +663,10 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       if (tid < 64) *reinterpret_cast<f4*>(&s.Zs[(tid / 4) * LT + 4 * (tid % 4)]) = r.sx;
       else *reinterpret_cast<f4*>(&s.NQs[((tid - 64) / 4) * LT + 4 * (tid % 4)]) = r.sx;
     }
-    if (do_c) *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
+    if (do_c) {
+      *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
+      if (!MAP && norm_out) *reinterpret_cast<f4*>(&s.rd[4 * tid]) = r.rdx;
+    }
     if constexpr (!MAP) {
       float x[4];
       r.qx.unpack(x);
@@ -695,6 +701,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       const f4 nqa = lds4(&s.NQs[c * LT + 4 * g]);
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+      if (norm_out) ot *= lds4(&s.rd[4 * g]);
       IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
         io_store2(ob, ob + D, ot[0], ot[1]);
@@ -782,9 +789,12 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   void* params[] = {&args};
   const long long hs = static_cast<long long>(a.n_heads) * a.n_seg;
   if (hs * (D / 8) > 0x7fffffffLL) return hipErrorInvalidValue;   // the largest grid below: 2 D/16 waves per pair
-  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
-                                   dim3(static_cast<unsigned>(hs)),
-                                   dim3(64 * NW), params, 0, stream);
+  // A separate penalty direction or the normalised read-out: the A chain of the block kernel that carries
+  // them; its records have the layout the S-row kernels below read.
+  const bool general = a.u != nullptr || a.normalise_output != 0 || a.zkey0 != nullptr || a.zkey_T != nullptr;
+  hipError_t err = general ? launch_a_scan_general(a, D, std::is_same<IO, uint16_t>::value ? 1 : 0, stream)
+                           : hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
+                                             dim3(static_cast<unsigned>(hs)), dim3(64 * NW), params, 0, stream);
   if (err != hipSuccess) return err;
   // With enough (head, segment) pairs to fill the chip the block operands are shared through LDS by a
   // workgroup per pair; with few, one wave per slab of S and deep register prefetch give the most waves.
@@ -829,6 +839,7 @@ hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream
   args.seg_A = nullptr;
   args.seg_S = nullptr;
   args.seg_PQ = nullptr;
+  args.seg_zkey = nullptr;
   return dispatch_phases(args, d, io_dtype, stream);
 }
 
@@ -862,7 +873,7 @@ SegmentPlan plan_segments(int n_heads, int T, int requested) {
 namespace {
 // workspace of the time-parallel mode, in floats, after the two-phase region
 struct TpLayout {
-  size_t gram, seg_A, seg_PQ, seg_S, total;
+  size_t gram, seg_A, seg_PQ, seg_S, key_part, seg_zkey, total;
 };
 TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
   const int nblk = (T + C - 1) / C;
@@ -874,6 +885,10 @@ TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
   l.seg_A = off;  off += mats;
   l.seg_PQ = off; off += 2 * mats;
   l.seg_S = off;  off += mats;
+  const size_t vecs = static_cast<size_t>(n_heads) * n_seg * d;      // one d-vector per (head, seg)
+  l.key_part = off; off += 2 * vecs;          // float64
+  l.seg_zkey = off; off += vecs;
+  off = (off + 3) & ~static_cast<size_t>(3);
   l.total = off;
   return l;
 }
@@ -901,6 +916,12 @@ hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int r
   if (err != hipSuccess) return err;
   err = launch_boundary(args, d, G, a.ws + l.seg_A, stream);
   if (err != hipSuccess) return err;
+  if (a.normalise_output != 0 || a.zkey_T != nullptr) {   // the key sum every segment starts with
+    float* seg_zkey = a.ws + l.seg_zkey;
+    err = launch_keysum(args, d, io_dtype, reinterpret_cast<double*>(a.ws + l.key_part), seg_zkey, stream);
+    if (err != hipSuccess) return err;
+    args.seg_zkey = seg_zkey;
+  }
   return dispatch_phases(args, d, io_dtype, stream);
 }
 

@@ -59,12 +59,19 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     for d, want in ((128, vla.MODE_CHUNKED), (64, vla.MODE_CHUNKED), (32, vla.MODE_CHUNKED),
                     (96, vla.MODE_CHUNKED), (16, vla.MODE_CHUNKED)):
         assert vla.resolve_mode(2, 2, 64, d, d, vla.VLA_BF16, refresh_period=20) == want
-    # few heads on a long sequence: still the block kernel, the segment modes carry no options
-    assert vla.resolve_mode(1, 4, 65536, 64, 64, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
+    # few heads on a long sequence: the time-parallel mode carries every option but the identity refresh
+    assert vla.resolve_mode(1, 4, 65536, 64, 64, vla.VLA_BF16, normalise_output=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, u=FAKE, normalise_output=1,
+                            feature_map=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(1, 4, 65536, 64, 64, vla.VLA_BF16, normalise_output=1,
+                            refresh_period=20) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=vla.MODE_SCAN, normalise_output=1) == vla.MODE_SCAN
     for mode in (vla.MODE_TWO_PHASE, vla.MODE_TIME_PARALLEL):
-        assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, normalise_output=1) == -1
+        assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, normalise_output=1) == mode
+        assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, u=FAKE, u_scale=0.5) == mode
+        assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, refresh_period=20) == -1
         assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=mode, feature_map=1) == mode
     # the feature map alone keeps the plain routing
     assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, feature_map=1) == vla.MODE_TIME_PARALLEL
@@ -96,7 +103,7 @@ def call(**kw):
     (dict(B=0), 1), (dict(H=-1), 1), (dict(T=-1), 1), (dict(d_k=0, d_v=0), 1),
     (dict(io_dtype=7), 1), (dict(mode=9), 1), (dict(lambda0=0.0), 1), (dict(eps=-1.0), 1),
     (dict(refresh_period=-1), 1), (dict(step_offset=-5), 1), (dict(step_offset=2**31 - 20, refresh_period=4), 1), (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1),
-    (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, normalise_output=1), 2),
+    (dict(mode=3, d_k=64, d_v=64, refresh_period=3), 2), (dict(mode=4, d_k=64, d_v=64, normalise_output=1, refresh_period=5), 2),
     (dict(mode=3, d_k=16, d_v=16), 2),
     (dict(q=0), 1), (dict(o=0), 1), (dict(q=FAKE + 4), 1), (dict(S0=FAKE + 8), 1),
     (dict(o=FAKE), 1),                       # o aliases q
@@ -168,28 +175,29 @@ def test_workspace_query_and_mode_resolution():
 
 def test_time_parallel_workspace_follows_the_segment_plan():
     """Workspace = the two-phase region (per 16-token block: 16 reciprocal key norms, W [d][16], Z and -NQ^T
-    [16][16] and 16 write strengths) + per (head, segment) one float64 and four float32 d x d matrices (Gram,
-    A start, P, Q, S start); one segment needs nothing beyond the two-phase region."""
+    [16][16], 16 write strengths and 16 read-out denominators) + per (head, segment) one float64 and four
+    float32 d x d matrices (Gram, A start, P, Q, S start) and one float64 and one float32 d-vector (key sums);
+    one segment needs nothing beyond the two-phase region."""
     B, H, T, d = 1, 16, 8192, 64
     two = vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
     nblk = T // 16
-    assert two == B * H * nblk * (16 + 16 * d + 528) * 4
+    assert two == B * H * nblk * (16 + 16 * d + 544) * 4
     tp = lambda s: vla.vla_forward_workspace_bytes(B, H, T, d, d, vla.VLA_BF16,
                                                    mode=vla.MODE_TIME_PARALLEL, segments=s)
     assert tp(1) == two
     for s in (2, 8, 64):
-        assert tp(s) == two + B * H * s * d * d * 4 * 6
+        assert tp(s) == two + B * H * s * (d * d * 6 + d * 3) * 4
     # 512 blocks in 100 segments: ceil(512/100) = 6 blocks each -> 86 non-empty segments
-    assert tp(100) == two + B * H * 86 * d * d * 4 * 6
+    assert tp(100) == two + B * H * 86 * (d * d * 6 + d * 3) * 4
     # never more segments than blocks, never more than 256
     assert vla.vla_forward_workspace_bytes(1, 1, 64, d, d, vla.VLA_F32, mode=vla.MODE_TIME_PARALLEL,
-                                           segments=99) == 4 * (16 + 16 * d + 528) * 4 + 4 * d * d * 24
+                                           segments=99) == 4 * (16 + 16 * d + 544) * 4 + 4 * (d * d * 6 + d * 3) * 4
     big = vla.vla_forward_workspace_bytes(1, 1, 16 * 4096, d, d, vla.VLA_F32,
                                           mode=vla.MODE_TIME_PARALLEL, segments=100000)
-    assert big == 4096 * (16 + 16 * d + 528) * 4 + 256 * d * d * 24
+    assert big == 4096 * (16 + 16 * d + 544) * 4 + 256 * (d * d * 6 + d * 3) * 4
     # the library's own choice: about 1024 (head, segment) pairs, segments of at least 16 blocks
     auto = tp(0)
-    assert auto == two + B * H * 32 * d * d * 24          # 512 blocks / 16 = 32 < 1024 / 16 heads = 64
+    assert auto == two + B * H * 32 * (d * d * 6 + d * 3) * 4    # 512 blocks / 16 = 32 < 1024 / 16 heads = 64
 
 
 def test_torch_front_end_refuses_cpu_tensors():

@@ -19,7 +19,7 @@ def modes_for(d):
     return [SCAN, BLOCK]
 
 
-def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, mode=None, **opt):
+def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, mode=None, segments=None, **opt):
     import torch
 
     import paper_2605_11196_amd as vla
@@ -37,7 +37,7 @@ def run_both(q, k, v, *, dtype="f32", u=None, S0=None, A0=None, zkey0=None, mode
                                        u_scale=opt.get("u_scale"), refresh_period=opt.get("refresh_period"),
                                        refresh_eta=opt.get("refresh_eta"), step_offset=opt.get("step_offset"),
                                        normalise_output=opt.get("normalise_output"),
-                                       feature_map=opt.get("feature_map"))
+                                       feature_map=opt.get("feature_map"), segments=segments)
     torch.cuda.synchronize()
     got = dict(o=to_np(o), S_T=to_np(S_T), A_T=to_np(A_T), zkey_T=to_np(zk))
     return got, ref
@@ -164,7 +164,7 @@ def test_feature_map_alone_runs_on_every_block_mode(d, T, mode, segments, dtype)
     assert max(errs.values()) <= TOL[dtype], errs
 
 
-def test_options_are_refused_by_the_segment_modes_and_taken_by_the_block_kernel():
+def test_refresh_is_refused_by_the_segment_modes_and_taken_by_the_block_kernel():
     import torch
 
     import paper_2605_11196_amd as vla
@@ -268,3 +268,74 @@ def test_feature_map_with_many_small_heads(d, B, H):
                 A=slab_rel_err(got["A_T"], ref["A_T"], 2))
     print(d, B * H, errs)
     assert max(errs.values()) <= 1e-4, errs
+
+
+# ---------------------------------------------------------------- the options inside the segment modes
+TWO_PHASE, TIME_PARALLEL = 3, 4
+SEGMENT_OPTION_SETS = {k: v for k, v in OPTION_SETS.items() if "refresh_period" not in v}
+SEGMENT_OPTION_SETS["paper_head"] = dict(with_u=True, u_scale=0.125, normalise_output=True, feature_map=True)
+
+
+@pytest.mark.parametrize("name", list(SEGMENT_OPTION_SETS))
+@pytest.mark.parametrize("d,T,segments,dtype", [(64, 330, 5, "f32"), (32, 200, 13, "f32"), (128, 150, 3, "f32"),
+                                                (64, 1000, 0, "bf16"), (128, 97, 2, "bf16")])
+def test_options_in_the_two_phase_and_time_parallel_modes(name, d, T, segments, dtype):
+    """A separate penalty direction (the Gram sums at the segment boundaries are then over u, eq. (penalty)), the
+    normalised read-out (every segment starts from the prefix sum of the keys before it, eq. (output)) and the
+    feature map, in both segment modes, ragged last blocks and short last segments included."""
+    cfg = dict(SEGMENT_OPTION_SETS[name])
+    rng = np.random.default_rng(300 + d + T)
+    q, k, v = vla_inputs.gaussian_qkv(2, 3, T, d, seed=1700 + d + T)
+    if cfg.pop("positive", False):
+        q, k = np.abs(q) + 0.05, np.abs(k) + 0.05
+    u = rng.standard_normal(q.shape).astype(np.float32) if cfg.pop("with_u", False) else None
+    cfg.pop("want_zkey_only", None)
+    for mode in (TWO_PHASE, TIME_PARALLEL):
+        got, ref = run_both(q, k, v, dtype=dtype, u=u, lambda0=0.1, mode=mode,
+                            segments=segments if mode == TIME_PARALLEL else None, **cfg)
+        print(name, d, T, dtype, mode, assert_close(got, ref, TOL[dtype]))
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_time_parallel_with_options_carries_state_between_calls(d):
+    """[0,T1) then [T1,T) in the time-parallel mode with S, A and the key sum carried == one oracle run; the
+    second call starts from a non-trivial A0 (inverted in float64 at the boundaries), S0 and key sum."""
+    T, T1 = 500, 212
+    rng = np.random.default_rng(8 + d)
+    q, k, v = vla_inputs.gaussian_qkv(1, 4, T, d, seed=91 + d)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    opt = dict(lambda0=0.1, u_scale=d ** -0.5, normalise_output=True, feature_map=True, mode=TIME_PARALLEL)
+    ref = oracle.forward(q, k, v, u=u, lambda0=0.1, u_scale=d ** -0.5, normalise_output=True, feature_map=True)
+    a, _ = run_both(q[:, :, :T1], k[:, :, :T1], v[:, :, :T1], u=u[:, :, :T1], segments=4, **opt)
+    b, _ = run_both(q[:, :, T1:], k[:, :, T1:], v[:, :, T1:], u=u[:, :, T1:], S0=a["S_T"], A0=a["A_T"],
+                    zkey0=a["zkey_T"], segments=6, **opt)
+    joined = dict(o=np.concatenate([a["o"], b["o"]], axis=2), S_T=b["S_T"], A_T=b["A_T"], zkey_T=b["zkey_T"])
+    print(d, assert_close(joined, ref, 1e-4))
+
+
+@pytest.mark.parametrize("d,T,segments", [(64, 250, 8), (32, 300, 8), (128, 150, 8)])
+def test_options_with_many_head_segment_pairs(d, T, segments):
+    """256 (head, segment) pairs: the S recurrence runs in the kernels that share a block's operands through
+    LDS, which carry the read-out denominators as well."""
+    rng = np.random.default_rng(d)
+    q, k, v = vla_inputs.gaussian_qkv(4, 8, T, d, seed=2200 + d)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    z0 = np.abs(rng.standard_normal((4, 8, d))).astype(np.float32)
+    for dtype in ("f32", "bf16"):
+        got, ref = run_both(q, k, v, dtype=dtype, u=u, zkey0=z0, lambda0=0.1, u_scale=0.25, normalise_output=True,
+                            feature_map=True, mode=TIME_PARALLEL, segments=segments)
+        print(d, dtype, assert_close(got, ref, TOL[dtype]))
+
+
+def test_auto_sends_a_few_head_call_with_the_papers_options_to_the_time_parallel_mode():
+    import paper_2605_11196_amd as vla
+
+    assert vla.resolve_mode(1, 16, 131072, 64, 64, vla.VLA_BF16, u=0x10000, normalise_output=1,
+                            feature_map=1) == vla.MODE_TIME_PARALLEL
+    d, T = 32, 4096
+    rng = np.random.default_rng(3)
+    q, k, v = vla_inputs.gaussian_qkv(1, 4, T, d, seed=31)
+    u = rng.standard_normal(q.shape).astype(np.float32)
+    got, ref = run_both(q, k, v, dtype="bf16", u=u, lambda0=0.1, u_scale=d ** -0.5, normalise_output=True,
+                        feature_map=True)       # mode AUTO
+    print(assert_close(got, ref, TOL["bf16"]))

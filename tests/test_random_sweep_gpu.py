@@ -52,6 +52,35 @@ def draw_cases(n, seed):
 CASES = draw_cases(160, seed=20260511)
 
 
+def draw_segment_option_cases(n, seed):
+    """The options the segment modes carry (everything but the identity refresh) in the two-phase and
+    time-parallel modes: supplied penalty directions, normalised read-out with a carried key sum, feature map."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        d = int(rng.choice([32, 64, 128]))
+        mode = int(rng.choice([TWO_PHASE, TIME_PARALLEL], p=[0.3, 0.7]))
+        c = dict(i=1000 + i, d=d, mode=mode, T=int(rng.integers(1, 900)), B=int(rng.integers(1, 3)),
+                 H=int(rng.integers(1, 4)), dtype=str(rng.choice(["f32", "bf16"])),
+                 given_state=bool(rng.random() < 0.5), zero_frac=float(rng.choice([0.0, 0.0, 0.1])),
+                 seed=int(rng.integers(1 << 30)),
+                 segments=int(rng.integers(2, 12)) if mode == TIME_PARALLEL else None, opts={})
+        o = {}
+        if rng.random() < 0.7:
+            o["with_u"] = True
+            o["u_scale"] = float(rng.choice([1.0, 0.5, d ** -0.5]))
+        if rng.random() < 0.6 or not o:
+            o["normalise_output"] = True
+        if rng.random() < 0.5 or o.get("normalise_output"):
+            o["feature_map"] = True
+        c["opts"] = o
+        cases.append(c)
+    return cases
+
+
+CASES += draw_segment_option_cases(60, seed=20260512)
+
+
 @pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c['i']}-d{c['d']}-T{c['T']}-m{c['mode']}-{c['dtype']}")
 def test_random_case_matches_the_oracle(case):
     import torch
