@@ -664,6 +664,7 @@ hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipS
   switch (d) {
     case 32: return bf ? launch_scan<32, uint16_t>(a, stream) : launch_scan<32, float>(a, stream);
     case 64: return bf ? launch_scan<64, uint16_t>(a, stream) : launch_scan<64, float>(a, stream);
+    case 96: return bf ? launch_scan<96, uint16_t>(a, stream) : launch_scan<96, float>(a, stream);
     case 128: return bf ? launch_scan<128, uint16_t>(a, stream) : launch_scan<128, float>(a, stream);
     default: return hipErrorInvalidValue;
   }

@@ -62,7 +62,7 @@ hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStr
 bool chunk_supported(int d);
 bool chunk_supported(int d_k, int d_v);
 // Head sizes of the two-phase and time-parallel modes.
-inline bool block_family_supported(int d) { return d == 32 || d == 64 || d == 128; }
+inline bool block_family_supported(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream);
 // Same block form, several heads per workgroup (vla_chunk_multihead.hip); head sizes 32 and 64.
 // launch_chunk picks it by head size and head count (prefer_multihead).
@@ -72,7 +72,7 @@ hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hip
 inline bool general_block_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
 hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 // Its A chain alone, one workgroup per (head, time segment), writing the workspace records of the two-phase and
-// time-parallel modes (head sizes 32, 64, 128).
+// time-parallel modes (head sizes 32, 64, 96, 128).
 hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
 

@@ -27,8 +27,12 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 // receives D[i = l / 16 + 4 r][j = l % 16] in element r), both operands being the same staged tile.  A wave
 // holds at most 16 result tiles: up to D = 64 every wave covers the whole matrix and the waves take the
 // tokens of a tile in turn (summed through LDS at the end); at D = 128 each wave owns two tile rows.
-template <int D, typename IO>
+// DL: the head size of the data; D >= DL: the size the tiles are laid out for.  They differ for d = 96, which
+// runs in the d = 128 layout with the columns from 96 on held at zero (the loads, the staging and the final
+// stores skip them).
+template <int D, int DL, typename IO>
 __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(ForwardArgs a, double* G) {
+  static_assert(DL <= D && DL % 16 == 0, "padded layout");
   constexpr int NTI = D / 16;                                // tiles per side
   constexpr int TR = NTI * NTI <= 16 ? NTI : 16 / NTI;       // tile rows per wave
   constexpr int RGW = NTI / TR;                              // waves across the rows
@@ -60,7 +64,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   const int te = min(a.T, tb + a.seg_blocks * C);
   // the directions the penalty matrix accumulates: the caller's u (scaled after normalisation), else the keys
   const bool has_u = a.u != nullptr;
-  const IO* kh = static_cast<const IO*>(has_u ? a.u : a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
+  const IO* kh = static_cast<const IO*>(has_u ? a.u : a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * DL;
   const double eps = static_cast<double>(a.eps);
   const double scale = has_u ? static_cast<double>(a.u_scale) : 1.0;
   const int srow = tid / TPR;
@@ -78,7 +82,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   RawRow<IO, EPT> raw[PF];
   auto fetch = [&](int t0, RawRow<IO, EPT>& o) {
     const int t = t0 + srow;
-    o.load(kh + static_cast<size_t>(t < te ? t : te - 1) * D + scol);
+    if (D == DL || scol < DL) o.load(kh + static_cast<size_t>(t < te ? t : te - 1) * DL + scol);
   };
   // stage: k^ = k / max(||k||, eps) in float64; rows past the end are zero.  1 / ||k|| is a float32
   // reciprocal square root refined by one Newton step in float64 (relative error ~1e-14).
@@ -86,7 +90,11 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     const int t = t0 + srow;
     double x[EPT];
     o.unpack(x);
-    if (a.feature_map && !has_u) {   // ELU(x) + 1 on keys, in float32, as the kernels that run the recurrence apply it
+    if (D != DL && scol >= DL) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) x[e] = 0.0;
+    }
+    if (a.feature_map && !has_u && (D == DL || scol < DL)) {   // ELU(x) + 1 on keys, in float32, as the kernels that run the recurrence apply it
 #pragma unroll
       for (int e = 0; e < EPT; ++e) x[e] = static_cast<double>(elu_plus_one(static_cast<float>(x[e])));
     }
@@ -140,7 +148,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   }
 
   // element r of tile (i, j) is G[16 (rgw TR + i) + g + 4 r][16 j + c]
-  double* Gh = G + static_cast<size_t>(blockIdx.x) * D * D;
+  double* Gh = G + static_cast<size_t>(blockIdx.x) * DL * DL;
   if constexpr (NGW == 1) {
 #pragma unroll
     for (int i = 0; i < TR; ++i)
@@ -149,8 +157,10 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int row = 16 * (rgw * TR + i) + g + 4 * r, col = 16 * j + c;
-          Gh[row * D + col] = acc[i][j][r];
-          if (SYM && j > i) Gh[col * D + row] = acc[i][j][r];
+          if (D == DL || (row < DL && col < DL)) {
+            Gh[row * DL + col] = acc[i][j][r];
+            if (SYM && j > i) Gh[col * DL + row] = acc[i][j][r];
+          }
         }
   } else {
     __syncthreads();   // every wave is done with the tile buffers
@@ -168,6 +178,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
       }
       __syncthreads();
     }
+    static_assert(NGW == 1 || D == DL, "the padded layout is only used where each wave owns its tile rows");
     for (int o = tid; o < D * D; o += kThreads) {
       const int row = o / D, col = o - row * D;
       Gh[o] = (SYM && row / 16 > col / 16) ? red[col * D + row] : red[o];   // tile below the diagonal: mirror
@@ -289,8 +300,11 @@ struct SpdInverse {
 
 // One workgroup per (head, segment): seg_A = inverse(inverse(A0) + sum of the Gram matrices before it),
 // G holding the prefix sums.
-template <int D>
+// DL: the head size of the data; D >= DL: the size the inversion is laid out for (d = 96 runs in the d = 128
+// layout: the matrix is bordered with an identity block, whose inverse is itself).
+template <int D, int DL>
 __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const double* G, float* seg_A) {
+  static_assert(DL <= D, "padded layout");
   constexpr int RG = kThreads / D;
   constexpr int NR = D / RG;
   __shared__ __align__(16) double colp[2 * SpdInverse<D>::STRIDE];
@@ -299,12 +313,15 @@ __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const
   const int seg = blockIdx.x - head * a.n_seg;
   const int j = threadIdx.x % D;
   const int rg = threadIdx.x / D;
-  const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr;
-  float* out = seg_A + static_cast<size_t>(blockIdx.x) * D * D;
+  const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * DL * DL : nullptr;
+  float* out = seg_A + static_cast<size_t>(blockIdx.x) * DL * DL;
   const float diag = 1.0f / a.lambda0;   // the same float32 value the first segment starts from
+  const bool jin = D == DL || j < DL;    // column j belongs to the data
 
   if (seg == 0) {   // the first segment starts from the caller's A0, bit for bit
-    for (int i = rg; i < D; i += RG) out[i * D + j] = A0 ? A0[i * D + j] : (i == j ? diag : 0.0f);
+    if (jin) {
+      for (int i = rg; i < DL; i += RG) out[i * DL + j] = A0 ? A0[i * DL + j] : (i == j ? diag : 0.0f);
+    }
     return;
   }
   const SpdInverse<D> inv{colp};
@@ -313,18 +330,26 @@ __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const
 #pragma unroll
     for (int n = 0; n < NR; ++n) {
       const int i = rg + RG * n;
-      m[n] = 0.5 * (static_cast<double>(A0[i * D + j]) + static_cast<double>(A0[j * D + i]));
+      m[n] = (jin && (D == DL || i < DL))
+                 ? 0.5 * (static_cast<double>(A0[i * DL + j]) + static_cast<double>(A0[j * DL + i]))
+                 : (i == j ? 1.0 : 0.0);
     }
     inv.run(m);
     __syncthreads();   // the pivot buffers are reused by the second inversion
   } else {
 #pragma unroll
-    for (int n = 0; n < NR; ++n) m[n] = (rg + RG * n == j) ? 1.0 / static_cast<double>(diag) : 0.0;
+    for (int n = 0; n < NR; ++n) {
+      const int i = rg + RG * n;
+      m[n] = (i == j) ? ((jin) ? 1.0 / static_cast<double>(diag) : 1.0) : 0.0;
+    }
   }
   // G holds inclusive prefix sums: G[head][seg - 1] covers every token before this segment
-  const double* Gh = G + (static_cast<size_t>(blockIdx.x) - 1) * D * D;
+  const double* Gh = G + (static_cast<size_t>(blockIdx.x) - 1) * DL * DL;
 #pragma unroll
-  for (int n = 0; n < NR; ++n) m[n] += Gh[(rg + RG * n) * D + j];
+  for (int n = 0; n < NR; ++n) {
+    const int i = rg + RG * n;
+    if (jin && (D == DL || i < DL)) m[n] += Gh[i * DL + j];
+  }
   inv.run(m);
   // The inverse of a symmetric matrix is symmetric up to rounding; store the lower triangle's values on both
   // sides so that the float32 matrix the recurrence starts from is exactly symmetric.
@@ -332,9 +357,9 @@ __global__ void __launch_bounds__(kThreads) boundary_kernel(ForwardArgs a, const
   for (int n = 0; n < NR; ++n) {
     const int i = rg + RG * n;
     const float v = static_cast<float>(m[n]);
-    if (i >= j) {
-      out[i * D + j] = v;
-      out[j * D + i] = v;
+    if (i >= j && (D == DL || i < DL)) {
+      out[i * DL + j] = v;
+      out[j * DL + i] = v;
     }
   }
 }
@@ -414,21 +439,21 @@ __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, f
   }
 }
 
-template <int D>
+template <int D, int DL = D>
 hipError_t launch_boundary_d(const ForwardArgs& a, const double* G, float* seg_A, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args, &G, &seg_A};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&boundary_kernel<D>), dim3(a.n_heads * a.n_seg),
+  return hipLaunchKernel(reinterpret_cast<const void*>(&boundary_kernel<D, DL>), dim3(a.n_heads * a.n_seg),
                          dim3(kThreads), params, 0, stream);
 }
-template <int D, typename IO>
+template <int D, typename IO, int DL = D>
 hipError_t launch_gram_d(const ForwardArgs& a, double* G, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args, &G};
-  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&gram_kernel<D, IO>),
+  hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&gram_kernel<D, DL, IO>),
                                    dim3(a.n_heads * a.n_seg), dim3(kThreads), params, 0, stream);
   if (err != hipSuccess) return err;
-  int nh = a.n_heads, ns = a.n_seg, dd = D * D;
+  int nh = a.n_heads, ns = a.n_seg, dd = DL * DL;
   void* p2[] = {&G, &nh, &ns, &dd};
   const long long elems = static_cast<long long>(nh) * dd;
   return hipLaunchKernel(reinterpret_cast<const void*>(&gram_prefix_kernel),
@@ -472,6 +497,8 @@ hipError_t launch_keysum(const ForwardArgs& a, int d, int io_dtype, double* part
                        : launch_keysum_d<32, float>(a, part, seg_zkey, stream);
     case 64: return bf ? launch_keysum_d<64, uint16_t>(a, part, seg_zkey, stream)
                        : launch_keysum_d<64, float>(a, part, seg_zkey, stream);
+    case 96: return bf ? launch_keysum_d<96, uint16_t>(a, part, seg_zkey, stream)
+                       : launch_keysum_d<96, float>(a, part, seg_zkey, stream);
     case 128: return bf ? launch_keysum_d<128, uint16_t>(a, part, seg_zkey, stream)
                         : launch_keysum_d<128, float>(a, part, seg_zkey, stream);
     default: return hipErrorInvalidValue;
@@ -483,6 +510,7 @@ hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hip
   switch (d) {
     case 32: return bf ? launch_gram_d<32, uint16_t>(a, G, stream) : launch_gram_d<32, float>(a, G, stream);
     case 64: return bf ? launch_gram_d<64, uint16_t>(a, G, stream) : launch_gram_d<64, float>(a, G, stream);
+    case 96: return bf ? launch_gram_d<128, uint16_t, 96>(a, G, stream) : launch_gram_d<128, float, 96>(a, G, stream);
     case 128: return bf ? launch_gram_d<128, uint16_t>(a, G, stream) : launch_gram_d<128, float>(a, G, stream);
     default: return hipErrorInvalidValue;
   }
@@ -492,6 +520,7 @@ hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* 
   switch (d) {
     case 32: return launch_boundary_d<32>(a, G, seg_A, stream);
     case 64: return launch_boundary_d<64>(a, G, seg_A, stream);
+    case 96: return launch_boundary_d<128, 96>(a, G, seg_A, stream);
     case 128: return launch_boundary_d<128>(a, G, seg_A, stream);
     default: return hipErrorInvalidValue;
   }
@@ -501,6 +530,7 @@ hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t
   switch (d) {
     case 32: return launch_combine_d<32>(a, seg_S, stream);
     case 64: return launch_combine_d<64>(a, seg_S, stream);
+    case 96: return launch_combine_d<96>(a, seg_S, stream);
     case 128: return launch_combine_d<128>(a, seg_S, stream);
     default: return hipErrorInvalidValue;
   }

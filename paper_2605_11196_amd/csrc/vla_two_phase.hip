@@ -36,9 +36,15 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
   constexpr int NB = D / 16;
   constexpr int LD = D + 4;
   constexpr int NT = 64 * NW;
-  constexpr int EPT = C * D / NT;
-  constexpr int TPR = D / EPT;
-  static_assert(EPT % 4 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0, "staging layout");
+  // Staging: a token row is split over TPR threads of EPT elements each.  For the power-of-two head sizes every
+  // thread stages; at d = 96 a row takes 6 threads of 16 elements in a group of 8 (two lanes of each group and
+  // the third wave stage nothing), so that a row never straddles a wave and sums with a power-of-two shuffle.
+  constexpr int TPR0 = NT / C;
+  constexpr bool PADDED = (TPR0 & (TPR0 - 1)) != 0;
+  constexpr int EPT = PADDED ? 16 : C * D / NT;
+  constexpr int TPR = PADDED ? 8 : D / EPT;
+  static_assert(EPT % 4 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0 && C * TPR <= NT && D % EPT == 0 &&
+                D / EPT <= TPR, "staging layout");
 
   __shared__ __align__(16) float Ks[C * LD];
   __shared__ __align__(16) float Qs[C * LD];
@@ -98,13 +104,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
+  const bool stager = !PADDED || (tid < C * TPR && sseg < D);    // this thread holds a row segment
+  const bool stage_wave = !PADDED || tid < C * TPR;              // uniform per wave
 
   RawRow<IO, EPT> kpre, qpre;
   auto prefetch = [&](int t0) {
-    const int tr = t0 + srow;
-    const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
-    kpre.load(kh + koff);
-    qpre.load(qh + koff);
+    if (stager) {
+      const int tr = t0 + srow;
+      const unsigned koff = static_cast<unsigned>((tr < T ? tr : T - 1) * D + sseg);
+      kpre.load(kh + koff);
+      qpre.load(qh + koff);
+    }
   };
   if (tb < T) prefetch(tb);
 
@@ -159,10 +169,15 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
   for (int t0 = tb; t0 < T; t0 += C, ++blk, ++it) {
     const int pb = it & 1;
     // ---- stage K^ and Q (LDS); 1 / max(||k||, eps) per token goes to the workspace
-    {
+    if (stage_wave) {
       float kx[EPT];
-      const bool live = t0 + srow < T;
-      kpre.unpack(kx);
+      const bool live = t0 + srow < T && stager;
+      if (stager) {
+        kpre.unpack(kx);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) kx[e] = 0.0f;
+      }
       if (fmap) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
@@ -178,22 +193,24 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
       const float sm = fmaxf(ss, eps * eps);
       float rn = __builtin_amdgcn_rsqf(sm);
       rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f);
-      if (sseg == 0) RN[t0 + srow] = live ? rn : 0.0f;   // rows past the end: zero keys
+      if (stager) {
+        if (sseg == 0) RN[t0 + srow] = live ? rn : 0.0f;   // rows past the end: zero keys
 #pragma unroll
-      for (int e = 0; e < EPT; e += 4) {
-        *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) =
-            f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+        for (int e = 0; e < EPT; e += 4) {
+          *reinterpret_cast<f4*>(&Ks[srow * LD + sseg + e]) =
+              f4{kx[e] * rn, kx[e + 1] * rn, kx[e + 2] * rn, kx[e + 3] * rn};
+        }
+        qpre.unpack(kx);
+        if (fmap) {
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPT; e += 4)
+          *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
       }
-      qpre.unpack(kx);
-      if (fmap) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
-      }
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
-#pragma unroll
-      for (int e = 0; e < EPT; e += 4)
-        *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
     }
     __syncthreads();  // (1)
     if (t0 + C < T) prefetch(t0 + C);
@@ -563,8 +580,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     float Wb[D * LT];      // W  [j][t]
     float Zs[C * LT];      // Z  [t][s]
     float NQs[C * LT];     // -NQ^T [t][s]
-    float cv[C];           // -c_t
-    float rd[C];           // 1 / max(q_t . zkey_t, eps) (normalised read-out only)
+    float cv[2 * C];       // -c_t, then 1 / max(q_t . zkey_t, eps) (normalised read-out only)
   };
   __shared__ __align__(16) Stage stg[NST];
 
@@ -621,9 +637,9 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const int wrow = pc / 4, wcol = 4 * (pc % 4);
   const int sm_src = tid < 64 ? 4 * tid : C * C + 4 * (tid - 64);
   const bool do_sm = tid < (MAP ? 64 : 128);   // Z on threads 0-63, -NQ^T on 64-127 (not in the map pass)
-  const bool do_c = tid < 4;                   // -c
+  const bool do_c = tid < ((!MAP && norm_out) ? 8 : 4);   // -c (and the read-out denominators behind it)
   struct Regs {
-    f4 wx, sx, cx, rdx;
+    f4 wx, sx, cx;
     RawRow<IO, 4> kx, qx;
     float krn;          // 1 / max(||k||, eps) of token row krow (0 past the end)
     IO v[4];
@@ -637,11 +653,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     }
     if (do_w) r.wx = *reinterpret_cast<const f4*>(WT + static_cast<size_t>(blk) * (D * C) + wrow * C + wcol);
     if (do_sm) r.sx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + sm_src);
-    if (do_c) {
-      r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
-      if (!MAP && norm_out)
-        r.rdx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + C + 4 * tid);
-    }
+    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
     if constexpr (!MAP) r.qx.load(qh + kq);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -663,10 +675,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       if (tid < 64) *reinterpret_cast<f4*>(&s.Zs[(tid / 4) * LT + 4 * (tid % 4)]) = r.sx;
       else *reinterpret_cast<f4*>(&s.NQs[((tid - 64) / 4) * LT + 4 * (tid % 4)]) = r.sx;
     }
-    if (do_c) {
-      *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
-      if (!MAP && norm_out) *reinterpret_cast<f4*>(&s.rd[4 * tid]) = r.rdx;
-    }
+    if (do_c) *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
     if constexpr (!MAP) {
       float x[4];
       r.qx.unpack(x);
@@ -701,7 +710,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       const f4 nqa = lds4(&s.NQs[c * LT + 4 * g]);
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
-      if (norm_out) ot *= lds4(&s.rd[4 * g]);
+      if (norm_out) ot *= lds4(&s.cv[C + 4 * g]);
       IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
         io_store2(ob, ob + D, ot[0], ot[1]);
@@ -826,6 +835,7 @@ hipError_t dispatch_phases(const ForwardArgs& a, int d, int io_dtype, hipStream_
   switch (d) {
     case 32: return bf ? launch_phases<32, 2, uint16_t>(a, stream) : launch_phases<32, 2, float>(a, stream);
     case 64: return bf ? launch_phases<64, 2, uint16_t>(a, stream) : launch_phases<64, 2, float>(a, stream);
+    case 96: return bf ? launch_phases<96, 3, uint16_t>(a, stream) : launch_phases<96, 3, float>(a, stream);
     case 128: return bf ? launch_phases<128, 4, uint16_t>(a, stream) : launch_phases<128, 4, float>(a, stream);
     default: return hipErrorInvalidValue;
   }

@@ -65,7 +65,8 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
                             feature_map=1) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(1, 4, 65536, 64, 64, vla.VLA_BF16, normalise_output=1,
                             refresh_period=20) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, normalise_output=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(1, 4, 65536, 16, 16, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 128, 128, vla.VLA_BF16, mode=vla.MODE_SCAN, normalise_output=1) == vla.MODE_SCAN
     for mode in (vla.MODE_TWO_PHASE, vla.MODE_TIME_PARALLEL):
@@ -78,10 +79,12 @@ def test_options_run_on_the_block_kernel_or_the_scan_family():
     assert vla.resolve_mode(64, 32, 8192, 128, 128, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
-    # d = 96: the plain block kernel (with or without the feature map), no segment modes
+    # d = 96 has every mode; d = 16 has no segment modes
     assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
+    assert vla.resolve_mode(1, 4, 65536, 96, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(2, 2, 64, 96, 96, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE) == vla.MODE_TWO_PHASE
+    assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
     assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16) == vla.MODE_CHUNKED     # plain block kernel at d = 16
     assert vla.resolve_mode(2, 2, 64, 16, 16, vla.VLA_BF16, refresh_period=5) == vla.MODE_CHUNKED
 
@@ -164,7 +167,8 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(1, 16, 500, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 128, 512, 64, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(1, 128, 1024, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
-    assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_CHUNKED   # no segment modes at d = 96
+    assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(1, 16, 131072, 16, 16, vla.VLA_BF16) == vla.MODE_CHUNKED   # no segment modes at d = 16
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_CHUNKED   # d_k != d_v: plain kernels
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1

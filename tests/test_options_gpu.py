@@ -278,7 +278,8 @@ SEGMENT_OPTION_SETS["paper_head"] = dict(with_u=True, u_scale=0.125, normalise_o
 
 @pytest.mark.parametrize("name", list(SEGMENT_OPTION_SETS))
 @pytest.mark.parametrize("d,T,segments,dtype", [(64, 330, 5, "f32"), (32, 200, 13, "f32"), (128, 150, 3, "f32"),
-                                                (64, 1000, 0, "bf16"), (128, 97, 2, "bf16")])
+                                                (64, 1000, 0, "bf16"), (128, 97, 2, "bf16"), (96, 210, 4, "f32"),
+                                                (96, 90, 3, "bf16")])
 def test_options_in_the_two_phase_and_time_parallel_modes(name, d, T, segments, dtype):
     """A separate penalty direction (the Gram sums at the segment boundaries are then over u, eq. (penalty)), the
     normalised read-out (every segment starts from the prefix sum of the keys before it, eq. (output)) and the
@@ -296,7 +297,7 @@ def test_options_in_the_two_phase_and_time_parallel_modes(name, d, T, segments, 
         print(name, d, T, dtype, mode, assert_close(got, ref, TOL[dtype]))
 
 
-@pytest.mark.parametrize("d", [32, 64, 128])
+@pytest.mark.parametrize("d", [32, 64, 96, 128])
 def test_time_parallel_with_options_carries_state_between_calls(d):
     """[0,T1) then [T1,T) in the time-parallel mode with S, A and the key sum carried == one oracle run; the
     second call starts from a non-trivial A0 (inverted in float64 at the boundaries), S0 and key sum."""

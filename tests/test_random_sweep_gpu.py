@@ -58,7 +58,7 @@ def draw_segment_option_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
     for i in range(n):
-        d = int(rng.choice([32, 64, 128]))
+        d = int(rng.choice([32, 64, 96, 128]))
         mode = int(rng.choice([TWO_PHASE, TIME_PARALLEL], p=[0.3, 0.7]))
         c = dict(i=1000 + i, d=d, mode=mode, T=int(rng.integers(1, 900)), B=int(rng.integers(1, 3)),
                  H=int(rng.integers(1, 4)), dtype=str(rng.choice(["f32", "bf16"])),

@@ -20,6 +20,8 @@ TP = 4  # VLA_MODE_TIME_PARALLEL
     (32, 200, 256),     # more segments asked for than blocks: one block per segment
     (128, 513, 2),      # second segment ends in a one-token block
     (128, 300, 7),
+    (96, 700, 6),       # three waves per head, keys staged by 6 threads of 16 elements; Gram sums and the
+    (96, 47, 3),        # boundary inverse run in the d = 128 layout with the extra columns held at zero
     (64, 4096, 0),      # the library's own choice (16 segments for 6 heads)
     (32, 2048, 0),
     (64, 16, 4),        # a single block: degenerates to one segment
@@ -31,7 +33,7 @@ def test_segments_match_the_sequential_oracle(d, T, segments, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("d,T,segments", [(64, 250, 8), (32, 300, 8), (128, 150, 8), (64, 16 * 9, 9)])
+@pytest.mark.parametrize("d,T,segments", [(64, 250, 8), (32, 300, 8), (128, 150, 8), (64, 16 * 9, 9), (96, 200, 8)])
 def test_many_head_segment_pairs_take_the_shared_operand_kernels(d, T, segments, dtype):
     """32 heads x 8 segments = 256 (head, segment) pairs: from there on the S recurrence runs with one
     workgroup per pair and the block operands staged once through LDS (ragged last block, one- and
@@ -42,13 +44,13 @@ def test_many_head_segment_pairs_take_the_shared_operand_kernels(d, T, segments,
     print(d, T, segments, dtype, errs)
 
 
-@pytest.mark.parametrize("d,T", [(64, 100), (128, 33), (32, 200)])
+@pytest.mark.parametrize("d,T", [(64, 100), (128, 33), (32, 200), (96, 70)])
 def test_two_phase_with_many_heads_takes_the_shared_operand_kernel(d, T):
     q, k, v = vla_inputs.gaussian_qkv(16, 16, T, d, seed=1300 + d)
     check_parity(q, k, v, lambda0=0.1, mode=3)
 
 
-@pytest.mark.parametrize("d", [32, 64, 128])
+@pytest.mark.parametrize("d", [32, 64, 96, 128])
 def test_given_initial_state_enters_the_boundary_inverse(d):
     """A non-trivial symmetric positive definite A0 and a non-zero S0 (the state after T1 tokens, from
     the oracle) must be carried through the boundary computation: A0 is inverted in float64 there."""
