@@ -143,10 +143,12 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *          returns VLA_ERR_INVALID_ARG -- with three exceptions: S_T == S0, A_T == A0 and
  *          zkey_T == zkey0 (the same pointer: the state is then updated in place).
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
- *   d_k == d_v in {16, 32, 64, 96, 128}  (SCAN and CHUNKED cover all of them, TWO_PHASE and
- *          TIME_PARALLEL 32, 64, 128), or d_k, d_v in
- *          {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2 (SCAN and CHUNKED; no options other than
- *          feature_map, which only CHUNKED carries for these shapes)
+ *   d_k, d_v in {16, 32, 64, 96, 128}, any pair.  With d_k == d_v: SCAN and CHUNKED at every size,
+ *          TWO_PHASE and TIME_PARALLEL from 32.  With d_k != d_v (S is d_v x d_k): SCAN for every pair and
+ *          every option; CHUNKED (without options other than feature_map) where the d_k / 32 waves of a
+ *          head share out the rows of S in whole 16-row tiles: every d_v with d_k = 16 or 32, d_v >= 32
+ *          with d_k = 64, d_v >= 64 with d_k = 128, none with d_k = 96; AUTO picks CHUNKED where it
+ *          applies and SCAN otherwise
  *   opts   host pointer or NULL
  *   workspace, workspace_bytes: device scratch of at least
  *          vla_forward_workspace_bytes(...) bytes (may be NULL/0 when that is 0)
@@ -195,8 +197,8 @@ int vla_forward_static(const void* q, const void* k, const void* v, const float*
  *   S      [B, H, d_v, d_k] float32 row-major, updated in place (required)
  *   A      [B, H, d_k, d_k] float32 row-major, updated in place (required; symmetric positive definite)
  *   o      [B, H, d_v]      io_dtype, written; must not overlap any input
- *   d_k == d_v in {16, 32, 64, 96, 128}, or d_k, d_v in {16, 32, 64, 128} with d_v = 2 d_k or d_v = d_k / 2
- *          (then without any of the optional lines of Algorithm 1)
+ *   d_k == d_v in {16, 32, 64, 96, 128}, or d_k in {16, 32, 64, 128} with any other d_v of that set (then
+ *          without any of the optional lines of Algorithm 1)
  *   opts   host pointer or NULL.  eps and the optional lines of Algorithm 1 are honoured as in vla_forward
  *          with T = 1: u [B, H, d_k] (io_dtype) with u_scale, the identity refresh (this call is step
  *          step_offset + 1 of the schedule), normalise_output with zkey0 / zkey_T [B, H, d_k] (may alias),

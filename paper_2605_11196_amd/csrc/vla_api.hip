@@ -128,15 +128,20 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
   // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0), 256 heads at d = 32 (2.7 against
   // 4.5 ms; 512 heads 5.1 against 4.5)
-  const long long few = d >= 128 ? 64 : (d >= 64 ? 128 : 256);
-  // short sequences: 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads 0.19 against 0.17
-  const bool long_enough = T >= 1024 || (T >= 512 && 2 * heads <= few);
+  // d = 96 (its Gram sums and boundary inverses run in the d = 128 layout): 64 heads 3.5 against 6.5 ms, 128 heads
+  // 6.3 against 6.5
+  const long long few = d >= 96 ? 64 : (d >= 64 ? 128 : 256);
+  // short sequences: 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads 0.19 against 0.17;
+  // at d = 96 the crossover sits one octave higher (T = 1024: 16 heads 0.29 against 0.41 ms, 64 heads 0.43
+  // against 0.41; T = 512: 16 heads 0.26 against 0.21)
+  const int t_long = d == 96 ? 2048 : 1024;
+  const bool long_enough = T >= t_long || (2 * T >= t_long && 2 * heads <= few);
   if (heads <= few && long_enough) return VLA_MODE_TIME_PARALLEL;
   return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
 }
 
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
-  if (mode == VLA_MODE_SCAN) return d == d_v || !general_path(o);   // the option kernels are square only
+  if (mode == VLA_MODE_SCAN) return true;   // every pair of head sizes, with or without options
   if (!vla::chunk_supported(d, d_v)) return false;
   if (d != d_v) return mode == VLA_MODE_CHUNKED && !needs_general_kernel(o);   // the plain block kernel only
   if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::general_block_supported(d);
@@ -282,7 +287,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* S0, c
   switch (mode) {
     case VLA_MODE_SCAN:
       err = general_path(op)
-                ? vla::launch_scan_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
+                ? vla::launch_scan_general(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream))
                 : vla::launch_scan(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_CHUNKED:

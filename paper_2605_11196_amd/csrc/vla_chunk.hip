@@ -531,12 +531,14 @@ bool prefer_multihead(int d, int n_heads) {
   return false;
 }
 
-// Value heads as wide as the key heads, or half or twice as wide (the wave that owns 32 columns of A then owns
-// 16 or 64 rows of S).
+// The d_k / 32 waves of a head (one below d_k = 32) share out the d_v rows of S in whole 16-row tiles: every value
+// head size from 16 to 128 with key heads of 16 or 32, value heads from 32 with key heads of 64, from 64 with key
+// heads of 128; key heads of 96 (three waves) only with value heads of 96.
 bool chunk_supported(int d_k, int d_v) {
-  if (d_k == d_v) return chunk_supported(d_k);
-  return (d_k == 16 && d_v == 32) || (d_k == 32 && (d_v == 16 || d_v == 64)) ||
-         (d_k == 64 && (d_v == 32 || d_v == 128)) || (d_k == 128 && d_v == 64);
+  if (!chunk_supported(d_k) || !chunk_supported(d_v)) return false;
+  if (d_k == 96 || d_v == 96) return d_k == d_v || (d_v == 96 && d_k <= 64);
+  const int waves = d_k >= 32 ? d_k / 32 : 1;
+  return d_v % (16 * waves) == 0;
 }
 
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
@@ -553,6 +555,12 @@ hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hi
     case 64032: return launch_io<64, 32, 2>(a, io_dtype, stream);
     case 64128: return launch_io<64, 128, 2>(a, io_dtype, stream);
     case 128064: return launch_io<128, 64, 4>(a, io_dtype, stream);
+    case 16064: return launch_io<16, 64, 1>(a, io_dtype, stream);
+    case 16096: return launch_io<16, 96, 1>(a, io_dtype, stream);
+    case 16128: return launch_io<16, 128, 1>(a, io_dtype, stream);
+    case 32096: return launch_io<32, 96, 1>(a, io_dtype, stream);
+    case 32128: return launch_io<32, 128, 1>(a, io_dtype, stream);
+    case 64096: return launch_io<64, 96, 2>(a, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }

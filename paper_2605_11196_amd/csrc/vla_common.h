@@ -50,11 +50,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return static_cast<uint16_t>(x >> 16);
 }
 
-// Token-by-token scan, one workgroup per head (vla_scan.hip); the only kernel family with d_k != d_v.
+// Token-by-token scan, one workgroup per head (vla_scan.hip); every pair of head sizes d_k, d_v.
 bool scan_supported(int d_k, int d_v);
 hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream);
 // Same, with the optional lines of Algorithm 1 (separate u, refresh, normalised read-out, ELU+1).
-hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+hipError_t launch_scan_general(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream);
 
 
 // Block form on FP32 MFMA, 16 tokens per block (vla_chunk.hip); head sizes 16, 32, 64, 96 and 128, and value

@@ -297,7 +297,7 @@ hipError_t launch(const DecodeArgs& a, int n_heads, hipStream_t stream) {
                            : reinterpret_cast<const void*>(&decode_kernel<D, D, IO>);
   return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
 }
-// value heads half or twice as wide as the key heads: the plain kernel only
+// value heads of another size than the key heads: the plain kernel only
 template <int D, int DV>
 hipError_t launch_rect(const DecodeArgs& a, int n_heads, int io_dtype, hipStream_t stream) {
   DecodeArgs args = a;
@@ -309,11 +309,13 @@ hipError_t launch_rect(const DecodeArgs& a, int n_heads, int io_dtype, hipStream
 
 }  // namespace
 
+// Square heads of every size with or without options; without options also every value head size with key heads
+// of 16, 32, 64 or 128 (a wave's 32 rows of A go with 32 d_v / d_k rows of S, a whole number of four-row passes).
 bool decode_supported(int d_k, int d_v, bool options) {
-  if (d_k == d_v) return d_k == 16 || d_k == 32 || d_k == 64 || d_k == 96 || d_k == 128;
-  const bool pow2 = (d_k == 16 || d_k == 32 || d_k == 64 || d_k == 128) &&
-                    (d_v == 16 || d_v == 32 || d_v == 64 || d_v == 128);
-  return !options && pow2 && (d_v == 2 * d_k || d_k == 2 * d_v);
+  const auto ok = [](int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; };
+  if (!ok(d_k) || !ok(d_v)) return false;
+  if (d_k == d_v) return true;
+  return !options && d_k != 96;
 }
 
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
@@ -323,18 +325,23 @@ hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, 
   const DecodeArgs a{q, k, v, S, A, o, opt.eps, opt.u, opt.u_scale, refresh ? 1 : 0, opt.refresh_eta,
                      opt.normalise_output, opt.feature_map, opt.zkey0, opt.zkey_T};
   const bool bf = io_dtype == 1;
-  switch (d * 1000 + d_v) {
-    case 16016: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);
-    case 32032: return bf ? launch<32, uint16_t>(a, n_heads, stream) : launch<32, float>(a, n_heads, stream);
-    case 64064: return bf ? launch<64, uint16_t>(a, n_heads, stream) : launch<64, float>(a, n_heads, stream);
-    case 96096: return bf ? launch<96, uint16_t>(a, n_heads, stream) : launch<96, float>(a, n_heads, stream);
-    case 128128: return bf ? launch<128, uint16_t>(a, n_heads, stream) : launch<128, float>(a, n_heads, stream);
-    case 16032: return launch_rect<16, 32>(a, n_heads, io_dtype, stream);
-    case 32016: return launch_rect<32, 16>(a, n_heads, io_dtype, stream);
-    case 32064: return launch_rect<32, 64>(a, n_heads, io_dtype, stream);
-    case 64032: return launch_rect<64, 32>(a, n_heads, io_dtype, stream);
-    case 64128: return launch_rect<64, 128>(a, n_heads, io_dtype, stream);
-    case 128064: return launch_rect<128, 64>(a, n_heads, io_dtype, stream);
+  if (d != d_v) {
+    switch (d * 1000 + d_v) {
+#define VLA_RECT(DK, DVV) case DK * 1000 + DVV: return launch_rect<DK, DVV>(a, n_heads, io_dtype, stream);
+      VLA_RECT(16, 32) VLA_RECT(16, 64) VLA_RECT(16, 96) VLA_RECT(16, 128)
+      VLA_RECT(32, 16) VLA_RECT(32, 64) VLA_RECT(32, 96) VLA_RECT(32, 128)
+      VLA_RECT(64, 16) VLA_RECT(64, 32) VLA_RECT(64, 96) VLA_RECT(64, 128)
+      VLA_RECT(128, 16) VLA_RECT(128, 32) VLA_RECT(128, 64) VLA_RECT(128, 96)
+#undef VLA_RECT
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (d) {
+    case 16: return bf ? launch<16, uint16_t>(a, n_heads, stream) : launch<16, float>(a, n_heads, stream);
+    case 32: return bf ? launch<32, uint16_t>(a, n_heads, stream) : launch<32, float>(a, n_heads, stream);
+    case 64: return bf ? launch<64, uint16_t>(a, n_heads, stream) : launch<64, float>(a, n_heads, stream);
+    case 96: return bf ? launch<96, uint16_t>(a, n_heads, stream) : launch<96, float>(a, n_heads, stream);
+    case 128: return bf ? launch<128, uint16_t>(a, n_heads, stream) : launch<128, float>(a, n_heads, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -217,15 +217,16 @@ constexpr int kTileG = 16;
 
 __device__ __forceinline__ float elu1(float x) { return x > 0.0f ? x + 1.0f : expf(x); }
 
-template <int D, typename IO>
-__global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
-  constexpr int NT = 2 * D;
+// D = d_k, DV = d_v as in scan_kernel: threads [0, D) own the rows of A, threads [D, D + DV) the rows of S.
+template <int D, int DV, typename IO>
+__global__ void __launch_bounds__(D + DV) scan_general_kernel(ForwardArgs a) {
+  constexpr int NT = D + DV;
   constexpr int RED_LANES = D < 64 ? D : 64;
   constexpr int NWA = (D + 63) / 64;
 
   __shared__ __align__(16) float qs[kTileG * D];
   __shared__ __align__(16) float ks[kTileG * D];
-  __shared__ __align__(16) float vs[kTileG * D];
+  __shared__ __align__(16) float vs[kTileG * DV];
   __shared__ __align__(16) float us[kTileG * D];
   __shared__ __align__(16) float zb[2][D];   // z' (raw)
   __shared__ __align__(16) float ab[2][D];   // a = A_t k^
@@ -234,7 +235,7 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
 
   const int head = blockIdx.x;
   const int tid = threadIdx.x;
-  const int role = tid / D;
+  const int role = tid < D ? 0 : 1;
   const int i = tid - role * D;
   const int T = a.T;
   const bool has_u = a.u != nullptr;
@@ -243,7 +244,7 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
   {
     const float* src = role == 0 ? a.A0 : a.S0;
     if (src != nullptr) {
-      const float* p = src + (static_cast<size_t>(head) * D + i) * D;
+      const float* p = src + (static_cast<size_t>(head) * (role == 0 ? D : DV) + i) * D;
 #pragma unroll
       for (int j = 0; j < D; j += 4) load4(p + j, &row[j]);
     } else {
@@ -255,11 +256,12 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
   float zkey = (role == 0 && a.zkey0 != nullptr) ? a.zkey0[static_cast<size_t>(head) * D + i] : 0.0f;
 
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(T) * D;
+  const size_t slabv = static_cast<size_t>(head) * static_cast<size_t>(T) * DV;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
-  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  const IO* vh = static_cast<const IO*>(a.v) + slabv;
   const IO* uh = has_u ? static_cast<const IO*>(a.u) + slab : kh;
-  IO* oh = static_cast<IO*>(a.o) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slabv;
   const float eps = a.eps;
 
   for (int t0 = 0; t0 < T; t0 += kTileG) {
@@ -276,7 +278,10 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
       *reinterpret_cast<float4*>(&ks[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
       if (has_u) load4(uh + off, x);  // without a supplied u the penalty direction is the key as used
       *reinterpret_cast<float4*>(&us[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
-      load4(vh + off, x);
+    }
+    for (int idx = tid; idx < nt * (DV / 4); idx += NT) {
+      float x[4];
+      load4(vh + static_cast<size_t>(t0) * DV + static_cast<size_t>(idx) * 4, x);
       *reinterpret_cast<float4*>(&vs[idx * 4]) = make_float4(x[0], x[1], x[2], x[3]);
     }
     __syncthreads();
@@ -386,7 +391,7 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
 #pragma unroll
         for (int w = 0; w < NWA; ++w) { aa += red2[par][w][0]; aq += red2[par][w][1]; }
         const float inv_an = 1.0f / fmaxf(sqrtf(aa), eps);
-        const float e = vs[tt * D + i] - mv * inv_nk;
+        const float e = vs[tt * DV + i] - mv * inv_nk;
         const float gcoef = e * inv_an;
         const float4* a4 = reinterpret_cast<const float4*>(&ab[par][0]);
 #pragma unroll
@@ -399,14 +404,14 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
         }
         float ov = fmaf(gcoef, aq, rv);
         if (a.normalise_output) ov /= fmaxf(qz, eps);
-        store1(oh + static_cast<size_t>(t0 + tt) * D + i, ov);
+        store1(oh + static_cast<size_t>(t0 + tt) * DV + i, ov);
       }
     }
   }
 
   float* dst = role == 0 ? a.A_T : a.S_T;
   if (dst != nullptr) {
-    float* p = dst + (static_cast<size_t>(head) * D + i) * D;
+    float* p = dst + (static_cast<size_t>(head) * (role == 0 ? D : DV) + i) * D;
 #pragma unroll
     for (int j = 0; j < D; j += 4) {
       *reinterpret_cast<float4*>(p + j) = make_float4(row[j], row[j + 1], row[j + 2], row[j + 3]);
@@ -415,12 +420,12 @@ __global__ void __launch_bounds__(2 * D) scan_general_kernel(ForwardArgs a) {
   if (role == 0 && a.zkey_T != nullptr) a.zkey_T[static_cast<size_t>(head) * D + i] = zkey;
 }
 
-template <int D, typename IO>
+template <int D, int DV, typename IO>
 hipError_t launch_general(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_general_kernel<D, IO>), dim3(a.n_heads),
-                         dim3(2 * D), params, 0, stream);
+  return hipLaunchKernel(reinterpret_cast<const void*>(&scan_general_kernel<D, DV, IO>), dim3(a.n_heads),
+                         dim3(D + DV), params, 0, stream);
 }
 
 template <int D, int DV, typename IO>
@@ -433,47 +438,49 @@ hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
                          dim3(D + DV), params, 0, stream);
 }
 template <int D, int DV>
-hipError_t launch_io(const ForwardArgs& a, int io_dtype, hipStream_t stream) {
+hipError_t launch_pair(const ForwardArgs& a, int io_dtype, bool general, hipStream_t stream) {
+  if (general) {
+    return io_dtype == 1 ? launch_general<D, DV, uint16_t>(a, stream) : launch_general<D, DV, float>(a, stream);
+  }
   return io_dtype == 1 ? launch<D, DV, uint16_t>(a, stream) : launch<D, DV, float>(a, stream);
+}
+template <int D>
+hipError_t launch_dk(const ForwardArgs& a, int d_v, int io_dtype, bool general, hipStream_t stream) {
+  switch (d_v) {
+    case 16: return launch_pair<D, 16>(a, io_dtype, general, stream);
+    case 32: return launch_pair<D, 32>(a, io_dtype, general, stream);
+    case 64: return launch_pair<D, 64>(a, io_dtype, general, stream);
+    case 96: return launch_pair<D, 96>(a, io_dtype, general, stream);
+    case 128: return launch_pair<D, 128>(a, io_dtype, general, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+hipError_t launch_any(const ForwardArgs& a, int d_k, int d_v, int io_dtype, bool general, hipStream_t stream) {
+  switch (d_k) {
+    case 16: return launch_dk<16>(a, d_v, io_dtype, general, stream);
+    case 32: return launch_dk<32>(a, d_v, io_dtype, general, stream);
+    case 64: return launch_dk<64>(a, d_v, io_dtype, general, stream);
+    case 96: return launch_dk<96>(a, d_v, io_dtype, general, stream);
+    case 128: return launch_dk<128>(a, d_v, io_dtype, general, stream);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
-// Square heads of every supported size, and value heads half or twice as wide as the key heads.
+// Every pair of key and value head sizes out of 16, 32, 64, 96, 128, with or without the optional lines of
+// Algorithm 1.
 bool scan_supported(int d_k, int d_v) {
-  if (d_k == d_v) return d_k == 16 || d_k == 32 || d_k == 64 || d_k == 96 || d_k == 128;
-  const bool pow2 = (d_k == 16 || d_k == 32 || d_k == 64 || d_k == 128) &&
-                    (d_v == 16 || d_v == 32 || d_v == 64 || d_v == 128);
-  return pow2 && (d_v == 2 * d_k || d_k == 2 * d_v);
+  const auto ok = [](int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; };
+  return ok(d_k) && ok(d_v);
 }
 
 hipError_t launch_scan(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
-  switch (d_k * 1000 + d_v) {
-    case 16016: return launch_io<16, 16>(a, io_dtype, stream);
-    case 32032: return launch_io<32, 32>(a, io_dtype, stream);
-    case 64064: return launch_io<64, 64>(a, io_dtype, stream);
-    case 96096: return launch_io<96, 96>(a, io_dtype, stream);
-    case 128128: return launch_io<128, 128>(a, io_dtype, stream);
-    case 16032: return launch_io<16, 32>(a, io_dtype, stream);
-    case 32016: return launch_io<32, 16>(a, io_dtype, stream);
-    case 32064: return launch_io<32, 64>(a, io_dtype, stream);
-    case 64032: return launch_io<64, 32>(a, io_dtype, stream);
-    case 64128: return launch_io<64, 128>(a, io_dtype, stream);
-    case 128064: return launch_io<128, 64>(a, io_dtype, stream);
-    default: return hipErrorInvalidValue;
-  }
+  return launch_any(a, d_k, d_v, io_dtype, false, stream);
 }
 
-hipError_t launch_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
-  const bool bf = io_dtype == 1;
-  switch (d) {
-    case 16: return bf ? launch_general<16, uint16_t>(a, stream) : launch_general<16, float>(a, stream);
-    case 32: return bf ? launch_general<32, uint16_t>(a, stream) : launch_general<32, float>(a, stream);
-    case 64: return bf ? launch_general<64, uint16_t>(a, stream) : launch_general<64, float>(a, stream);
-    case 96: return bf ? launch_general<96, uint16_t>(a, stream) : launch_general<96, float>(a, stream);
-    case 128: return bf ? launch_general<128, uint16_t>(a, stream) : launch_general<128, float>(a, stream);
-    default: return hipErrorInvalidValue;
-  }
+hipError_t launch_scan_general(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
+  return launch_any(a, d_k, d_v, io_dtype, true, stream);
 }
 
 }  // namespace vla

@@ -120,8 +120,9 @@ def call(**kw):
     (dict(S_T=FAKE + 0x6000, A_T=FAKE + 0x6200), 1),  # the two state outputs inside each other
     (dict(zkey0=FAKE + 0x7000, zkey_T=FAKE + 0x7010, normalise_output=1), 1),
     (dict(mode=3, d_k=64, d_v=64, workspace=FAKE + 0x2800, workspace_bytes=1 << 20), 1),   # workspace over v and o
-    (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=64), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
-    (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4), 2),   # rectangular: plain kernels only
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=48), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
+    (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4, mode=2), 2),   # rectangular heads with
+    (dict(d_k=96, d_v=64, mode=2), 2), (dict(d_k=128, d_v=32, mode=2), 2),                     # options: scan only
     (dict(d_k=64, d_v=128, mode=3), 2), (dict(d_k=128, d_v=64, mode=4), 2),
 ])
 def test_host_side_validation_returns_status_without_launch(kw, status):
@@ -144,7 +145,7 @@ def decode_call(**kw):
     (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
     (dict(o=FAKE + 0x1000 + 0x20), 1), (dict(A=FAKE + 0x4100), 1),      # o inside k; A inside S (1024 bytes)
     (dict(o=FAKE + 0x4000 + 0x3f0), 1), (dict(u=FAKE + 0x3000 - 0x10), 1),   # o inside S; u ends inside o
-    (dict(d_k=48, d_v=48), 2), (dict(d_k=32, d_v=128), 2),
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=96, d_v=32), 2),
     (dict(d_k=32, d_v=64, refresh_period=2), 2), (dict(d_k=64, d_v=32, feature_map=1), 2),   # rectangular: no options
     (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1), (dict(refresh_period=-2), 1),   # option arguments are checked too
 ])
@@ -173,8 +174,18 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
     assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 16, 64, vla.VLA_BF16) == -1
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == -1
+    # every pair of head sizes runs: on the block kernel where the waves of a head can share out the rows of S in
+    # whole tiles, else on the scan kernel; with options other than the feature map always on the scan kernel
+    assert vla.resolve_mode(4, 4, 4096, 16, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 64, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 128, 32, vla.VLA_BF16) == vla.MODE_SCAN
+    assert vla.resolve_mode(4, 4, 4096, 96, 64, vla.VLA_BF16) == vla.MODE_SCAN
+    assert vla.resolve_mode(4, 4, 4096, 64, 16, vla.VLA_BF16) == vla.MODE_SCAN
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_SCAN
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, u=FAKE, refresh_period=20) == vla.MODE_SCAN
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == -1
+    assert vla.resolve_mode(4, 4, 4096, 32, 48, vla.VLA_BF16) == -1
 
 
 def test_time_parallel_workspace_follows_the_segment_plan():

@@ -372,10 +372,22 @@ def test_forward_can_be_captured_in_a_hip_graph_and_replayed(mode, shape):
             assert torch.equal(g, e), rep
 
 
+SIZES = (16, 32, 64, 96, 128)
+RECT_PAIRS = [(dk, dv) for dk in SIZES for dv in SIZES if dk != dv]
+
+
+def block_kernel_takes(dk, dv):
+    """The waves of a head (d_k / 32, one below 32) share out the d_v rows of S in whole 16-row tiles."""
+    if dk == 96:
+        return False
+    return dv % (16 * max(dk // 32, 1)) == 0
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("dk,dv", [(16, 32), (32, 16), (32, 64), (64, 32), (64, 128), (128, 64)])
-def test_value_heads_half_or_twice_as_wide_as_key_heads(dk, dv, dtype):
-    """d_k != d_v: S is d_v x d_k, A is d_k x d_k (Section 3.3 only fixes the shapes through o = S q)."""
+@pytest.mark.parametrize("dk,dv", RECT_PAIRS)
+def test_value_heads_of_another_size_than_the_key_heads(dk, dv, dtype):
+    """d_k != d_v: S is d_v x d_k, A is d_k x d_k (Section 3.3 only fixes the shapes through o = S q).  Every pair
+    of sizes runs on the scan kernel; the block kernel takes those whose S rows split into whole tiles per wave."""
     import torch
 
     import paper_2605_11196_amd as vla
@@ -393,7 +405,10 @@ def test_value_heads_half_or_twice_as_wide_as_key_heads(dk, dv, dtype):
     tq, tk, tv = (torch.from_numpy(x).to(dev).to(tdt) for x in (q, k, v))
     io = vla.VLA_F32 if dtype == "f32" else vla.VLA_BF16
     modes = [m for m in (None, 1, 2) if m is None or vla.resolve_mode(B, H, T, dk, dv, io, mode=m) == m]
-    assert modes == [None, 1, 2] and vla.resolve_mode(B, H, T, dk, dv, io) == 2
+    if block_kernel_takes(dk, dv):
+        assert modes == [None, 1, 2] and vla.resolve_mode(B, H, T, dk, dv, io) == 2
+    else:
+        assert modes == [None, 1] and vla.resolve_mode(B, H, T, dk, dv, io) == 1
     for mode in modes:
         o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1, mode=mode)
         torch.cuda.synchronize()
@@ -403,7 +418,7 @@ def test_value_heads_half_or_twice_as_wide_as_key_heads(dk, dv, dtype):
                     A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
         print(dk, dv, dtype, mode, errs)
         assert max(errs.values()) <= TOL[dtype], (mode, errs)
-    if True:   # the block kernel carries the feature map for these shapes too
+    if True:   # the feature map: on the block kernel where it takes the shape, else on the scan kernel
         ref = oracle.forward(q, k, v, S0, None, lambda0=0.1, feature_map=True)
         o, S_T, A_T = vla.vla_forward(tq, tk, tv, torch.from_numpy(S0).to(dev), None, lambda0=0.1,
                                       feature_map=True)
@@ -422,7 +437,7 @@ def test_block_modes_hold_the_float32_tolerance_on_long_sequences(d, T):
     for shapes without a block kernel.)"""
     q, k, v = vla_inputs.gaussian_qkv(1, 2, T, d, seed=9)
     ref = oracle.forward(q, k, v, lambda0=0.1)
-    for mode in ((2, 3, 4) if d != 96 else (2,)):
+    for mode in (2, 3, 4):
         o, S_T, A_T = gpu_forward(q, k, v, mode=mode)
         errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(S_T, ref["S_T"], 2),
                     A=slab_rel_err(A_T, ref["A_T"], 2))
@@ -471,3 +486,31 @@ def test_many_small_heads_share_a_workgroup(d, B, H, T, dtype):
     print(d, B * H, T, dtype, errs)
     errs, _, _ = check_parity(q[:, :, :16], k[:, :, :16], v[:, :, :16], dtype=dtype, mode=2)
     print(d, B * H, 16, dtype, errs)
+
+
+@pytest.mark.parametrize("dk,dv", [(32, 128), (64, 96), (128, 16), (96, 32), (16, 64)])
+def test_options_on_heads_with_another_value_size(dk, dv):
+    """Every optional line of Algorithm 1 with d_k != d_v: the token-by-token kernel carries them (AUTO routes
+    there), carried key sum and refresh phase included."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, T = 1, 3, 77
+    rng = np.random.default_rng(50 + dk + dv)
+    q, k, u = (rng.standard_normal((B, H, T, dk)).astype(np.float32) for _ in range(3))
+    v = rng.standard_normal((B, H, T, dv)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
+    z0 = np.abs(rng.standard_normal((B, H, dk))).astype(np.float32)
+    opt = dict(lambda0=0.1, u_scale=dk ** -0.5, refresh_period=7, refresh_eta=1e-2, step_offset=3,
+               normalise_output=True, feature_map=True)
+    ref = oracle.forward(q, k, v, S0, None, u=u, zkey0=z0, **opt)
+    dev = torch.device("cuda:0")
+    t = lambda x: torch.from_numpy(x).to(dev)
+    assert vla.resolve_mode(B, H, T, dk, dv, vla.VLA_F32, refresh_period=7) == 1
+    o, S_T, A_T, zk = vla.vla_forward(t(q), t(k), t(v), t(S0), None, u=t(u), zkey0=t(z0), return_zkey=True, **opt)
+    torch.cuda.synchronize()
+    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A_T), ref["A_T"], 2), z=slab_rel_err(to_np(zk), ref["zkey_T"], 1))
+    print(dk, dv, errs)
+    assert max(errs.values()) <= 1e-4, errs
