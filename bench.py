@@ -34,7 +34,8 @@ MODE_NAMES = {1: "scan", 2: "chunked", 3: "two_phase", 4: "time_parallel"}
 # summary, valid for that shape and mode only; every other case reports null.
 PROFILED_TRAFFIC_BYTES = {
     # (B, H, T, d_h, io dtype, resolved mode): (bytes per launch, summary)
-    (64, 32, 8192, 128, "bf16", 2): (17044037 * 1024, "profiles/chunk_kernel_large_batch_hbm_traffic.txt"),
+    (64, 32, 8192, 128, "bf16", 2): (17045169 * 1024, "profiles/chunk_kernel_large_batch_hbm_traffic.txt"),
+    (1, 16, 131072, 64, "bf16", 4): (4940685 * 1024, "profiles/time_parallel_long_context_hbm_traffic.txt"),
 }
 
 
@@ -54,10 +55,11 @@ def parse_args():
     ap.add_argument("--decode", action="store_true",
                     help="time vla_decode_step (one token for every head of the workload, state in place) "
                          "instead of vla_forward; the roofline is then the HBM one")
-    ap.add_argument("--options", default="none", choices=["none", "paper"],
+    ap.add_argument("--options", default="none", choices=["none", "paper", "paper_no_refresh"],
                     help="'paper': switch on every optional line of Algorithm 1 (separate penalty directions u "
                          "with u_scale = 1/sqrt(d_h), identity refresh every 20 steps, normalised read-out, "
-                         "ELU+1 features); the flop count per head-token is then 12 d^2")
+                         "ELU+1 features); the flop count per head-token is then 12 d^2.  'paper_no_refresh': the "
+                         "same without the identity refresh (what the time-parallel mode carries)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true",
                     help="print the headline entry only (the secondary entries belong to the default workload)")
@@ -136,12 +138,13 @@ def forward_case(c, *, mode=0, segments=None, options="none", steps=10, warmup=3
                    for x in vla_inputs.gaussian_qkv(B, H, T, d, c["seed"], c["std"]))
     extra = {}
     u = None
-    if options == "paper":
+    if options != "none":
         gen_u = torch.Generator(device=dev)
         gen_u.manual_seed(c["seed"] + 1000)
         u = torch.randn(B, H, T, d, device=dev, generator=gen_u).to(tdt)
-        extra = dict(u=u.data_ptr(), u_scale=d ** -0.5, refresh_period=20, refresh_eta=1e-3,
-                     normalise_output=1, feature_map=1)
+        extra = dict(u=u.data_ptr(), u_scale=d ** -0.5, normalise_output=1, feature_map=1)
+        if options == "paper":
+            extra.update(refresh_period=20, refresh_eta=1e-3)
     o = torch.empty_like(v)
     S_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
     A_T = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
@@ -174,8 +177,8 @@ def forward_case(c, *, mode=0, segments=None, options="none", steps=10, warmup=3
     head_tokens = B * H * T
     # algorithmic work per launch: 5 d^2 FMA per head-token (6 d^2 with separate penalty directions); q, k, v
     # (and u) read and o written once, S_T and A_T written once per head
-    flops = (12.0 if options == "paper" else 10.0) * d * d * head_tokens
-    n_streams = 5 if options == "paper" else 4
+    flops = (12.0 if options != "none" else 10.0) * d * d * head_tokens
+    n_streams = 5 if options != "none" else 4
     io_bytes = (2 if dtype == "bf16" else 4) * n_streams * d * head_tokens + B * H * 2 * d * d * 4
     tflops = flops / avg_s / 1e12
     traffic, traffic_src = PROFILED_TRAFFIC_BYTES.get((B, H, T, d, dtype, resolved), (None, None))
@@ -185,6 +188,8 @@ def forward_case(c, *, mode=0, segments=None, options="none", steps=10, warmup=3
                 f"lambda0={c['lambda0']}")
     if options == "paper":
         workload += ", every option of Algorithm 1 on (u with u_scale=1/sqrt(d_h), refresh 20, normalised, ELU+1)"
+    elif options == "paper_no_refresh":
+        workload += ", options of Algorithm 1 on (u with u_scale=1/sqrt(d_h), normalised, ELU+1; no refresh)"
     res = {
         "workload": workload, "io_dtype": dtype, "kernel_mode": MODE_NAMES.get(resolved, str(resolved)),
         "B": B, "H": H, "T": T, "d": d, "head_tokens": head_tokens, "steps": steps, "warmup": warmup,
@@ -209,9 +214,10 @@ def forward_case(c, *, mode=0, segments=None, options="none", steps=10, warmup=3
         qs, ks, vs = (pick(x).astype(np.float64) for x in (q, k, v))
         oracle.load()
         oracle_opt = {}
-        if options == "paper":
+        if options != "none":
             oracle_opt = dict(u=pick(u).astype(np.float64), u_scale=extra["u_scale"],
-                              refresh_period=extra["refresh_period"], refresh_eta=extra["refresh_eta"],
+                              refresh_period=extra.get("refresh_period", 0),
+                              refresh_eta=extra.get("refresh_eta", 1e-3),
                               normalise_output=True, feature_map=True)
         tc0 = time.perf_counter()
         ref = oracle.forward(qs, ks, vs, lambda0=c["lambda0"], **oracle_opt)
@@ -299,8 +305,9 @@ def decode_case(c, *, steps=10, warmup=3, oracle_heads=0):
 
 def secondary_entry(name, r):
     rf = r["roofline"]
-    e = {"name": name, "workload": r["workload"], "kernel_mode": r["kernel_mode"],
-         "value": sig(r["value"]), "unit": "head-tokens/s", "steps": r["steps"], "warmup": r["warmup"],
+    e = {"name": name, "shape": f"B={r['B']} H={r['H']} T={r['T']} d_h={r['d']} {r['io_dtype']}",
+         "kernel_mode": r["kernel_mode"],
+         "value": sig(r["value"]), "unit": "head-tokens/s", "steps": r["steps"],
          "ms_per_step": sig(r["ms_per_step"]), "kernel_ms": sig(rf["kernel_ms"]),
          "kernel_ms_median": sig(rf["kernel_ms_median"]),
          "roofline": {"bound": rf["bound"], "achieved": sig(rf["achieved"]), "peak": rf["peak"],
@@ -367,6 +374,8 @@ def main():
         for T in make_case("long_context")["T_sweep"]:
             sec.append(secondary_entry(f"long_context_T{T}", forward_case(
                 make_case("long_context", T=T), steps=k2, warmup=w2, oracle_heads=2)))
+        sec.append(secondary_entry("long_context_T131072_options_no_refresh", forward_case(
+            make_case("long_context", T=131072), options="paper_no_refresh", steps=k2, warmup=w2, oracle_heads=2)))
         sec.append(secondary_entry("large_batch_options_paper", forward_case(
             make_case("large_batch"), options="paper", steps=k2, warmup=w2, oracle_heads=4)))
         sec.append(secondary_entry("decode_large_batch_heads", decode_case(
