@@ -125,18 +125,20 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
     return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
   }
   const long long heads = static_cast<long long>(B) * H;
-  // measured crossover at T = 16384: 64 heads at d = 128 (4.5 against 7.7 ms; 128 heads 8.2 against 7.7),
-  // 128 heads at d = 64 (2.8 against 5.0 ms; 256 heads 5.3 against 5.0), 256 heads at d = 32 (2.7 against
-  // 4.5 ms; 512 heads 5.1 against 4.5)
-  // d = 96 (its Gram sums and boundary inverses run in the d = 128 layout): 64 heads 3.5 against 6.5 ms, 128 heads
-  // 6.3 against 6.5
-  const long long few = d >= 96 ? 64 : (d >= 64 ? 128 : 256);
-  // short sequences: 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads 0.19 against 0.17;
-  // at d = 96 the crossover sits one octave higher (T = 1024: 16 heads 0.29 against 0.41 ms, 64 heads 0.43
-  // against 0.41; T = 512: 16 heads 0.26 against 0.21)
+  // Measured crossovers against the fused block kernel (bf16, one MI355X).  Long sequences, T = 2048 / 16384:
+  //   d = 128:  64 heads 0.85 / 4.2 against 0.96 / 7.6 ms,  96 heads 1.27 / 6.3 against 0.96 / 7.7
+  //   d =  96:  64 heads 0.69 / 3.5 against 0.82 / 6.5,     96 heads 1.05 / 5.1 against 0.82 / 6.5
+  //   d =  64: 192 heads 0.57 / 3.5 against 0.63 / 5.0,    256 heads 0.70 / 4.6 against 0.62 / 5.0
+  //   d =  32: 512 heads 0.53 / 3.8 against 0.57 / 4.5,    768 heads 0.58 / 4.5 against 0.58 / 4.6
+  const long long few = d >= 96 ? 64 : (d >= 64 ? 192 : 512);
+  // Short sequences (half the length): 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads
+  // 0.19 against 0.17.  At d = 96 (Gram sums and boundary inverses in the d = 128 layout) the crossover sits one
+  // octave higher (T = 1024: 16 heads 0.29 against 0.41 ms, 64 heads 0.43 against 0.41; T = 512: 16 heads 0.26
+  // against 0.21).
+  const long long few_short = d >= 96 ? 32 : (d >= 64 ? 64 : 128);
   const int t_long = d == 96 ? 2048 : 1024;
-  const bool long_enough = T >= t_long || (2 * T >= t_long && 2 * heads <= few);
-  if (heads <= few && long_enough) return VLA_MODE_TIME_PARALLEL;
+  const bool take = T >= t_long ? heads <= few : (2 * T >= t_long && heads <= few_short);
+  if (take) return VLA_MODE_TIME_PARALLEL;
   return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
 }
 
