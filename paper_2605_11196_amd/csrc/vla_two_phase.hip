@@ -28,9 +28,20 @@ namespace {
 
 // ------------------------------------------------------------------------------------------ phase 1
 // Two-wave workgroups (d <= 64) are compiled for three waves per SIMD.
-template <int D, int NW, typename IO>
-__global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(ForwardArgs a) {
+//
+// MAPF (time-parallel mode, d <= 64): the workgroup also forms the affine map S_end = S_start P + Q of its
+// segment, which the composition of the segment-start states needs.  Rows of S are independent, so P is what the
+// rows of the identity evolve into with v = 0 and Q what a zero state evolves into with the real v; both run here
+// one block behind the A chain, on the operands that are still in LDS (K^ and W of the previous block in a second
+// copy, Z and c from the C x C pass), instead of in a pass of their own that reads them back from the workspace.
+// The 2 d/16 row slabs of 16 rows are dealt out over the waves.
+template <int D, int NW, typename IO, bool MAPF = false>
+__global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_kernel(ForwardArgs a) {
   static_assert(NW >= 2, "the C x C pass of the previous block runs on a second wave");
+  constexpr int NKB = MAPF ? 2 : 1;            // copies of K^ and W in LDS
+  constexpr int NSLAB = D / 16;                // 16-row slabs of a d x d state
+  constexpr int SPW = 2 * NSLAB / NW;          // slabs of the map (Q run, then P run) per wave
+  static_assert(!MAPF || (2 * NSLAB) % NW == 0, "whole slabs per wave");
   constexpr int SL = D / NW;
   constexpr int NJ = SL / 16;
   constexpr int NB = D / 16;
@@ -46,11 +57,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
   static_assert(EPT % 4 == 0 && TPR <= 16 && (TPR & (TPR - 1)) == 0 && C * TPR <= NT && D % EPT == 0 &&
                 D / EPT <= TPR, "staging layout");
 
-  __shared__ __align__(16) float Ks[C * LD];
+  __shared__ __align__(16) float Ksb[NKB][C * LD];
   __shared__ __align__(16) float Qs[C * LD];
   __shared__ __align__(16) float Ys[C * LD];
-  __shared__ __align__(16) float Wb[D * LT];
+  __shared__ __align__(16) float Wbb[NKB][D * LT];
   __shared__ __align__(16) float Gp[NW][2][C * LT];
+  // MAPF: Z [t][s] and -c of the previous block live in Y^T's array, which is dead between barrier (2) of a block
+  // and the first barrier of the next one: exactly the window in which they are written and read (four
+  // workgroups of 40 KB share a compute unit; separate arrays would make it three)
+  static_assert(C * LD >= C * LT + C, "Z and c fit the Y^T array");
+  float* const Zs = Ys;
+  float* const cvs = Ys + C * LT;
   // kept for one more block (two copies, by block parity): the wave that turns them into c, Z, NQ reads the
   // previous block's while the factorisation of the current block writes its own
   __shared__ __align__(16) float Lis[2][C * LT];   // L^{-1} [t][s]
@@ -160,14 +177,85 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
 #pragma unroll
       for (int t = 0; t < C; ++t) smb[t * C + c] = Zr[t];
       smb[2 * C * C + c] = -cs;
+      if constexpr (MAPF) {
+#pragma unroll
+        for (int t = 0; t < C; ++t) Zs[t * LT + c] = Zr[t];
+        cvs[c] = -cs;
+      }
     }
     *reinterpret_cast<f4*>(smb + C * C + c * C + 4 * g) = nq;  // -NQ^T[t = c][s = 4g + r]
+  };
+
+  // ---- the segment's affine map (MAPF): mst[i][b][r] = X[row0_i + c][16b + 4g + r] for this wave's slabs
+  const bool do_map = MAPF && seg != a.n_seg - 1;   // nothing follows the last segment
+  const IO* vh = static_cast<const IO*>(a.v) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
+  f4 mst[MAPF ? SPW : 1][NB];
+  IO vcur[MAPF ? SPW : 1][4], vnext[MAPF ? SPW : 1][4];
+  if constexpr (MAPF) {
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const int sl = w + NW * i;                       // slab: Q run for sl < NSLAB, then P run
+      const bool p_run = sl >= NSLAB;
+      const int row0 = (sl % NSLAB) * 16;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mst[i][b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+    }
+  }
+  // v of the block starting at t0 in accumulator layout, for the Q-run slabs (rows past the end: the last row)
+  auto load_map_v = [&](int t0, IO (&vv)[MAPF ? SPW : 1][4]) {
+    if constexpr (MAPF) {
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const int sl = w + NW * i;
+        if (sl < NSLAB) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int t = t0 + 4 * g + r;
+            vv[i][r] = vh[static_cast<size_t>(t < T ? t : T - 1) * D + sl * 16 + c];
+          }
+        }
+      }
+    }
+  };
+  // one block of the S recurrence on this wave's slabs: operands of the block in LDS copy `kb`
+  auto map_step = [&](int t0, int kb, const IO (&vv)[MAPF ? SPW : 1][4]) {
+    if constexpr (MAPF) {
+      const f4 za = lds4(&Zs[c * LT + 4 * g]);
+      const f4 cg = lds4(&cvs[4 * g]);
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const int sl = w + NW * i;
+        f4 ft;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ft[r] = (sl < NSLAB && t0 + 4 * g + r < T) ? neg_widen(vv[i][r]) : 0.0f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const f4 ka = lds4(&Ksb[kb][c * LD + 16 * b + 4 * g]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], mst[i][b][r], ft);
+        }
+        f4 et = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
+        const f4 ce = et * cg;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const f4 wa = lds4(&Wbb[kb][(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) mst[i][b] = mfma16(wa[r], ce[r], mst[i][b]);
+        }
+      }
+    }
   };
 
   int blk = seg * a.seg_blocks;
   int it = 0;   // blocks done by this workgroup
   for (int t0 = tb; t0 < T; t0 += C, ++blk, ++it) {
     const int pb = it & 1;
+    float* Ks = Ksb[MAPF ? pb : 0];
+    float* Wb = Wbb[MAPF ? pb : 0];
     // ---- stage K^ and Q (LDS); 1 / max(||k||, eps) per token goes to the workspace
     if (stage_wave) {
       float kx[EPT];
@@ -214,6 +302,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
     }
     __syncthreads();  // (1)
     if (t0 + C < T) prefetch(t0 + C);
+    if (do_map) load_map_v(t0, vnext);   // consumed one block later
 
     // ---- Y^T = K^ A0 and the partial Gram matrices
     f4 yt[NJ];
@@ -317,6 +406,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
+    // ---- the map, one block behind: Z and c of block it - 1 were formed before barrier (3), its K^ and W sit in
+    //      the other LDS copy, which is not written again before barrier (4)
+    if constexpr (MAPF) {
+      if (do_map) {
+        if (it > 0) map_step(t0 - C, pb ^ 1, vcur);
+#pragma unroll
+        for (int i = 0; i < SPW; ++i)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) vcur[i][r] = vnext[i][r];
+      }
+    }
     __syncthreads();  // (4)
 
     // ---- A -= W W^T
@@ -331,6 +431,21 @@ __global__ void __launch_bounds__(64 * NW, NW == 2 ? 3 : 2) a_scan_kernel(Forwar
   }
   // c, Z, NQ of the last block: everything it needs was written before the last barrier
   if (it > 0 && w == it % NW) cz_pass((it - 1) & 1, SMp + static_cast<size_t>(blk - 1) * SMB);
+  if constexpr (MAPF) {
+    if (do_map && it > 0) {   // uniform over the workgroup
+      __syncthreads();        // Z and c of the last block
+      map_step((blk - 1) * C, (it - 1) & 1, vcur);
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const int sl = w + NW * i;
+        float* out = a.seg_PQ + (static_cast<size_t>(blockIdx.x) * 2 + (sl >= NSLAB ? 0 : 1)) * D * D;
+        const int row0 = (sl % NSLAB) * 16;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          *reinterpret_cast<f4*>(out + (row0 + c) * D + 16 * b + 4 * g) = mst[i][b];
+      }
+    }
+  }
 
   if (a.A_T && seg == a.n_seg - 1) {
     float* AT = a.A_T + static_cast<size_t>(head) * D * D;
@@ -801,9 +916,16 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   // A separate penalty direction or the normalised read-out: the A chain of the block kernel that carries
   // them; its records have the layout the S-row kernels below read.
   const bool general = a.u != nullptr || a.normalise_output != 0 || a.zkey0 != nullptr || a.zkey_T != nullptr;
+  // Up to d = 64 the plain A scan also forms the per-segment affine maps of S (its registers hold them beside A).
+  constexpr bool kFusedMap = D <= 64;
+  const bool fused_map = kFusedMap && !general && a.n_seg > 1;
+  const void* scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, false>);
+  if constexpr (kFusedMap) {
+    if (fused_map) scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, true>);
+  }
   hipError_t err = general ? launch_a_scan_general(a, D, std::is_same<IO, uint16_t>::value ? 1 : 0, stream)
-                           : hipLaunchKernel(reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO>),
-                                             dim3(static_cast<unsigned>(hs)), dim3(64 * NW), params, 0, stream);
+                           : hipLaunchKernel(scan_fn, dim3(static_cast<unsigned>(hs)), dim3(64 * NW), params, 0,
+                                             stream);
   if (err != hipSuccess) return err;
   // With enough (head, segment) pairs to fill the chip the block operands are shared through LDS by a
   // workgroup per pair; with few, one wave per slab of S and deep register prefetch give the most waves.
@@ -814,8 +936,10 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   };
   if (a.n_seg > 1) {
     // the state of S at the segment boundaries: per-segment affine maps, then their composition
-    err = rows(std::true_type{});
-    if (err != hipSuccess) return err;
+    if (!fused_map) {
+      err = rows(std::true_type{});
+      if (err != hipSuccess) return err;
+    }
     err = launch_combine(a, D, const_cast<float*>(a.seg_S), stream);
     if (err != hipSuccess) return err;
   }
