@@ -35,7 +35,7 @@ MODE_NAMES = {1: "scan", 2: "chunked", 3: "two_phase", 4: "time_parallel"}
 PROFILED_TRAFFIC_BYTES = {
     # (B, H, T, d_h, io dtype, resolved mode): (bytes per launch, summary)
     (64, 32, 8192, 128, "bf16", 2): (17045169 * 1024, "profiles/chunk_kernel_large_batch_hbm_traffic.txt"),
-    (1, 16, 131072, 64, "bf16", 4): (4940685 * 1024, "profiles/time_parallel_long_context_hbm_traffic.txt"),
+    (1, 16, 131072, 64, "bf16", 4): (4013682 * 1024, "profiles/time_parallel_long_context_hbm_traffic.txt"),
 }
 
 
