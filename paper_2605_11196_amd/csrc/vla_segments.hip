@@ -203,31 +203,44 @@ __global__ void __launch_bounds__(kThreads) gram_prefix_kernel(double* G, int n_
 
 // ------------------------------------------------------------------------------------------ key sums
 // Normalised read-out (eq. (output)): zkey_t = zkey_0 + sum_{s<=t} k_s with k_s the key as used before its L2
-// normalisation (after the feature map).  Per (head, segment) the sum of its keys, in float64; thread (rg, j)
-// adds column j of every RG-th token.
+// normalisation (after the feature map).  Per (head, segment) the sum of its keys, in float64; a thread adds eight
+// consecutive columns of every RG-th token, the row groups are summed through LDS.
 template <int D, typename IO>
-__global__ void __launch_bounds__(D * (256 / D)) keysum_kernel(ForwardArgs a, double* part) {
-  constexpr int RG = 256 / D;
+__global__ void __launch_bounds__(kThreads) keysum_kernel(ForwardArgs a, double* part) {
+  constexpr int EPT = 8;                 // consecutive columns per thread: one 16- or 32-byte piece of a row
+  constexpr int TPR = D / EPT;           // threads per token row
+  constexpr int RG = kThreads / TPR;     // rows in flight per pass (the last groups idle when 256 / TPR is no integer)
   __shared__ double red[RG][D];
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
-  const int j = threadIdx.x % D;
-  const int rg = threadIdx.x / D;
+  const int rg = threadIdx.x / TPR;
+  const int j0 = (threadIdx.x % TPR) * EPT;
   const int tb = seg * a.seg_blocks * C;
   const int te = min(a.T, tb + a.seg_blocks * C);
   const IO* kh = static_cast<const IO*>(a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
-  double sum = 0.0;
-  for (int t = tb + rg; t < te; t += RG) {
-    float x = widen(kh[static_cast<size_t>(t) * D + j]);
-    if (a.feature_map) x = elu_plus_one(x);
-    sum += static_cast<double>(x);
-  }
-  red[rg][j] = sum;
-  __syncthreads();
-  if (rg == 0) {
+  double sum[EPT];
 #pragma unroll
-    for (int r = 1; r < RG; ++r) sum += red[r][j];
-    part[static_cast<size_t>(blockIdx.x) * D + j] = sum;
+  for (int e = 0; e < EPT; ++e) sum[e] = 0.0;
+  if (rg < RG) {
+    for (int t = tb + rg; t < te; t += RG) {
+      RawRow<IO, EPT> raw;
+      raw.load(kh + static_cast<size_t>(t) * D + j0);
+      float x[EPT];
+      raw.unpack(x);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        if (a.feature_map) x[e] = elu_plus_one(x[e]);
+        sum[e] += static_cast<double>(x[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) red[rg][j0 + e] = sum[e];
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < D; j += kThreads) {
+    double total = 0.0;
+    for (int r = 0; r < RG; ++r) total += red[r][j];
+    part[static_cast<size_t>(blockIdx.x) * D + j] = total;
   }
 }
 // seg_zkey[h][s] = zkey0[h] + the sums of the segments before s, one thread per (head, column)
@@ -476,7 +489,7 @@ hipError_t launch_keysum_d(const ForwardArgs& a, double* part, float* seg_zkey, 
   ForwardArgs args = a;
   void* params[] = {&args, &part};
   hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(&keysum_kernel<D, IO>),
-                                   dim3(a.n_heads * a.n_seg), dim3(D * (256 / D)), params, 0, stream);
+                                   dim3(a.n_heads * a.n_seg), dim3(kThreads), params, 0, stream);
   if (err != hipSuccess) return err;
   const double* cpart = part;
   const float* z0 = a.zkey0;
