@@ -64,7 +64,7 @@ enum GramTile {
 //       workspace (the layout of vla_mfma_util.h: 1 / ||k_t||, the write directions alpha_t in W's place, Z,
 //       -NQ^T, -c_t and the reciprocal read-out denominators); S, v and o are not touched.
 template <int D, typename IO, bool FULL, bool SCAN>
-__global__ void __launch_bounds__(4 * D) chunk_general_kernel(ForwardArgs a) {
+__global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_general_kernel(ForwardArgs a) {
   constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
   constexpr int NB = D / 16;       // 16-row blocks over the head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
