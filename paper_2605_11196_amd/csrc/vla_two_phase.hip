@@ -918,7 +918,9 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   const bool general = a.u != nullptr || a.normalise_output != 0 || a.zkey0 != nullptr || a.zkey_T != nullptr;
   // Up to d = 64 the plain A scan also forms the per-segment affine maps of S (its registers hold them beside A).
   constexpr bool kFusedMap = D <= 64;
-  const bool fused_map = kFusedMap && !general && a.n_seg > 1;
+  // Worth it once the (head, segment) pairs fill the chip (measured at 16 heads, d = 64: 3 % faster at 1024
+  // pairs, 5 % slower at 512 and below, where a block's latency counts and the maps lengthen it).
+  const bool fused_map = kFusedMap && !general && a.n_seg > 1 && hs >= 768;
   const void* scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, false>);
   if constexpr (kFusedMap) {
     if (fused_map) scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, true>);

@@ -44,6 +44,22 @@ def test_many_head_segment_pairs_take_the_shared_operand_kernels(d, T, segments,
     print(d, T, segments, dtype, errs)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,T,segments", [(64, 300, 8), (32, 277, 8), (64, 16 * 8 + 1, 8), (32, 16 * 16, 8)])
+def test_chip_filling_pair_counts_form_the_maps_inside_the_a_scan(d, T, segments, dtype):
+    """96 heads x 8 segments = 768 (head, segment) pairs: from there on (d <= 64, no options) the A scan forms the
+    per-segment affine maps of S itself, one block behind (two- and three-block segments, a ragged last block, a
+    one-token last segment, a given S0 and A0)."""
+    q, k, v = vla_inputs.gaussian_qkv(6, 16, T, d, seed=1250 + d + T)
+    rng = np.random.default_rng(d + T)
+    S0 = rng.standard_normal((6, 16, d, d)).astype(np.float32)
+    R = rng.standard_normal((6, 16, d, d)) / np.sqrt(d)
+    A0 = (np.eye(d) * 2.0 + R @ np.swapaxes(R, -1, -2)).astype(np.float32)   # symmetric positive definite
+    A0 = (A0 + np.swapaxes(A0, -1, -2)) / 2
+    errs, _, _ = check_parity(q, k, v, S0, A0, dtype=dtype, lambda0=0.1, mode=TP, segments=segments)
+    print(d, T, segments, dtype, errs)
+
+
 @pytest.mark.parametrize("d,T", [(64, 100), (128, 33), (32, 200), (96, 70)])
 def test_two_phase_with_many_heads_takes_the_shared_operand_kernel(d, T):
     q, k, v = vla_inputs.gaussian_qkv(16, 16, T, d, seed=1300 + d)
