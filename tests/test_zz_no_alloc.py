@@ -109,3 +109,46 @@ def test_request_beyond_the_static_array_is_refused_or_rerouted():
     assert rc == 0
     torch.cuda.synchronize()
     assert torch.equal(o, ref)
+
+
+@pytest.mark.parametrize("mode", [4, 0])
+def test_static_entry_point_records_into_a_graph_and_replays(mode):
+    """The callers this entry point is for: under stream capture nothing may allocate.  After one eager call
+    (which looks the array up), the call is recorded into a graph; every replay, with other data in the same
+    input buffers and eager work in between, must reproduce the eager result bit for bit."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    dev = torch.device("cuda:0")
+    B, H, T, d, segments = 1, 6, 1100, 64, (4 if mode == 4 else None)
+    q, k, v = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in vla_inputs.gaussian_qkv(B, H, T, d, seed=31))
+    o = torch.empty_like(v)
+    S_T = torch.empty((B, H, d, d), device=dev)
+    A_T = torch.empty((B, H, d, d), device=dev)
+
+    def call(stream):
+        rc = vla.vla_forward_static_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(),
+                                        S_T.data_ptr(), A_T.data_ptr(), B, H, T, d, d, vla.VLA_BF16, lambda0=0.1,
+                                        mode=mode, stream=stream, segments=segments)
+        assert rc == 0, vla.status_string(rc)
+
+    call(torch.cuda.current_stream().cuda_stream)     # eager: the first call on a device looks the array up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        fresh = [torch.from_numpy(x).to(dev).to(torch.bfloat16)
+                 for x in vla_inputs.gaussian_qkv(B, H, T, d, seed=40 + rep)]
+        for dst, src in zip((q, k, v), fresh):
+            dst.copy_(src)
+        call(torch.cuda.current_stream().cuda_stream)  # eager reference on the same buffers
+        torch.cuda.synchronize()
+        want = (o.clone(), S_T.clone(), A_T.clone())
+        for t in (o, S_T, A_T):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "S_T", "A_T"), want, (o, S_T, A_T)):
+            assert torch.equal(a, b), (name, rep)
