@@ -194,10 +194,18 @@ __global__ void __launch_bounds__(kThreads) gram_prefix_kernel(double* G, int n_
   const int head = static_cast<int>(e / dd);
   double* p = G + (static_cast<size_t>(head) * n_seg) * dd + (e - static_cast<long long>(head) * dd);
   double run = 0.0;
-#pragma unroll 8
-  for (int s = 0; s + 1 < n_seg; ++s) {
-    run += p[static_cast<size_t>(s) * dd];
-    p[static_cast<size_t>(s) * dd] = run;
+  const int n = n_seg - 1;   // the last segment's matrix is never needed
+  // sixteen loads in flight at a time: the chain is as long as the memory latency times the trips it makes
+  constexpr int U = 16;
+  for (int s = 0; s < n; s += U) {
+    double x[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) x[i] = s + i < n ? p[static_cast<size_t>(s + i) * dd] : 0.0;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      run += x[i];
+      if (s + i < n) p[static_cast<size_t>(s + i) * dd] = run;
+    }
   }
 }
 
@@ -251,10 +259,17 @@ __global__ void __launch_bounds__(kThreads) keysum_prefix_kernel(const double* p
   const int head = static_cast<int>(e / d);
   const int j = static_cast<int>(e - static_cast<long long>(head) * d);
   double run = zkey0 ? static_cast<double>(zkey0[e]) : 0.0;
-  for (int s = 0; s < n_seg; ++s) {
-    const size_t o = (static_cast<size_t>(head) * n_seg + s) * d + j;
-    seg_zkey[o] = static_cast<float>(run);
-    run += part[o];
+  const size_t base = static_cast<size_t>(head) * n_seg * d + j;
+  constexpr int U = 16;   // loads in flight
+  for (int s = 0; s < n_seg; s += U) {
+    double x[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) x[i] = s + i < n_seg ? part[base + static_cast<size_t>(s + i) * d] : 0.0;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      if (s + i < n_seg) seg_zkey[base + static_cast<size_t>(s + i) * d] = static_cast<float>(run);
+      run += x[i];
+    }
   }
 }
 
