@@ -314,6 +314,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       stage_next();
     }
     if (w == sw) {
+      __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
       float m[C];  // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
       const bool lower = lane < 32;
 #pragma unroll
@@ -343,6 +344,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int s4 = 0; s4 < C; s4 += 4)
           *reinterpret_cast<f4*>(&Lrs[c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (3) L^{-1} visible
 
@@ -380,6 +382,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     if (w != sw2) update_A();
     if (w == sw) stage_next();  // (sw != sw2 when NW > 1)
     if (w == sw2) {
+      __builtin_amdgcn_s_setprio(3);
       float m[C];  // lane c: row c of L
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -422,6 +425,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         const float csr = __shfl(cs, s);
         NQs[c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (5) Z, NQ, c visible
 

@@ -405,6 +405,7 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
     } else {
       // Lanes 0-31 hold rows of I + G (-> rows of L), lanes 32-63 columns of the identity (-> columns of
       // L^{-1}); one broadcast of L[j][t] serves the trailing update and the forward substitution.
+      __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
       float m[C];
       const bool lower = lane < 32;
 #pragma unroll
@@ -433,6 +434,7 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
 #pragma unroll
         for (int t = 0; t < C; ++t) Lis[t * LT + c] = m[t];
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (3) L^{-1} visible
 
@@ -491,6 +493,7 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
     if (w != sw2) update_A();
     if (w == sw) stage_next();
     if (w == sw2) {
+      __builtin_amdgcn_s_setprio(3);
       float wn2 = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) wn2 += wn2p[ww][c];
@@ -561,6 +564,7 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
           else *reinterpret_cast<f4*>(&rdens[4 * g]) = den;
         }
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (5) Z, NQ, c, denominators visible; the next block is staged in full
 

@@ -298,6 +298,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
       r_pass();
       stage_next();
     } else {
+      __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
       float m[C];
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -316,6 +317,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
         for (int s4 = 0; s4 < C; s4 += 4)
           *reinterpret_cast<f4*>(&Lrs[hrow][c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (3) L^{-1}, L visible
 
@@ -353,6 +355,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
     if (w != sw2) update_A();
     if (w == sw) stage_next();
     if (w == sw2) {
+      __builtin_amdgcn_s_setprio(3);
       float m[C];  // lane c: row c of this row's head's L
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -398,6 +401,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
           NQs[h2][c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
         }
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (5) Z, NQ, c visible
 

@@ -347,6 +347,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
     const int sw = it % NW;
     const int sw2 = (it + 1) % NW;
     if (w == sw) {
+      __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other wave waits for: issue it first
       const bool lower = lane < 32;
       float m[C];
 #pragma unroll
@@ -381,8 +382,11 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
 #pragma unroll
         for (int t = 0; t < C; ++t) Lis[pb][t * LT + c] = m[t];
       }
+      __builtin_amdgcn_s_setprio(0);
     } else if (w == sw2 && it > 0) {
+      __builtin_amdgcn_s_setprio(3);
       cz_pass(pb ^ 1, SMp + static_cast<size_t>(blk - 1) * SMB);
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();  // (3)
 
