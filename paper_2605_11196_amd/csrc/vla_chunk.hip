@@ -212,6 +212,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   }
   __syncthreads();  // block 0 staged
 
+  __builtin_amdgcn_s_setprio(1);
   int blk = 0;
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
     const float* Ks = Ksb[blk & 1];
@@ -310,8 +311,10 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
     };
     if (w != sw) {  // the other waves use the matrix pipes while wave sw factorises
+      __builtin_amdgcn_s_setprio(0);
       r_pass();
       stage_next();
+      __builtin_amdgcn_s_setprio(1);
     }
     if (w == sw) {
       __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
@@ -344,11 +347,12 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int s4 = 0; s4 < C; s4 += 4)
           *reinterpret_cast<f4*>(&Lrs[c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     }
     __syncthreads();  // (3) L^{-1} visible
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
+    __builtin_amdgcn_s_setprio(2);
     const f4 la = lds4(&Lis[c * LT + 4 * g]);
     f4 nwt[NJ];  // -W^T
     {
@@ -366,6 +370,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
+    __builtin_amdgcn_s_setprio(1);
     __syncthreads();  // (4) W and the norm partials visible
 
     // ================= phase 2 (wave sw2): c_t, Z, NQ -- the other waves update A meanwhile
@@ -379,7 +384,11 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
           for (int jn = 0; jn < NJ; ++jn) At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
       }
     };
-    if (w != sw2) update_A();
+    if (w != sw2) {
+      __builtin_amdgcn_s_setprio(0);
+      update_A();
+      __builtin_amdgcn_s_setprio(1);
+    }
     if (w == sw) stage_next();  // (sw != sw2 when NW > 1)
     if (w == sw2) {
       __builtin_amdgcn_s_setprio(3);
@@ -425,7 +434,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         const float csr = __shfl(cs, s);
         NQs[c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
       }
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     }
     __syncthreads();  // (5) Z, NQ, c visible
 

@@ -212,6 +212,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
   }
   __syncthreads();  // block 0 staged
 
+  __builtin_amdgcn_s_setprio(1);
   int blk = 0;
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
     const float* Ks = Ksb[hh];
@@ -295,8 +296,10 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
       }
     };
     if (w != sw) {
+      __builtin_amdgcn_s_setprio(0);   // filler while wave sw factorises
       r_pass();
       stage_next();
+      __builtin_amdgcn_s_setprio(1);
     } else {
       __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
       float m[C];
@@ -317,11 +320,12 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
         for (int s4 = 0; s4 < C; s4 += 4)
           *reinterpret_cast<f4*>(&Lrs[hrow][c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     }
     __syncthreads();  // (3) L^{-1}, L visible
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
+    __builtin_amdgcn_s_setprio(2);   // short, and every wave of the workgroup waits on it
     const f4 la = lds4(&Lis[hh][c * LT + 4 * g]);
     f4 nwt[NJ];  // -W^T
     {
@@ -339,6 +343,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[hh][wl][4 * g]) = n2;
     }
+    __builtin_amdgcn_s_setprio(1);
     __syncthreads();  // (4) W and the norm partials visible
 
     // ================= C x C section 2 (wave sw2, one head per 16-lane row): c_t, Z; then NQ head by head
@@ -352,7 +357,11 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
           for (int jn = 0; jn < NJ; ++jn) At[b][jn] = mfma16(wa[r], nwt[jn][r], At[b][jn]);
       }
     };
-    if (w != sw2) update_A();
+    if (w != sw2) {
+      __builtin_amdgcn_s_setprio(0);
+      update_A();
+      __builtin_amdgcn_s_setprio(1);
+    }
     if (w == sw) stage_next();
     if (w == sw2) {
       __builtin_amdgcn_s_setprio(3);
@@ -401,7 +410,7 @@ __global__ void __launch_bounds__(256, 2) chunk_multihead_kernel(ForwardArgs a) 
           NQs[h2][c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
         }
       }
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     }
     __syncthreads();  // (5) Z, NQ, c visible
 
