@@ -252,6 +252,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
 
   int blk = seg * a.seg_blocks;
   int it = 0;   // blocks done by this workgroup
+  __builtin_amdgcn_s_setprio(1);
   for (int t0 = tb; t0 < T; t0 += C, ++blk, ++it) {
     const int pb = it & 1;
     float* Ks = Ksb[MAPF ? pb : 0];
@@ -382,11 +383,11 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
 #pragma unroll
         for (int t = 0; t < C; ++t) Lis[pb][t * LT + c] = m[t];
       }
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     } else if (w == sw2 && it > 0) {
       __builtin_amdgcn_s_setprio(3);
       cz_pass(pb ^ 1, SMp + static_cast<size_t>(blk - 1) * SMB);
-      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(1);
     }
     __syncthreads();  // (3)
 
@@ -414,7 +415,9 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
     //      the other LDS copy, which is not written again before barrier (4)
     if constexpr (MAPF) {
       if (do_map) {
+        __builtin_amdgcn_s_setprio(0);   // off the A chain's path: behind the other workgroups' work
         if (it > 0) map_step(t0 - C, pb ^ 1, vcur);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int i = 0; i < SPW; ++i)
 #pragma unroll
