@@ -32,11 +32,23 @@
 namespace vla {
 namespace {
 
+// Wave priority: LEVELS = 2: the full scheme (level FULL); 1: only the serial chains are raised (level CHAIN at
+// their start and end, nothing where CHAIN < 0); 0: every wave stays at the default priority.
+template <int LEVELS, int FULL, int CHAIN>
+__device__ __forceinline__ void prio() {
+  if constexpr (LEVELS == 2) __builtin_amdgcn_s_setprio(FULL);
+  else if constexpr (LEVELS == 1 && CHAIN >= 0) __builtin_amdgcn_s_setprio(CHAIN);
+}
+
 // FMAP: q and k are replaced by ELU(x) + 1 while they are staged (the feature map of Section 3.3).
 // DV: head size of v and o (rows of S); the wave that owns columns [SL w, SL w + SL) of A owns rows
 // [SLV w, SLV w + SLV) of S.
 template <int D, int DV, int NW, typename IO, bool FMAP>
 __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
+  // Measured at 2048 heads, T = 8192: the full scheme gains 5 % with four waves (d = 128), 1 % with three (d = 96),
+  // 1-5 % with one (d = 16, 32); two-wave workgroups (d = 64), four of which share a compute unit, lose up to
+  // 20 % with any of it (1536 heads: 7.0 -> 8.5 ms) and stay at the default priority.
+  constexpr int kLevels = NW == 2 ? 0 : 2;
   constexpr int SL = D / NW;       // columns of A owned by one wave
   constexpr int NJ = SL / 16;      // 16-wide tiles in a slab of A
   constexpr int SLV = DV / NW;     // rows of S owned by one wave
@@ -212,7 +224,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   }
   __syncthreads();  // block 0 staged
 
-  __builtin_amdgcn_s_setprio(1);
+  prio<kLevels, 1, -1>();
   int blk = 0;
   for (int t0 = 0; t0 < T; t0 += C, ++blk) {
     const float* Ks = Ksb[blk & 1];
@@ -311,13 +323,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
     };
     if (w != sw) {  // the other waves use the matrix pipes while wave sw factorises
-      __builtin_amdgcn_s_setprio(0);
+      prio<kLevels, 0, -1>();
       r_pass();
       stage_next();
-      __builtin_amdgcn_s_setprio(1);
+      prio<kLevels, 1, -1>();
     }
     if (w == sw) {
-      __builtin_amdgcn_s_setprio(3);   // the dependent chain is what the other waves wait for: issue it first
+      prio<kLevels, 3, 3>();   // the dependent chain is what the other waves wait for: issue it first
       float m[C];  // lanes <32, lane c: row c of L;  lanes >=32, lane c: m[t] = L^{-1}[t][c]
       const bool lower = lane < 32;
 #pragma unroll
@@ -347,12 +359,12 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         for (int s4 = 0; s4 < C; s4 += 4)
           *reinterpret_cast<f4*>(&Lrs[c * LT + s4]) = f4{m[s4], m[s4 + 1], m[s4 + 2], m[s4 + 3]};
       }
-      __builtin_amdgcn_s_setprio(1);
+      prio<kLevels, 1, 0>();
     }
     __syncthreads();  // (3) L^{-1} visible
 
     // ================= W^T = L^{-1} Y^T, partial ||w_t||^2, W to LDS
-    __builtin_amdgcn_s_setprio(2);
+    prio<kLevels, 2, -1>();
     const f4 la = lds4(&Lis[c * LT + 4 * g]);
     f4 nwt[NJ];  // -W^T
     {
@@ -370,7 +382,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       for (int r = 0; r < 4; ++r) n2[r] = row_sum16(n2[r]);
       if (c == 0) *reinterpret_cast<f4*>(&wn2p[w][4 * g]) = n2;
     }
-    __builtin_amdgcn_s_setprio(1);
+    prio<kLevels, 1, -1>();
     __syncthreads();  // (4) W and the norm partials visible
 
     // ================= phase 2 (wave sw2): c_t, Z, NQ -- the other waves update A meanwhile
@@ -385,13 +397,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       }
     };
     if (w != sw2) {
-      __builtin_amdgcn_s_setprio(0);
+      prio<kLevels, 0, -1>();
       update_A();
-      __builtin_amdgcn_s_setprio(1);
+      prio<kLevels, 1, -1>();
     }
     if (w == sw) stage_next();  // (sw != sw2 when NW > 1)
     if (w == sw2) {
-      __builtin_amdgcn_s_setprio(3);
+      prio<kLevels, 3, 3>();
       float m[C];  // lane c: row c of L
 #pragma unroll
       for (int s4 = 0; s4 < C; s4 += 4) {
@@ -434,7 +446,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         const float csr = __shfl(cs, s);
         NQs[c * LT + s] = (s <= c) ? -(csr * hq[r]) : 0.0f;
       }
-      __builtin_amdgcn_s_setprio(1);
+      prio<kLevels, 1, 0>();
     }
     __syncthreads();  // (5) Z, NQ, c visible
 
@@ -528,18 +540,18 @@ bool chunk_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 ||
 
 // Several heads per workgroup (vla_chunk_multihead.hip) or one?  Measured on one MI355X, T = 8192:
 //   d = 64 (two-wave workgroups here, four-wave ones of two heads there; both hold 1024 heads per chip at a
-//   time): up to 256 heads one workgroup per compute unit either way, 2.5 against 2.8 ms; 257-512 heads 4.1
-//   against 2.8 ms (two two-wave workgroups on a compute unit are placed on three of its four SIMDs); 1024
-//   heads 4.5 against 4.3 ms; 2048 heads 9.2 against 8.7 ms; but 1536 heads 7.3 against 8.8 ms: the larger
-//   workgroups refill a draining chip two to a compute unit, so a launch that is not a whole number of full
-//   rounds pays for its tail.
+//   time): up to 256 heads one workgroup per compute unit either way, 2.5 against 2.7 ms; 257-512 heads 4.1
+//   against 2.7 ms (two two-wave workgroups on a compute unit are placed on three of its four SIMDs); 768-1024
+//   heads 4.3-4.5 against 4.1-4.2 ms; 2048 heads 8.9 against 8.3 ms, 3072: 13.2 against 12.4, 4096: 17.6 against
+//   16.5; but 1280-1536 heads 7.0 against 8.4-8.5 ms: the larger workgroups refill a draining chip two to a
+//   compute unit, so a launch that is not a whole number of full rounds pays for its tail.
 //   d = 32 (one-wave workgroups here, four heads per workgroup there): up to 1024 heads 2.3 against 2.4 ms,
-//   1280-1536 heads 3.6 against 3.4 ms, 2048 heads 4.5 against 3.4 ms.
+//   1280-1536 heads 3.35 against 3.25 ms, 2048 heads 4.6 against 3.25 ms, 4096: 9.2 against 6.5.
 bool prefer_multihead(int d, int n_heads) {
   if (d == 32) return n_heads > 1024;
   if (d == 64) {
     const int wgs = (n_heads + 1) / 2;
-    return n_heads > 256 && (wgs <= 256 || wgs % 512 == 0 || wgs >= 4096);
+    return n_heads > 256 && (wgs <= 512 || wgs % 512 == 0 || wgs >= 4096);
   }
   return false;
 }
