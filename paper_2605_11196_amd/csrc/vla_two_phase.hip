@@ -751,35 +751,68 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   // ---- this thread's share of a block's operands
   // big operands: piece `pc` of k and of q (row pc / (D/4), columns 4 (pc % (D/4)) ..) and of W (row
   // pc / 4 of [D][16], columns 4 (pc % 4) ..); in the map pass the first half of the threads carries K^ and
-  // the second half W.  small operands: Z (64 pieces), -NQ^T (64), -c (4) on the first threads.
+  // the second half W.  small operands: the record Z | -NQ^T | -c | denominators is 136 pieces in a row, piece
+  // t on thread t (Z on 0-63, -NQ^T on 64-127 outside the map pass, -c and the denominators on 128-135); with
+  // only 128 threads (d = 32 outside the map pass) the last pieces ride in a register of their own on threads 0-7.
   const int pc = MAP ? tid % CH : tid;
   const bool do_k = !MAP || tid < CH;
   const bool do_w = !MAP || tid >= CH;
   const int krow = pc / (D / 4), kcol = 4 * (pc % (D / 4));
   const int wrow = pc / 4, wcol = 4 * (pc % 4);
-  const int sm_src = tid < 64 ? 4 * tid : C * C + 4 * (tid - 64);
-  const bool do_sm = tid < (MAP ? 64 : 128);   // Z on threads 0-63, -NQ^T on 64-127 (not in the map pass)
-  const bool do_c = tid < ((!MAP && norm_out) ? 8 : 4);   // -c (and the read-out denominators behind it)
+  constexpr bool kSepC = NT < 136;
+  const int nc = (!MAP && norm_out) ? 8 : 4;   // -c (and the read-out denominators behind it)
+  const bool do_sm = tid < (MAP ? 64 : 128) || (!kSepC && tid >= 128 && tid < 128 + nc);
+  const bool do_c = kSepC && tid < nc;
   struct Regs {
     f4 wx, sx, cx;
     RawRow<IO, 4> kx, qx;
     float krn;          // 1 / max(||k||, eps) of token row krow (0 past the end)
     IO v[4];
   };
+  // Byte offsets inside a block's records are per-thread constants (32 bits); the block's base addresses are
+  // uniform (scalar registers).  Only the ragged last block has to clamp its token rows (rows past the end read
+  // the last row).
+  // (krow D + kcol = wrow C + wcol = 4 pc and sm_src = 4 tid: piece pc of a row-major array of 4-element pieces.)
+  constexpr unsigned ES = sizeof(IO);
+  static_assert(C == 16, "piece arithmetic");
+  const unsigned p16 = 16u * static_cast<unsigned>(pc);      // byte offset of float piece pc
+  const unsigned t16 = 16u * static_cast<unsigned>(tid);
+  const unsigned kq_off = p16 * ES / 4u;                       // 4 pc elements of IO
+  const unsigned w_off = p16;
+  const unsigned sm_off = t16;
+  const unsigned c_off = static_cast<unsigned>(2 * C * C) * 4u + t16;
+  const unsigned rn_off = static_cast<unsigned>(krow) * 4u;
+  const unsigned v_off = static_cast<unsigned>(4 * g * D + row0 + c) * ES;
+  auto at = [](const void* base, unsigned byte_off) { return static_cast<const char*>(base) + byte_off; };
   auto fetch = [&](int blk, Regs& r) {
+    const size_t tok = static_cast<size_t>(blk) * (C * D);
+    const IO* kb = kh + tok;
+    const IO* qb = qh + tok;
+    const IO* vb = vh + tok;
+    const float* wb = WT + tok;
+    const float* sb = SMp + static_cast<size_t>(blk) * SMB;
+    const float* rb = RN + static_cast<size_t>(blk) * C;
     const int lim = T - 1 - blk * C;   // last live token row of the block
-    const size_t kq = static_cast<size_t>(blk) * (C * D) + min(krow, lim) * D + kcol;   // past the end: the last row
-    if (do_k) {
-      r.kx.load(kh + kq);
-      r.krn = RN[blk * C + krow];
-    }
-    if (do_w) r.wx = *reinterpret_cast<const f4*>(WT + static_cast<size_t>(blk) * (D * C) + wrow * C + wcol);
-    if (do_sm) r.sx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + sm_src);
-    if (do_c) r.cx = *reinterpret_cast<const f4*>(SMp + static_cast<size_t>(blk) * SMB + 2 * C * C + 4 * tid);
-    if constexpr (!MAP) r.qx.load(qh + kq);
+    unsigned kq = kq_off, vo[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      r.v[i] = vh[static_cast<size_t>(blk) * (C * D) + min(4 * g + i, lim) * D + row0 + c];
+    for (int i = 0; i < 4; ++i) vo[i] = v_off + static_cast<unsigned>(i * D) * ES;
+    if (lim < C - 1) {   // uniform
+      kq = static_cast<unsigned>(min(krow, lim) * D + kcol) * ES;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vo[i] = static_cast<unsigned>(min(4 * g + i, lim) * D + row0 + c) * ES;
+    }
+    if (do_w) r.wx = *reinterpret_cast<const f4*>(at(wb, w_off));
+    if (do_sm) r.sx = *reinterpret_cast<const f4*>(at(sb, sm_off));
+    if constexpr (kSepC) {
+      if (do_c) r.cx = *reinterpret_cast<const f4*>(at(sb, c_off));
+    }
+    if (do_k) {
+      r.kx.load(reinterpret_cast<const IO*>(at(kb, kq)));
+      r.krn = *reinterpret_cast<const float*>(at(rb, rn_off));
+    }
+    if constexpr (!MAP) r.qx.load(reinterpret_cast<const IO*>(at(qb, kq)));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.v[i] = *reinterpret_cast<const IO*>(at(vb, vo[i]));
   };
   auto put = [&](const Regs& r, Stage& s) {
     if (do_k) {   // k^ = k / max(||k||, eps): the same product the A scan formed it with
@@ -795,9 +828,12 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     if (do_sm) {
       // Z and -NQ^T rows are 16 floats in the workspace and LT in LDS
       if (tid < 64) *reinterpret_cast<f4*>(&s.Zs[(tid / 4) * LT + 4 * (tid % 4)]) = r.sx;
-      else *reinterpret_cast<f4*>(&s.NQs[((tid - 64) / 4) * LT + 4 * (tid % 4)]) = r.sx;
+      else if (tid < 128) *reinterpret_cast<f4*>(&s.NQs[((tid - 64) / 4) * LT + 4 * (tid % 4)]) = r.sx;
+      else *reinterpret_cast<f4*>(&s.cv[4 * (tid - 128)]) = r.sx;
     }
-    if (do_c) *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
+    if constexpr (kSepC) {
+      if (do_c) *reinterpret_cast<f4*>(&s.cv[4 * tid]) = r.cx;
+    }
     if constexpr (!MAP) {
       float x[4];
       r.qx.unpack(x);
@@ -833,7 +869,8 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
 #pragma unroll
       for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
       if (norm_out) ot *= lds4(&s.cv[C + 4 * g]);
-      IO* ob = oh + static_cast<size_t>(blk) * (C * D) + 4 * g * D + row0 + c;
+      // uniform block base + this lane's 32-bit byte offset (the one its v loads use)
+      IO* ob = reinterpret_cast<IO*>(reinterpret_cast<char*>(oh + static_cast<size_t>(blk) * (C * D)) + v_off);
       if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
         io_store2(ob, ob + D, ot[0], ot[1]);
         io_store2(ob + 2 * D, ob + 3 * D, ot[2], ot[3]);
