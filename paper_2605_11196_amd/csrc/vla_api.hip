@@ -125,12 +125,17 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
     return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
   }
   const long long heads = static_cast<long long>(B) * H;
-  // Measured crossovers against the fused block kernel (bf16, one MI355X).  Long sequences, T = 2048 / 16384:
-  //   d = 128:  64 heads 0.85 / 4.2 against 0.96 / 7.6 ms,  96 heads 1.27 / 6.3 against 0.96 / 7.7
-  //   d =  96:  64 heads 0.69 / 3.5 against 0.82 / 6.5,     96 heads 1.05 / 5.1 against 0.82 / 6.5
-  //   d =  64: 192 heads 0.57 / 3.5 against 0.63 / 5.0,    256 heads 0.70 / 4.6 against 0.62 / 5.0
-  //   d =  32: 512 heads 0.53 / 3.8 against 0.57 / 4.5,    768 heads 0.58 / 4.5 against 0.58 / 4.6
-  const long long few = d >= 96 ? 64 : (d >= 64 ? 192 : 512);
+  // Measured crossovers against the fused block kernel (bf16, one MI355X; time-parallel against block kernel, ms).
+  // The segment kernels gain on the block kernel as the sequence grows (their fixed passes amortise):
+  //   d = 128:  T = 2048: 64 heads 0.75 / 0.96, 96 heads 1.18 / 0.98;   T = 4096: 96 heads 1.92 / 1.94, 128: 2.28 / 1.94;
+  //             T = 8192: 96 heads 3.24 / 3.86, 128: 3.93 / 3.88;       T = 16384: 128 heads 7.39 / 7.75, 192: 11.4 / 7.7
+  //   d =  96:  T = 2048: 64 heads 0.58 / 0.81, 96: 0.93 / 0.82;        T = 4096: 96 heads 1.56 / 1.64, 128: 1.82 / 1.64;
+  //             T = 8192: 128 heads 3.20 / 3.27;                        T = 16384: 128 heads 5.98 / 6.52; 160 (T = 32768): 15.0 / 13.0
+  //   d =  64:  T = 2048: 192 heads 0.53 / 0.63, 256: 0.63 / 0.63;      T = 4096: 256 heads 1.11 / 1.25, 320: 1.37 / 1.38;
+  //             T = 16384: 256 heads 4.01 / 4.98, 384: 7.43 / 5.45
+  //   d =  32:  T = 2048: 512 heads 0.50 / 0.57, 768: 0.59 / 0.58;      T = 16384: 512 heads 3.57 / 4.54, 768: 4.61 / 4.57
+  const long long few = d >= 96 ? (T >= 16384 ? 128 : (T >= 4096 ? 96 : 64))
+                                : (d >= 64 ? (T >= 4096 ? 256 : 192) : 512);
   // Short sequences (half the length): 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads
   // 0.19 against 0.17.  At d = 96 (Gram sums and boundary inverses in the d = 128 layout) the crossover sits one
   // octave higher (T = 1024: 16 heads 0.29 against 0.41 ms, 64 heads 0.43 against 0.41; T = 512: 16 heads 0.26
