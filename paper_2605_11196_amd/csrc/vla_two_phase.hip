@@ -271,8 +271,11 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
 #pragma unroll
         for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
       }
+      const bool ragged = t0 + C > T;   // uniform: only the last block masks rows past the end
+      if (ragged || PADDED) {
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+        for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+      }
       float ss = 0.0f;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) ss = fmaf(kx[e], kx[e], ss);
@@ -294,8 +297,10 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
 #pragma unroll
           for (int e = 0; e < EPT; ++e) kx[e] = elu_plus_one(kx[e]);
         }
+        if (ragged) {
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+          for (int e = 0; e < EPT; ++e) kx[e] = live ? kx[e] : 0.0f;
+        }
 #pragma unroll
         for (int e = 0; e < EPT; e += 4)
           *reinterpret_cast<f4*>(&Qs[srow * LD + sseg + e]) = f4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
