@@ -371,15 +371,18 @@ def main():
         sec = []
         sec.append(secondary_entry("large_batch_d64", forward_case(
             make_case("large_batch", d=64), steps=k2, warmup=w2, oracle_heads=8)))
+        # the long-context calls take 0.2 to 3 ms and each follows seconds of oracle work on the host, during
+        # which the GPU clocks fall: more warm-up launches and 30 timed ones (about 0.1 s per entry)
+        k3, w3 = max(30, args.steps), 10
         for T in make_case("long_context")["T_sweep"]:
             sec.append(secondary_entry(f"long_context_T{T}", forward_case(
-                make_case("long_context", T=T), steps=k2, warmup=w2, oracle_heads=2)))
+                make_case("long_context", T=T), steps=k3, warmup=w3, oracle_heads=2)))
         sec.append(secondary_entry("long_context_T131072_options_no_refresh", forward_case(
-            make_case("long_context", T=131072), options="paper_no_refresh", steps=k2, warmup=w2, oracle_heads=2)))
+            make_case("long_context", T=131072), options="paper_no_refresh", steps=k3, warmup=w3, oracle_heads=2)))
         sec.append(secondary_entry("large_batch_options_paper", forward_case(
             make_case("large_batch"), options="paper", steps=k2, warmup=w2, oracle_heads=4)))
         sec.append(secondary_entry("decode_large_batch_heads", decode_case(
-            make_case("large_batch"), steps=max(20, k2), warmup=w2, oracle_heads=8)))
+            make_case("large_batch"), steps=k3, warmup=w3, oracle_heads=8)))
         out["secondary"] = sec
     print(json.dumps(out))
 
