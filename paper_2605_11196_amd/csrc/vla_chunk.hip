@@ -51,9 +51,13 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   constexpr int kLevels = NW == 2 ? 0 : 2;
   constexpr int SL = D / NW;       // columns of A owned by one wave
   constexpr int NJ = SL / 16;      // 16-wide tiles in a slab of A
-  constexpr int SLV = DV / NW;     // rows of S owned by one wave
-  constexpr int NJV = SLV / 16;    // 16-wide tiles in a slab of S^T
-  static_assert(SLV % 16 == 0 && NJV >= 1, "a wave owns whole tiles of S");
+  // The DV / 16 row tiles of S are shared out over the waves: DV / (16 NW) consecutive tiles each where that
+  // divides (kEven), else tile t goes to wave t % NW, and a wave with fewer tiles than the others (or none)
+  // runs its spare slots on a copy of the last tile and stores nothing from them.
+  constexpr int TV = DV / 16;
+  constexpr bool kEven = TV % NW == 0;
+  constexpr int NJV = kEven ? TV / NW : (TV + NW - 1) / NW;   // tile slots per wave
+  static_assert(DV % 16 == 0 && NJV >= 1, "whole tiles of S");
   constexpr int NB = D / 16;       // 16-row blocks over the whole head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
   constexpr int NT = 64 * NW;
@@ -88,7 +92,17 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   const int T = a.T;
   const float eps = a.eps;
   const int col0 = SL * w;    // first column of this wave's slab of A
-  const int row0 = SLV * w;   // first row of this wave's slab of S
+  const int row0 = 16 * NJV * w;   // kEven: first row of this wave's slab of S
+  // first S row of this wave's tile slot jn, and whether the slot holds a tile of its own
+  auto s_row = [&](int jn) -> int {
+    if constexpr (kEven) {
+      return row0 + 16 * jn;
+    } else {
+      const int t = w + NW * jn;
+      return 16 * (t < TV ? t : TV - 1);
+    }
+  };
+  auto owns = [&](int jn) -> bool { return kEven || w + NW * jn < TV; };
 
   // ---- resident state: accumulator tiles
   // At[b][jn][r] = A[16b + 4g + r][col0 + 16jn + c]
@@ -99,7 +113,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * DV * D : nullptr;
     const float diag = 1.0f / a.lambda0;
     const int arc = (4 * g) * D + col0 + c;  // A[4g][col0 + c]
-    const int src = (row0 + c) * D + 4 * g;  // S[row0 + c][4g]
+    const int src = c * D + 4 * g;  // S[c][4g]
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
 #pragma unroll
@@ -116,7 +130,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
 #pragma unroll
       for (int jn = 0; jn < NJV; ++jn) {
         if (S0) {
-          const float4 x = *reinterpret_cast<const float4*>(S0 + src + 16 * jn * D + 16 * b);
+          const float4 x = *reinterpret_cast<const float4*>(S0 + src + s_row(jn) * D + 16 * b);
           St[b][jn] = f4{x.x, x.y, x.z, x.w};
         } else {
           St[b][jn] = f4{0, 0, 0, 0};
@@ -137,7 +151,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
   const int sseg = (tid % TPR) * EPT;
   const bool stager = !PADDED || (tid < C * TPR && sseg < D);    // this thread holds a row segment
   const bool stage_wave = !PADDED || tid < C * TPR;              // uniform per wave
-  const int vcol = row0 + c;  // first element of a v / o row this lane touches in accumulator layout
+  const int vcol = s_row(0) + c;  // first element of a v / o row this lane touches in accumulator layout
 
   RawRow<IO, EPT> kpre, qpre;
   IO vpre[NJV][4];  // V^T in accumulator layout: V[t0 + 4g + r][row0 + 16jn + c]
@@ -158,7 +172,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       const int t = t0 + 4 * g + r;
       const unsigned voff = static_cast<unsigned>((t < T ? t : T - 1) * DV + vcol);
 #pragma unroll
-      for (int jn = 0; jn < NJV; ++jn) vpre[jn][r] = vh[voff + 16 * jn];
+      for (int jn = 0; jn < NJV; ++jn) vpre[jn][r] = vh[voff + (s_row(jn) - s_row(0))];
     }
   };
   // normalise this thread's share of the keys of the block starting at t0 and put K^, Q into LDS half `buf`
@@ -476,10 +490,16 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
         const int t = t0 + 4 * g + r;
         if (t < T) {
           const unsigned ooff = static_cast<unsigned>(t * DV + vcol);
+          if constexpr (kEven) {
 #pragma unroll
-          for (int jn = 0; jn + 1 < NJV; jn += 2)
-            io_store2(oh + ooff + 16 * jn, oh + ooff + 16 * jn + 16, ot[jn][r], ot[jn + 1][r]);
-          if (NJV % 2 == 1) io_store(oh + ooff + 16 * (NJV - 1), ot[NJV - 1][r]);
+            for (int jn = 0; jn + 1 < NJV; jn += 2)
+              io_store2(oh + ooff + 16 * jn, oh + ooff + 16 * jn + 16, ot[jn][r], ot[jn + 1][r]);
+            if (NJV % 2 == 1) io_store(oh + ooff + 16 * (NJV - 1), ot[NJV - 1][r]);
+          } else {
+#pragma unroll
+            for (int jn = 0; jn < NJV; ++jn)
+              if (owns(jn)) io_store(oh + ooff + (s_row(jn) - s_row(0)), ot[jn][r]);
+          }
         }
       }
     }
@@ -502,7 +522,7 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
     int g2 = g, c2 = c;
     asm volatile("" : "+v"(g2), "+v"(c2));  // recompute the addresses here instead of carrying them over the loop
     const int arc = (4 * g2) * D + col0 + c2;
-    const int src = (row0 + c2) * D + 4 * g2;
+    const int src = c2 * D + 4 * g2;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (AT) {
@@ -514,8 +534,9 @@ __global__ void __launch_bounds__(64 * NW, 2) chunk_kernel(ForwardArgs a) {
       if (ST) {
 #pragma unroll
         for (int jn = 0; jn < NJV; ++jn)
-          *reinterpret_cast<float4*>(ST + src + 16 * jn * D + 16 * b) =
-              make_float4(St[b][jn][0], St[b][jn][1], St[b][jn][2], St[b][jn][3]);
+          if (owns(jn))
+            *reinterpret_cast<float4*>(ST + src + s_row(jn) * D + 16 * b) =
+                make_float4(St[b][jn][0], St[b][jn][1], St[b][jn][2], St[b][jn][3]);
       }
     }
   }
@@ -556,15 +577,9 @@ bool prefer_multihead(int d, int n_heads) {
   return false;
 }
 
-// The d_k / 32 waves of a head (one below d_k = 32) share out the d_v rows of S in whole 16-row tiles: every value
-// head size from 16 to 128 with key heads of 16 or 32, value heads from 32 with key heads of 64, from 64 with key
-// heads of 128; key heads of 96 (three waves) only with value heads of 96.
-bool chunk_supported(int d_k, int d_v) {
-  if (!chunk_supported(d_k) || !chunk_supported(d_v)) return false;
-  if (d_k == 96 || d_v == 96) return d_k == d_v || (d_v == 96 && d_k <= 64);
-  const int waves = d_k >= 32 ? d_k / 32 : 1;
-  return d_v % (16 * waves) == 0;
-}
+// The d_k / 32 waves of a head (one below d_k = 32) share out the d_v / 16 row tiles of S, evenly where the counts
+// divide and one by one in turn where they do not: every pair of head sizes runs.
+bool chunk_supported(int d_k, int d_v) { return chunk_supported(d_k) && chunk_supported(d_v); }
 
 hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hipStream_t stream) {
   if (d_k == d_v && prefer_multihead(d_k, a.n_heads)) return launch_chunk_multihead(a, d_k, io_dtype, stream);
@@ -586,6 +601,14 @@ hipError_t launch_chunk(const ForwardArgs& a, int d_k, int d_v, int io_dtype, hi
     case 32096: return launch_io<32, 96, 1>(a, io_dtype, stream);
     case 32128: return launch_io<32, 128, 1>(a, io_dtype, stream);
     case 64096: return launch_io<64, 96, 2>(a, io_dtype, stream);
+    case 64016: return launch_io<64, 16, 2>(a, io_dtype, stream);
+    case 96016: return launch_io<96, 16, 3>(a, io_dtype, stream);
+    case 96032: return launch_io<96, 32, 3>(a, io_dtype, stream);
+    case 96064: return launch_io<96, 64, 3>(a, io_dtype, stream);
+    case 96128: return launch_io<96, 128, 3>(a, io_dtype, stream);
+    case 128016: return launch_io<128, 16, 4>(a, io_dtype, stream);
+    case 128032: return launch_io<128, 32, 4>(a, io_dtype, stream);
+    case 128096: return launch_io<128, 96, 4>(a, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }
