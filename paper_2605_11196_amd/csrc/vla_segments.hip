@@ -6,8 +6,9 @@
 // sum, so A at the start of every segment follows from one Gram matrix per segment and one d x d inversion, all
 // independent of each other; the segments then run the exact rank-1 recurrence concurrently.  The paper
 // treats the A loop as sequential (Section 3.4); this goes beyond it and is not valid with the identity
-// refresh.  Everything here is float64 so that the boundary matrices are at least as accurate
-// as the float32 chain they replace (a product of two float32 numbers is exact in float64).
+// refresh.  The directions are the float32 numbers the recurrence kernels work with; their outer products (exact
+// in float64), the sums and the inversions are float64, so that the boundary matrices are at least as accurate
+// as the float32 chain they replace.
 //
 // The S recurrence is affine in S (eq. (s-update)): S_end = S_start P + Q per segment.  P and Q come from the
 // map pass of the S-rows kernel; combine_kernel composes them from left to right.
@@ -22,9 +23,11 @@ constexpr int kThreads = 256;
 typedef double d4 __attribute__((ext_vector_type(4)));
 
 // One workgroup (4 waves) per (head, segment); the last segment's matrix is never needed.  Tokens are
-// normalised in float64 and staged through LDS 32 at a time; the outer products run on the float64 matrix
-// cores (v_mfma_f64_16x16x4_f64: lane l supplies A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16] and
-// receives D[i = l / 16 + 4 r][j = l % 16] in element r), both operands being the same staged tile.  A wave
+// normalised in float32, exactly as the kernels that run the recurrence normalise them (the sum is over the
+// directions those kernels use, float32 numbers), and staged through LDS 64 at a time (32 at d = 128); the outer
+// products run on the float64 matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies A[i = l % 16][k = l / 16] and
+// B[k = l / 16][j = l % 16] and receives D[i = l / 16 + 4 r][j = l % 16] in element r), both operands being the
+// same staged tile widened as it is read: a product of two float32 values is exact in float64.  A wave
 // holds at most 16 result tiles: up to D = 64 every wave covers the whole matrix and the waves take the
 // tokens of a tile in turn (summed through LDS at the end); at D = 128 each wave owns two tile rows.
 // DL: the head size of the data; D >= DL: the size the tiles are laid out for.  They differ for d = 96, which
@@ -37,18 +40,19 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   constexpr int TR = NTI * NTI <= 16 ? NTI : 16 / NTI;       // tile rows per wave
   constexpr int RGW = NTI / TR;                              // waves across the rows
   constexpr int NGW = (kThreads / 64) / RGW;                 // waves across the tokens
-  constexpr int TT = 32;                                     // tokens per tile
+  constexpr int TT = D <= 64 ? 64 : 32;                      // tokens per tile
   constexpr int KS = TT / 4;                                 // k-steps (4 tokens) per tile
-  constexpr int LDK = D + 16;                                // rows 32 banks apart: conflict-free operand reads
+  constexpr int LDK = D + 16;                                // rows 16 banks apart: conflict-free operand reads
   constexpr int EPT = TT * D / kThreads;                     // elements of the tile each thread stages
-  constexpr int TPR = D / EPT;                               // threads per token row (8)
-  static_assert(RGW * NGW * 64 == kThreads && KS % NGW == 0 && TPR == 8, "layout");
+  constexpr int TPR = D / EPT;                               // threads per token row
+  static_assert(RGW * NGW * 64 == kThreads && KS % NGW == 0 && (TPR == 4 || TPR == 8) && EPT % 4 == 0, "layout");
   // The sum of k^ k^T is symmetric: where a wave covers the whole matrix it forms the tiles on and above the
   // diagonal only (10 of 16 at d = 64).
   constexpr bool SYM = RGW == 1;
-  __shared__ double ktb[2][TT * LDK];   // double-buffered: one barrier per tile
-  static_assert(NGW == 1 || 2 * TT * LDK >= D * D, "the final sum over the waves reuses the tile buffers");
-  double* const red = &ktb[0][0];
+  __shared__ __align__(16) float ktb[2][TT * LDK];   // double-buffered: one barrier per tile
+  static_assert(NGW == 1 || 2 * TT * LDK * sizeof(float) >= D * D * sizeof(double),
+                "the final sum over the waves reuses the tile buffers");
+  double* const red = reinterpret_cast<double*>(&ktb[0][0]);
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
@@ -65,8 +69,8 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   // the directions the penalty matrix accumulates: the caller's u (scaled after normalisation), else the keys
   const bool has_u = a.u != nullptr;
   const IO* kh = static_cast<const IO*>(has_u ? a.u : a.k) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * DL;
-  const double eps = static_cast<double>(a.eps);
-  const double scale = has_u ? static_cast<double>(a.u_scale) : 1.0;
+  const float eps = a.eps;
+  const float scale = has_u ? a.u_scale : 1.0f;
   const int srow = tid / TPR;
   const int scol = (tid % TPR) * EPT;
 
@@ -78,50 +82,51 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
 
   // Fragments of the next PF tiles are kept in flight in raw form (a few registers each): with a thousand
   // workgroups streaming at once the memory latency is several tiles' worth of work.
-  constexpr int PF = D >= 128 ? 2 : 4;   // what the register file allows next to 128 accumulator registers
+  constexpr int PF = 2;   // what the register file allows next to the accumulator registers
   RawRow<IO, EPT> raw[PF];
   auto fetch = [&](int t0, RawRow<IO, EPT>& o) {
     const int t = t0 + srow;
     if (D == DL || scol < DL) o.load(kh + static_cast<size_t>(t < te ? t : te - 1) * DL + scol);
   };
-  // stage: k^ = k / max(||k||, eps) in float64; rows past the end are zero.  1 / ||k|| is a float32
-  // reciprocal square root refined by one Newton step in float64 (relative error ~1e-14).
-  auto stage = [&](int t0, const RawRow<IO, EPT>& o, double* kt) {
+  // stage: k^ = k / max(||k||, eps) as the recurrence kernels form it (float32: hardware reciprocal square
+  // root, one Newton step); rows past the end are zero
+  auto stage = [&](int t0, const RawRow<IO, EPT>& o, float* kt) {
     const int t = t0 + srow;
-    double x[EPT];
+    float x[EPT];
     o.unpack(x);
     if (D != DL && scol >= DL) {
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) x[e] = 0.0;
+      for (int e = 0; e < EPT; ++e) x[e] = 0.0f;
     }
-    if (a.feature_map && !has_u && (D == DL || scol < DL)) {   // ELU(x) + 1 on keys, in float32, as the kernels that run the recurrence apply it
+    if (a.feature_map && !has_u && (D == DL || scol < DL)) {   // ELU(x) + 1 on keys
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) x[e] = static_cast<double>(elu_plus_one(static_cast<float>(x[e])));
+      for (int e = 0; e < EPT; ++e) x[e] = elu_plus_one(x[e]);
     }
-    double ss = 0.0;
+    float ss = 0.0f;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      x[e] = t < te ? x[e] : 0.0;
-      ss = fma(x[e], x[e], ss);
+      x[e] = t < te ? x[e] : 0.0f;
+      ss = fmaf(x[e], x[e], ss);
     }
 #pragma unroll
     for (int off = TPR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-    const double y = static_cast<double>(__builtin_amdgcn_rsqf(static_cast<float>(ss)));
-    const double yn = y * fma(-0.5 * ss * y, y, 1.5);
-    const double rn = (ss > eps * eps ? yn : 1.0 / eps) * scale;
+    const float sm = fmaxf(ss, eps * eps);
+    float rn = __builtin_amdgcn_rsqf(sm);
+    rn = rn * fmaf(-0.5f * sm * rn, rn, 1.5f) * scale;
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) kt[srow * LDK + scol + e] = x[e] * rn;
+    for (int e = 0; e < EPT; e += 4)
+      *reinterpret_cast<f4*>(&kt[srow * LDK + scol + e]) = f4{x[e] * rn, x[e + 1] * rn, x[e + 2] * rn, x[e + 3] * rn};
   };
-  auto products = [&](const double* kt) {
+  auto products = [&](const float* kt) {
 #pragma unroll
     for (int kk = tgrp; kk < KS; kk += NGW) {
-      const double* row = &kt[(4 * kk + g) * LDK + c];
+      const float* row = &kt[(4 * kk + g) * LDK + c];
       double bv[NTI];
 #pragma unroll
-      for (int j = 0; j < NTI; ++j) bv[j] = row[16 * j];
+      for (int j = 0; j < NTI; ++j) bv[j] = static_cast<double>(row[16 * j]);
 #pragma unroll
       for (int i = 0; i < TR; ++i) {
-        const double av = RGW == 1 ? bv[i] : row[16 * (rgw * TR + i)];
+        const double av = RGW == 1 ? bv[i] : static_cast<double>(row[16 * (rgw * TR + i)]);
 #pragma unroll
         for (int j = (SYM ? i : 0); j < NTI; ++j)   // SYM: tiles below the diagonal are mirrored at the end
           acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[j], acc[i][j], 0, 0, 0);
@@ -136,7 +141,7 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     for (int u = 0; u < PF; ++u) {
       const int tu = t0 + u * TT;
       if (tu < te) {   // uniform over the workgroup
-        double* kt = ktb[u & 1];
+        float* kt = ktb[u & 1];
         stage(tu, raw[u], kt);
         // the buffer written here was last read two tiles ago, and every wave has passed the barrier of the
         // tile in between since then
