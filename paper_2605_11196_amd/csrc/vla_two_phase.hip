@@ -41,7 +41,8 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
   constexpr int NKB = MAPF ? 2 : 1;            // copies of K^ and W in LDS
   constexpr int NSLAB = D / 16;                // 16-row slabs of a d x d state
   constexpr int SPW = 2 * NSLAB / NW;          // slabs of the map (Q run, then P run) per wave
-  static_assert(!MAPF || (2 * NSLAB) % NW == 0, "whole slabs per wave");
+  static_assert(!MAPF || NSLAB % NW == 0, "whole slabs per wave, the Q run in its first slots");
+  constexpr int QSL = NSLAB / NW;              // slots i < QSL of a wave are Q-run slabs, the others P-run slabs
   constexpr int SL = D / NW;
   constexpr int NJ = SL / 16;
   constexpr int NB = D / 16;
@@ -190,7 +191,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
   const bool do_map = MAPF && seg != a.n_seg - 1;   // nothing follows the last segment
   const IO* vh = static_cast<const IO*>(a.v) + static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   f4 mst[MAPF ? SPW : 1][NB];
-  IO vcur[MAPF ? SPW : 1][4], vnext[MAPF ? SPW : 1][4];
+  IO vcur[MAPF ? SPW : 1][4] = {}, vnext[MAPF ? SPW : 1][4] = {};
   if constexpr (MAPF) {
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
@@ -207,14 +208,12 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
   auto load_map_v = [&](int t0, IO (&vv)[MAPF ? SPW : 1][4]) {
     if constexpr (MAPF) {
 #pragma unroll
-      for (int i = 0; i < SPW; ++i) {
+      for (int i = 0; i < QSL; ++i) {
         const int sl = w + NW * i;
-        if (sl < NSLAB) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int t = t0 + 4 * g + r;
-            vv[i][r] = vh[static_cast<size_t>(t < T ? t : T - 1) * D + sl * 16 + c];
-          }
+        for (int r = 0; r < 4; ++r) {
+          const int t = t0 + 4 * g + r;
+          vv[i][r] = vh[static_cast<size_t>(t < T ? t : T - 1) * D + sl * 16 + c];
         }
       }
     }
@@ -226,10 +225,16 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
       const f4 cg = lds4(&cvs[4 * g]);
 #pragma unroll
       for (int i = 0; i < SPW; ++i) {
-        const int sl = w + NW * i;
-        f4 ft;
+        f4 ft = f4{0, 0, 0, 0};
+        if (i < QSL) {   // known at compile time: the P run starts from v = 0
+          if (t0 + C <= T) {   // uniform: only the ragged last block masks rows past the end
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ft[r] = (sl < NSLAB && t0 + 4 * g + r < T) ? neg_widen(vv[i][r]) : 0.0f;
+            for (int r = 0; r < 4; ++r) ft[r] = neg_widen(vv[i][r]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ft[r] = (t0 + 4 * g + r < T) ? neg_widen(vv[i][r]) : 0.0f;
+          }
+        }
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
           const f4 ka = lds4(&Ksb[kb][c * LD + 16 * b + 4 * g]);
@@ -424,7 +429,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 2 && !MAPF) ? 3 : 2) a_scan_ke
         if (it > 0) map_step(t0 - C, pb ^ 1, vcur);
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-        for (int i = 0; i < SPW; ++i)
+        for (int i = 0; i < QSL; ++i)
 #pragma unroll
           for (int r = 0; r < 4; ++r) vcur[i][r] = vnext[i][r];
       }
