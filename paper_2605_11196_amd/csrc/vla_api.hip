@@ -117,7 +117,7 @@ bool general_path(const vla_opts& o) { return needs_general_kernel(o) || o.featu
 int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
-  if (d != d_v) return needs_general_kernel(o) ? VLA_MODE_SCAN : VLA_MODE_CHUNKED;   // rectangular heads
+  if (d != d_v) return VLA_MODE_CHUNKED;   // rectangular heads: the two block kernels, no segment modes
   const int with_options = vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
   // the identity refresh breaks A_t = M_t^{-1}, which the segment boundaries rest on
   if (o.refresh_period > 0) return with_options;
@@ -150,7 +150,7 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return true;   // every pair of head sizes, with or without options
   if (!vla::chunk_supported(d, d_v)) return false;
-  if (d != d_v) return mode == VLA_MODE_CHUNKED && !needs_general_kernel(o);   // the plain block kernel only
+  if (d != d_v) return mode == VLA_MODE_CHUNKED;   // the two block kernels
   if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::general_block_supported(d);
   // the segment modes carry every option but the identity refresh (A at a segment boundary is the explicit
   // inverse of a prefix sum only without it)
@@ -299,7 +299,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* S0, c
       break;
     case VLA_MODE_CHUNKED:
       err = needs_general_kernel(op)
-                ? vla::launch_chunk_general(a, d_k, io_dtype, static_cast<hipStream_t>(stream))
+                ? vla::launch_chunk_general(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream))
                 : vla::launch_chunk(a, d_k, d_v, io_dtype, static_cast<hipStream_t>(stream));
       break;
     case VLA_MODE_TWO_PHASE:

@@ -35,7 +35,8 @@
 // q_t . zkey_t = q_t . zkey_start + sum_{s<=t} ||k_s|| (Q K^^T)[t][s].
 //
 // Work split: D/16 waves per (batch, head); wave w owns columns [16w, 16w+16) of A and the same rows of S
-// as 16x16 MFMA accumulator tiles resident in VGPRs for the whole sequence.  The C x C Gram matrices are
+// (with a value head size other than D: the row tiles w, w + D/16, ... of S) as 16x16 MFMA accumulator tiles
+// resident in VGPRs for the whole sequence.  The C x C Gram matrices are
 // shared out over the waves (each one contracts over the whole head dimension), the C x C factorisations
 // run on one wave each, rotating with the block index.
 //
@@ -63,9 +64,15 @@ enum GramTile {
 //       chain only, from the A the segment starts with, and writes what the S recurrence needs into the
 //       workspace (the layout of vla_mfma_util.h: 1 / ||k_t||, the write directions alpha_t in W's place, Z,
 //       -NQ^T, -c_t and the reciprocal read-out denominators); S, v and o are not touched.
-template <int D, typename IO, bool FULL, bool SCAN>
+// DV: head size of v and o (rows of S).  The DV / 16 row tiles of S go to the waves in turn (tile t to wave
+//     t % NW: exactly one each for square heads); a wave with fewer tiles than the others, or none, runs its spare
+//     slots on a copy of the last tile and stores nothing from them.
+template <int D, int DV, typename IO, bool FULL, bool SCAN>
 __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_general_kernel(ForwardArgs a) {
   constexpr int NW = D / 16;       // waves; wave w owns columns 16w..16w+15
+  constexpr int TV = DV / 16;      // row tiles of S
+  constexpr int NJV = (TV + NW - 1) / NW;   // tile slots per wave
+  static_assert(DV % 16 == 0 && (!SCAN || DV == D), "whole tiles of S");
   constexpr int NB = D / 16;       // 16-row blocks over the head dimension
   constexpr int LD = D + 4;        // row stride of the token-major LDS arrays
   // Staging: a token row is split over thread slots of EPT elements.  At the power-of-two head sizes every
@@ -120,15 +127,21 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
   const float* Us = FULL ? Usb : nullptr;   // set per block when Y = X
   const float* Xs = FULL ? Xsb : Ys;
 
-  // ---- resident state: At[b][r] = A[16b + 4g + r][col0 + c],  St[b][r] = S[col0 + c][16b + 4g + r]
-  f4 At[NB], St[NB];
+  // first S row of this wave's tile slot jn, and whether the slot holds a tile of its own
+  auto s_row = [&](int jn) -> int {
+    const int t = w + NW * jn;
+    return 16 * (t < TV ? t : TV - 1);
+  };
+  auto owns = [&](int jn) -> bool { return w + NW * jn < TV; };
+  // ---- resident state: At[b][r] = A[16b + 4g + r][col0 + c],  St[jn][b][r] = S[s_row(jn) + c][16b + 4g + r]
+  f4 At[NB], St[NJV][NB];
   {
     const float* A0 = (SCAN && a.seg_A) ? a.seg_A + static_cast<size_t>(blockIdx.x) * D * D
                                         : (a.A0 ? a.A0 + static_cast<size_t>(head) * D * D : nullptr);
-    const float* S0 = (!SCAN && a.S0) ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* S0 = (!SCAN && a.S0) ? a.S0 + static_cast<size_t>(head) * DV * D : nullptr;
     const float diag = 1.0f / a.lambda0;
     const int arc = (4 * g) * D + col0 + c;
-    const int src = (col0 + c) * D + 4 * g;
+    const int src = c * D + 4 * g;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (A0) {
@@ -138,11 +151,14 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
 #pragma unroll
         for (int r = 0; r < 4; ++r) At[b][r] = (16 * b + 4 * g + r == col0 + c) ? diag : 0.0f;
       }
-      if (S0) {
-        const float4 x = *reinterpret_cast<const float4*>(S0 + src + 16 * b);
-        St[b] = f4{x.x, x.y, x.z, x.w};
-      } else {
-        St[b] = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int jn = 0; jn < NJV; ++jn) {
+        if (S0) {
+          const float4 x = *reinterpret_cast<const float4*>(S0 + src + s_row(jn) * D + 16 * b);
+          St[jn][b] = f4{x.x, x.y, x.z, x.w};
+        } else {
+          St[jn][b] = f4{0, 0, 0, 0};
+        }
       }
     }
   }
@@ -161,19 +177,19 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
   const size_t slab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * D;
   const IO* qh = static_cast<const IO*>(a.q) + slab;
   const IO* kh = static_cast<const IO*>(a.k) + slab;
-  const IO* vh = static_cast<const IO*>(a.v) + slab;
+  const size_t slab_v = static_cast<size_t>(head) * static_cast<size_t>(a.T) * DV;
+  const IO* vh = static_cast<const IO*>(a.v) + slab_v;
   const IO* uh = has_u ? static_cast<const IO*>(a.u) + slab : kh;
-  IO* oh = static_cast<IO*>(a.o) + slab;
+  IO* oh = static_cast<IO*>(a.o) + slab_v;
 
   // staging role of this thread: token row and 4-element column segment
   const int srow = tid / TPR;
   const int sseg = (tid % TPR) * EPT;
   const bool stager = !PADDED || (tid < C * TPR && sseg < D);   // this thread holds a row segment
   const bool stage_wave = !PADDED || tid < C * TPR;             // uniform per wave
-  const int vcol = col0 + c;
 
   RawRow<IO, EPT> kpre, qpre, upre;
-  IO vpre[4];  // V in accumulator layout: V[t0 + 4g + r][col0 + c]
+  IO vpre[NJV][4];  // V in accumulator layout: V[t0 + 4g + r][s_row(jn) + c]
 
   // Loads never branch on the row: rows past the end read the last valid row and are zeroed when consumed.
   auto load_kqu = [&](int t0) {
@@ -189,7 +205,9 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int t = t0 + 4 * g + r;
-      vpre[r] = vh[static_cast<unsigned>((t < T ? t : T - 1) * D + vcol)];
+      const unsigned voff = static_cast<unsigned>((t < T ? t : T - 1) * DV + c);
+#pragma unroll
+      for (int jn = 0; jn < NJV; ++jn) vpre[jn][r] = vh[voff + s_row(jn)];
     }
   };
   auto row_total = [&](float x) -> float {
@@ -304,10 +322,14 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
     int cc = c;  // opaque copy: keeps lane-dependent masks from being hoisted out of the loop
     asm volatile("" : "+v"(cc));
 
-    f4 ft = f4{0, 0, 0, 0};  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+    f4 ft[NJV];  // starts as -V^T, becomes -F^T = K^ S0^T - V^T
+#pragma unroll
+    for (int jn = 0; jn < NJV; ++jn) ft[jn] = f4{0, 0, 0, 0};
     if constexpr (!SCAN) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ft[r] = (4 * g + r < len) ? neg_widen(vpre[r]) : 0.0f;
+      for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ft[jn][r] = (4 * g + r < len) ? neg_widen(vpre[jn][r]) : 0.0f;
       if (tn < T) load_v(tn);
     }
 
@@ -328,7 +350,9 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
       }
       if constexpr (!SCAN) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ft = mfma16(ka[r], St[b][r], ft);
+        for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ft[jn] = mfma16(ka[r], St[jn][b][r], ft[jn]);
       }
     }
     if constexpr (FULL) {
@@ -389,14 +413,17 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
     // ================= phase 1 (one wave): Cholesky of I + G and L^{-1}
     const int sw = (blk + head) % NW;
     const int sw2 = (sw + (NW > 2 ? NW / 2 + 1 : 1)) % NW;  // another wave, on another SIMD, forms c, Z, NQ
-    f4 ot;  // R^T = Q S0^T, later O^T
+    f4 ot[NJV];  // R^T = Q S0^T, later O^T
     auto r_pass = [&]() {
-      ot = f4{0, 0, 0, 0};
+#pragma unroll
+      for (int jn = 0; jn < NJV; ++jn) ot[jn] = f4{0, 0, 0, 0};
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         const f4 qa = lds4(&Qs[c * LD + 16 * b + 4 * g]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ot = mfma16(qa[r], St[b][r], ot);
+        for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ot[jn] = mfma16(qa[r], St[jn][b][r], ot[jn]);
       }
     };
     if (w != sw) {
@@ -570,22 +597,32 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
 
     // ================= -E^T = Z (-F^T), O^T = Q S0^T + (-NQ^T)(-E^T), store o;  ce = diag(c) E^T
     if constexpr (!SCAN) {
-    f4 ce;
+    f4 ce[NJV];
     {
       const f4 za = lds4(&Zs[c * LT + 4 * g]);
-      f4 et = f4{0, 0, 0, 0};
+      f4 et[NJV];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
+      for (int jn = 0; jn < NJV; ++jn) {
+        et[jn] = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) et[jn] = mfma16(za[r], ft[jn][r], et[jn]);
+      }
       if (w == sw) r_pass();
       const f4 nqa = lds4(&NQs[c * LT + 4 * g]);
       const f4 cg = lds4(&cvec[4 * g]);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
-      ce = et * cg;
-      if (norm_out) ot *= lds4(&rdens[4 * g]);
+      for (int jn = 0; jn < NJV; ++jn) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (4 * g + r < len) io_store(oh + static_cast<unsigned>((t0 + 4 * g + r) * D + vcol), ot[r]);
+        for (int r = 0; r < 4; ++r) ot[jn] = mfma16(nqa[r], et[jn][r], ot[jn]);
+        ce[jn] = et[jn] * cg;
+        if (norm_out) ot[jn] *= lds4(&rdens[4 * g]);
+        if (owns(jn)) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (4 * g + r < len)
+              io_store(oh + static_cast<unsigned>((t0 + 4 * g + r) * DV + s_row(jn) + c), ot[jn][r]);
+          }
+        }
       }
     }
     // ================= S^T += Alpha diag(c) E^T  (and A -= W W^T on the wave that formed Z)
@@ -593,7 +630,9 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
     for (int b = 0; b < NB; ++b) {
       const f4 aa = lds4(&Ab[(16 * b + c) * LT + 4 * g]);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) St[b] = mfma16(aa[r], ce[r], St[b]);
+      for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) St[jn][b] = mfma16(aa[r], ce[jn][r], St[jn][b]);
     }
     }  // !SCAN
     if (w == sw2) update_A();
@@ -608,9 +647,9 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
   // ---- final state (SCAN: A and the key sum after the last segment; S belongs to phase 2)
   if (!SCAN || seg == a.n_seg - 1) {
     float* AT = a.A_T ? a.A_T + static_cast<size_t>(head) * D * D : nullptr;
-    float* ST = (!SCAN && a.S_T) ? a.S_T + static_cast<size_t>(head) * D * D : nullptr;
+    float* ST = (!SCAN && a.S_T) ? a.S_T + static_cast<size_t>(head) * DV * D : nullptr;
     const int arc = (4 * g) * D + col0 + c;
-    const int src = (col0 + c) * D + 4 * g;
+    const int src = c * D + 4 * g;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (AT) {
@@ -618,7 +657,11 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
         for (int r = 0; r < 4; ++r) AT[arc + (16 * b + r) * D] = At[b][r];
       }
       if (ST) {
-        *reinterpret_cast<float4*>(ST + src + 16 * b) = make_float4(St[b][0], St[b][1], St[b][2], St[b][3]);
+#pragma unroll
+        for (int jn = 0; jn < NJV; ++jn)
+          if (owns(jn))
+            *reinterpret_cast<float4*>(ST + src + s_row(jn) * D + 16 * b) =
+                make_float4(St[jn][b][0], St[jn][b][1], St[jn][b][2], St[jn][b][3]);
       }
     }
     if (a.zkey_T != nullptr && lane < 16) {
@@ -627,14 +670,29 @@ __global__ void __launch_bounds__(4 * D, (SCAN && D <= 64) ? 3 : 1) chunk_genera
   }
 }
 
-template <int D, typename IO>
+template <int D, int DV, typename IO>
 hipError_t launch(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
   const bool full = a.u != nullptr || a.refresh_period > 0;
-  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true, false>)
-                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false, false>);
+  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, DV, IO, true, false>)
+                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, DV, IO, false, false>);
   return hipLaunchKernel(fn, dim3(a.n_heads), dim3(4 * D), params, 0, stream);
+}
+template <int D, int DV>
+hipError_t launch_io(const ForwardArgs& a, int io_dtype, hipStream_t stream) {
+  return io_dtype == 1 ? launch<D, DV, uint16_t>(a, stream) : launch<D, DV, float>(a, stream);
+}
+template <int D>
+hipError_t launch_dv(const ForwardArgs& a, int d_v, int io_dtype, hipStream_t stream) {
+  switch (d_v) {
+    case 16: return launch_io<D, 16>(a, io_dtype, stream);
+    case 32: return launch_io<D, 32>(a, io_dtype, stream);
+    case 64: return launch_io<D, 64>(a, io_dtype, stream);
+    case 96: return launch_io<D, 96>(a, io_dtype, stream);
+    case 128: return launch_io<D, 128>(a, io_dtype, stream);
+    default: return hipErrorInvalidValue;
+  }
 }
 // phase 1 of the two-phase and time-parallel modes with options: one workgroup per (head, segment)
 template <int D, typename IO>
@@ -642,8 +700,8 @@ hipError_t launch_scan(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
   const bool full = a.u != nullptr || a.refresh_period > 0;
-  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, true, true>)
-                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, IO, false, true>);
+  const void* fn = full ? reinterpret_cast<const void*>(&chunk_general_kernel<D, D, IO, true, true>)
+                        : reinterpret_cast<const void*>(&chunk_general_kernel<D, D, IO, false, true>);
   const long long wgs = static_cast<long long>(a.n_heads) * a.n_seg;
   if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
   return hipLaunchKernel(fn, dim3(static_cast<unsigned>(wgs)), dim3(4 * D), params, 0, stream);
@@ -651,14 +709,13 @@ hipError_t launch_scan(const ForwardArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream) {
-  const bool bf = io_dtype == 1;
+hipError_t launch_chunk_general(const ForwardArgs& a, int d, int d_v, int io_dtype, hipStream_t stream) {
   switch (d) {
-    case 16: return bf ? launch<16, uint16_t>(a, stream) : launch<16, float>(a, stream);
-    case 32: return bf ? launch<32, uint16_t>(a, stream) : launch<32, float>(a, stream);
-    case 64: return bf ? launch<64, uint16_t>(a, stream) : launch<64, float>(a, stream);
-    case 96: return bf ? launch<96, uint16_t>(a, stream) : launch<96, float>(a, stream);
-    case 128: return bf ? launch<128, uint16_t>(a, stream) : launch<128, float>(a, stream);
+    case 16: return launch_dv<16>(a, d_v, io_dtype, stream);
+    case 32: return launch_dv<32>(a, d_v, io_dtype, stream);
+    case 64: return launch_dv<64>(a, d_v, io_dtype, stream);
+    case 96: return launch_dv<96>(a, d_v, io_dtype, stream);
+    case 128: return launch_dv<128>(a, d_v, io_dtype, stream);
     default: return hipErrorInvalidValue;
   }
 }

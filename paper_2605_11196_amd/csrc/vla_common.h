@@ -70,7 +70,7 @@ bool prefer_multihead(int d, int n_heads);
 hipError_t launch_chunk_multihead(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 // Same block form with the optional lines of Algorithm 1 (vla_chunk_general.hip); every head size.
 inline bool general_block_supported(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
-hipError_t launch_chunk_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
+hipError_t launch_chunk_general(const ForwardArgs& a, int d, int d_v, int io_dtype, hipStream_t stream);
 // Its A chain alone, one workgroup per (head, time segment), writing the workspace records of the two-phase and
 // time-parallel modes (head sizes 32, 64, 96, 128).
 hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);

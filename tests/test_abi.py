@@ -121,8 +121,8 @@ def call(**kw):
     (dict(zkey0=FAKE + 0x7000, zkey_T=FAKE + 0x7010, normalise_output=1), 1),
     (dict(mode=3, d_k=64, d_v=64, workspace=FAKE + 0x2800, workspace_bytes=1 << 20), 1),   # workspace over v and o
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=48), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
-    (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4, mode=2), 2),   # rectangular heads with
-    (dict(d_k=96, d_v=64, mode=2, refresh_period=4), 2), (dict(d_k=128, d_v=32, mode=2, normalise_output=1), 2),   # options: scan only
+    (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4, mode=3), 2),   # rectangular heads:
+    (dict(d_k=96, d_v=64, mode=4, refresh_period=4), 2), (dict(d_k=128, d_v=32, mode=3, normalise_output=1), 2),   # no segment modes
     (dict(d_k=64, d_v=128, mode=3), 2), (dict(d_k=128, d_v=64, mode=4), 2),
 ])
 def test_host_side_validation_returns_status_without_launch(kw, status):
@@ -174,17 +174,18 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
     assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
-    # every pair of head sizes runs on the block kernel (the waves of a head share out the row tiles of S, evenly
-    # or in turn); with options other than the feature map on the scan kernel
+    # every pair of head sizes runs on the block kernels (the waves of a head share out the row tiles of S, evenly
+    # or in turn), with or without options
     assert vla.resolve_mode(4, 4, 4096, 16, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 64, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 128, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 96, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 64, 16, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_SCAN
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, u=FAKE, refresh_period=20) == vla.MODE_SCAN
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == -1
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, u=FAKE, refresh_period=20) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL, normalise_output=1) == -1
     assert vla.resolve_mode(4, 4, 4096, 32, 48, vla.VLA_BF16) == -1
 
 

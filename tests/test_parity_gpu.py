@@ -487,10 +487,20 @@ def test_many_small_heads_share_a_workgroup(d, B, H, T, dtype):
     print(d, B * H, 16, dtype, errs)
 
 
-@pytest.mark.parametrize("dk,dv", [(32, 128), (64, 96), (128, 16), (96, 32), (16, 64)])
-def test_options_on_heads_with_another_value_size(dk, dv):
-    """Every optional line of Algorithm 1 with d_k != d_v: the token-by-token kernel carries them (AUTO routes
-    there), carried key sum and refresh phase included."""
+OPTION_SETS = {
+    "every option": dict(with_u=True, refresh_period=7, refresh_eta=1e-2, step_offset=3, normalise_output=True,
+                         feature_map=True),
+    "normalised read-out": dict(with_u=False, normalise_output=True, feature_map=True),
+    "penalty direction": dict(with_u=True),
+}
+
+
+@pytest.mark.parametrize("optset", sorted(OPTION_SETS))
+@pytest.mark.parametrize("dk,dv", RECT_PAIRS)
+def test_options_on_heads_with_another_value_size(dk, dv, optset):
+    """The optional lines of Algorithm 1 with d_k != d_v, on the token-by-token kernel (by name) and on the block
+    kernel that carries them (AUTO's choice and by name): carried key sum and refresh phase included, several
+    blocks and a ragged last one."""
     import torch
 
     import paper_2605_11196_amd as vla
@@ -501,15 +511,24 @@ def test_options_on_heads_with_another_value_size(dk, dv):
     v = rng.standard_normal((B, H, T, dv)).astype(np.float32)
     S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
     z0 = np.abs(rng.standard_normal((B, H, dk))).astype(np.float32)
-    opt = dict(lambda0=0.1, u_scale=dk ** -0.5, refresh_period=7, refresh_eta=1e-2, step_offset=3,
-               normalise_output=True, feature_map=True)
-    ref = oracle.forward(q, k, v, S0, None, u=u, zkey0=z0, **opt)
+    opt = dict(OPTION_SETS[optset], lambda0=0.1)
+    with_u = opt.pop("with_u")
+    if with_u:
+        opt["u_scale"] = dk ** -0.5
+    norm = bool(opt.get("normalise_output"))
+    ref = oracle.forward(q, k, v, S0, None, u=u if with_u else None, zkey0=z0 if norm else None, **opt)
     dev = torch.device("cuda:0")
     t = lambda x: torch.from_numpy(x).to(dev)
-    assert vla.resolve_mode(B, H, T, dk, dv, vla.VLA_F32, refresh_period=7) == 1
-    o, S_T, A_T, zk = vla.vla_forward(t(q), t(k), t(v), t(S0), None, u=t(u), zkey0=t(z0), return_zkey=True, **opt)
-    torch.cuda.synchronize()
-    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
-                A=slab_rel_err(to_np(A_T), ref["A_T"], 2), z=slab_rel_err(to_np(zk), ref["zkey_T"], 1))
-    print(dk, dv, errs)
-    assert max(errs.values()) <= 1e-4, errs
+    flags = {kk: vv for kk, vv in opt.items() if kk in ("refresh_period", "normalise_output", "feature_map")}
+    assert vla.resolve_mode(B, H, T, dk, dv, vla.VLA_F32, u=1 if with_u else 0, **flags) == 2
+    for mode in (None, 1, 2):
+        out = vla.vla_forward(t(q), t(k), t(v), t(S0), None, u=t(u) if with_u else None,
+                              zkey0=t(z0) if norm else None, return_zkey=norm, mode=mode, **opt)
+        torch.cuda.synchronize()
+        o, S_T, A_T = out[:3]
+        errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                    A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+        if norm:
+            errs["z"] = slab_rel_err(to_np(out[3]), ref["zkey_T"], 1)
+        print(dk, dv, optset, mode, errs)
+        assert max(errs.values()) <= 1e-4, (mode, errs)
