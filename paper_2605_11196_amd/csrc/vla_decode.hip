@@ -87,10 +87,14 @@ template <int D, int DV, typename IO>
 __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs a) {
   constexpr int EPL = D / 16;                 // floats per lane per row
   constexpr int ROWS_W = D >= 32 ? 32 : D;    // rows of A per wave
-  constexpr int ROWS_WV = ROWS_W * DV / D;    // rows of S per wave
+  constexpr int NWV = D >= 32 ? D / 32 : 1;   // waves
   constexpr int NP = ROWS_W / 4;              // passes over A: a wave instruction covers four rows
-  constexpr int NPV = ROWS_WV / 4;            // passes over S
-  static_assert(ROWS_WV % 4 == 0 && NPV >= 1, "whole passes over S");
+  // The DV / 4 four-row passes over S are shared out over the waves: DV / (4 NWV) consecutive ones each where that
+  // divides (kEven), else pass t goes to wave t % NWV and a wave's spare slots repeat the last pass without storing.
+  constexpr int TPV = DV / 4;
+  constexpr bool kEven = TPV % NWV == 0;
+  constexpr int NPV = kEven ? TPV / NWV : (TPV + NWV - 1) / NWV;   // pass slots per wave
+  static_assert(DV % 4 == 0 && NPV >= 1, "whole passes over S");
   __shared__ float zs[D];
 
   const int head = blockIdx.x;
@@ -100,7 +104,16 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
   const int g = lane >> 4;
   const int col0 = c * EPL;
   const int row0 = ROWS_W * w + g;            // row of A in pass p: row0 + 4 p
-  const int row0v = ROWS_WV * w + g;          // row of S in pass p: row0v + 4 p
+  // row of S in pass slot p of this wave, and whether the slot holds a pass of its own
+  auto s_row = [&](int p) -> int {
+    if constexpr (kEven) {
+      return 4 * (NPV * w + p) + g;
+    } else {
+      const int t = w + NWV * p;
+      return 4 * (t < TPV ? t : TPV - 1) + g;
+    }
+  };
+  auto owns = [&](int p) -> bool { return kEven || w + NWV * p < TPV; };
 
   float* Ah = a.A + static_cast<size_t>(head) * D * D;
   float* Sh = a.S + static_cast<size_t>(head) * DV * D;
@@ -114,12 +127,12 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
 #pragma unroll
   for (int p = 0; p < NP; ++p) load_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
 #pragma unroll
-  for (int p = 0; p < NPV; ++p) load_seg<EPL>(Sh + (row0v + 4 * p) * D + col0, Sr[p]);
+  for (int p = 0; p < NPV; ++p) load_seg<EPL>(Sh + s_row(p) * D + col0, Sr[p]);
   float kk[EPL], qq[EPL], vr[NPV];
   load_io<EPL>(kh + col0, kk);
   load_io<EPL>(qh + col0, qq);
 #pragma unroll
-  for (int p = 0; p < NPV; ++p) vr[p] = widen(vh[row0v + 4 * p]);
+  for (int p = 0; p < NPV; ++p) vr[p] = widen(vh[s_row(p)]);
 
   const float eps = a.eps;
   const float rn = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(kk, kk))), eps);
@@ -161,8 +174,10 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
     const float er = vr[p] - sk;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) Sr[p][e] = fmaf(er, al[e], Sr[p][e]);
-    store_seg<EPL>(Sh + (row0v + 4 * p) * D + col0, Sr[p]);
-    if (c == 0) io_store(oh + row0v + 4 * p, fmaf(er, aq, sq));
+    if (owns(p)) {
+      store_seg<EPL>(Sh + s_row(p) * D + col0, Sr[p]);
+      if (c == 0) io_store(oh + s_row(p), fmaf(er, aq, sq));
+    }
   }
 }
 
@@ -309,13 +324,13 @@ hipError_t launch_rect(const DecodeArgs& a, int n_heads, int io_dtype, hipStream
 
 }  // namespace
 
-// Square heads of every size with or without options; without options also every value head size with key heads
-// of 16, 32, 64 or 128 (a wave's 32 rows of A go with 32 d_v / d_k rows of S, a whole number of four-row passes).
+// Square heads of every size with or without options; without options also every pair of head sizes (the waves
+// share out the four-row passes over S evenly where the counts divide, in turn where they do not).
 bool decode_supported(int d_k, int d_v, bool options) {
   const auto ok = [](int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; };
   if (!ok(d_k) || !ok(d_v)) return false;
   if (d_k == d_v) return true;
-  return !options && d_k != 96;
+  return !options;
 }
 
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,
@@ -332,6 +347,7 @@ hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, 
       VLA_RECT(32, 16) VLA_RECT(32, 64) VLA_RECT(32, 96) VLA_RECT(32, 128)
       VLA_RECT(64, 16) VLA_RECT(64, 32) VLA_RECT(64, 96) VLA_RECT(64, 128)
       VLA_RECT(128, 16) VLA_RECT(128, 32) VLA_RECT(128, 64) VLA_RECT(128, 96)
+      VLA_RECT(96, 16) VLA_RECT(96, 32) VLA_RECT(96, 64) VLA_RECT(96, 128)
 #undef VLA_RECT
       default: return hipErrorInvalidValue;
     }

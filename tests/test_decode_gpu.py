@@ -137,7 +137,7 @@ def test_decode_steps_with_the_optional_lines_of_algorithm_1(d, name, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("dk,dv", [(dk, dv) for dk in (16, 32, 64, 128) for dv in (16, 32, 64, 96, 128) if dk != dv])
+@pytest.mark.parametrize("dk,dv", [(dk, dv) for dk in (16, 32, 64, 96, 128) for dv in (16, 32, 64, 96, 128) if dk != dv])
 def test_decode_steps_with_value_heads_of_another_size(dk, dv, dtype):
     """d_k != d_v in the decode step: S is d_v x d_k, A is d_k x d_k; options are refused for these shapes."""
     import torch
