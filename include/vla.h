@@ -197,8 +197,7 @@ int vla_forward_static(const void* q, const void* k, const void* v, const float*
  *   S      [B, H, d_v, d_k] float32 row-major, updated in place (required)
  *   A      [B, H, d_k, d_k] float32 row-major, updated in place (required; symmetric positive definite)
  *   o      [B, H, d_v]      io_dtype, written; must not overlap any input
- *   d_k, d_v in {16, 32, 64, 96, 128}, any pair; with d_k != d_v without any of the optional lines of
- *          Algorithm 1 (VLA_ERR_UNSUPPORTED otherwise)
+ *   d_k, d_v in {16, 32, 64, 96, 128}, any pair, with or without the optional lines of Algorithm 1
  *   opts   host pointer or NULL.  eps and the optional lines of Algorithm 1 are honoured as in vla_forward
  *          with T = 1: u [B, H, d_k] (io_dtype) with u_scale, the identity refresh (this call is step
  *          step_offset + 1 of the schedule), normalise_output with zkey0 / zkey_T [B, H, d_k] (may alias),

@@ -191,11 +191,17 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_kernel(DecodeArgs
 //   zkey += k;  o /= max(q . zkey, eps) when the read-out is normalised (eq. (output))
 __device__ __forceinline__ float elu1d(float x) { return x > 0.0f ? x + 1.0f : expf(x); }
 
-template <int D, typename IO>
+template <int D, int DV, typename IO>
 __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_general_kernel(DecodeArgs a) {
   constexpr int EPL = D / 16;
   constexpr int ROWS_W = D >= 32 ? 32 : D;
   constexpr int NP = ROWS_W / 4;
+  // the four-row passes over S are shared out over the waves as in decode_kernel
+  constexpr int NWV = D >= 32 ? D / 32 : 1;
+  constexpr int TPV = DV / 4;
+  constexpr bool kEven = TPV % NWV == 0;
+  constexpr int NPV = kEven ? TPV / NWV : (TPV + NWV - 1) / NWV;
+  static_assert(DV % 4 == 0 && NPV >= 1, "whole passes over S");
   __shared__ float zs[D];
   __shared__ float ys[D];
 
@@ -206,21 +212,31 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_general_kernel(De
   const int g = lane >> 4;
   const int col0 = c * EPL;
   const int row0 = ROWS_W * w + g;
+  auto s_row = [&](int p) -> int {
+    if constexpr (kEven) {
+      return 4 * (NPV * w + p) + g;
+    } else {
+      const int t = w + NWV * p;
+      return 4 * (t < TPV ? t : TPV - 1) + g;
+    }
+  };
+  auto owns = [&](int p) -> bool { return kEven || w + NWV * p < TPV; };
 
   float* Ah = a.A + static_cast<size_t>(head) * D * D;
-  float* Sh = a.S + static_cast<size_t>(head) * D * D;
+  float* Sh = a.S + static_cast<size_t>(head) * DV * D;
   const size_t hv = static_cast<size_t>(head) * D;
+  const size_t hvv = static_cast<size_t>(head) * DV;
   const IO* qh = static_cast<const IO*>(a.q) + hv;
   const IO* kh = static_cast<const IO*>(a.k) + hv;
-  const IO* vh = static_cast<const IO*>(a.v) + hv;
-  IO* oh = static_cast<IO*>(a.o) + hv;
+  const IO* vh = static_cast<const IO*>(a.v) + hvv;
+  IO* oh = static_cast<IO*>(a.o) + hvv;
 
-  float Ar[NP][EPL], Sr[NP][EPL];
+  float Ar[NP][EPL], Sr[NPV][EPL];
 #pragma unroll
   for (int p = 0; p < NP; ++p) load_seg<EPL>(Ah + (row0 + 4 * p) * D + col0, Ar[p]);
 #pragma unroll
-  for (int p = 0; p < NP; ++p) load_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
-  float kk[EPL], qq[EPL], uu[EPL], zk[EPL], vr[NP];
+  for (int p = 0; p < NPV; ++p) load_seg<EPL>(Sh + s_row(p) * D + col0, Sr[p]);
+  float kk[EPL], qq[EPL], uu[EPL], zk[EPL], vr[NPV];
   load_io<EPL>(kh + col0, kk);
   load_io<EPL>(qh + col0, qq);
   if (a.feature_map) {
@@ -236,7 +252,7 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_general_kernel(De
 #pragma unroll
   for (int e = 0; e < EPL; ++e) zk[e] = (a.zkey0 ? a.zkey0[hv + col0 + e] : 0.0f) + kk[e];   // key sum after this token
 #pragma unroll
-  for (int p = 0; p < NP; ++p) vr[p] = widen(vh[row0 + 4 * p]);
+  for (int p = 0; p < NPV; ++p) vr[p] = widen(vh[s_row(p)]);
 
   const float eps = a.eps;
   const float inv_nk = 1.0f / fmaxf(sqrtf(row_sum16(dot_seg<EPL>(kk, kk))), eps);
@@ -287,14 +303,16 @@ __global__ void __launch_bounds__(D >= 32 ? 2 * D : 64) decode_general_kernel(De
     store_seg<EPL>(Ah + row * D + col0, Ar[p]);
   }
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
+  for (int p = 0; p < NPV; ++p) {
     const float sk = row_sum16(dot_seg<EPL>(Sr[p], kk)) * inv_nk;
     const float sq = row_sum16(dot_seg<EPL>(Sr[p], qq));
     const float er = vr[p] - sk;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) Sr[p][e] = fmaf(er, al[e], Sr[p][e]);
-    store_seg<EPL>(Sh + (row0 + 4 * p) * D + col0, Sr[p]);
-    if (c == 0) io_store(oh + row0 + 4 * p, fmaf(er, aq, sq) * onorm);
+    if (owns(p)) {
+      store_seg<EPL>(Sh + s_row(p) * D + col0, Sr[p]);
+      if (c == 0) io_store(oh + s_row(p), fmaf(er, aq, sq) * onorm);
+    }
   }
   if (a.zkey_T != nullptr && w == 0 && g == 0) {
 #pragma unroll
@@ -308,29 +326,34 @@ hipError_t launch(const DecodeArgs& a, int n_heads, hipStream_t stream) {
   void* params[] = {&args};
   const bool general = a.u != nullptr || a.refresh != 0 || a.normalise_output != 0 || a.feature_map != 0 ||
                        a.zkey0 != nullptr || a.zkey_T != nullptr;
-  const void* fn = general ? reinterpret_cast<const void*>(&decode_general_kernel<D, IO>)
+  const void* fn = general ? reinterpret_cast<const void*>(&decode_general_kernel<D, D, IO>)
                            : reinterpret_cast<const void*>(&decode_kernel<D, D, IO>);
   return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
 }
-// value heads of another size than the key heads: the plain kernel only
+// value heads of another size than the key heads
 template <int D, int DV>
 hipError_t launch_rect(const DecodeArgs& a, int n_heads, int io_dtype, hipStream_t stream) {
   DecodeArgs args = a;
   void* params[] = {&args};
-  const void* fn = io_dtype == 1 ? reinterpret_cast<const void*>(&decode_kernel<D, DV, uint16_t>)
-                                 : reinterpret_cast<const void*>(&decode_kernel<D, DV, float>);
+  const bool general = a.u != nullptr || a.refresh != 0 || a.normalise_output != 0 || a.feature_map != 0 ||
+                       a.zkey0 != nullptr || a.zkey_T != nullptr;
+  const void* fn =
+      general ? (io_dtype == 1 ? reinterpret_cast<const void*>(&decode_general_kernel<D, DV, uint16_t>)
+                               : reinterpret_cast<const void*>(&decode_general_kernel<D, DV, float>))
+              : (io_dtype == 1 ? reinterpret_cast<const void*>(&decode_kernel<D, DV, uint16_t>)
+                               : reinterpret_cast<const void*>(&decode_kernel<D, DV, float>));
   return hipLaunchKernel(fn, dim3(n_heads), dim3(D >= 32 ? 2 * D : 64), params, 0, stream);
 }
 
 }  // namespace
 
-// Square heads of every size with or without options; without options also every pair of head sizes (the waves
-// share out the four-row passes over S evenly where the counts divide, in turn where they do not).
+// Every pair of head sizes with or without options (the waves share out the four-row passes over S evenly where
+// the counts divide, in turn where they do not).
 bool decode_supported(int d_k, int d_v, bool options) {
   const auto ok = [](int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; };
   if (!ok(d_k) || !ok(d_v)) return false;
-  if (d_k == d_v) return true;
-  return !options;
+  (void)options;
+  return true;
 }
 
 hipError_t launch_decode(const void* q, const void* k, const void* v, float* S, float* A, void* o,

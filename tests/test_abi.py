@@ -145,8 +145,8 @@ def decode_call(**kw):
     (dict(A=FAKE + 0x8004), 1), (dict(o=FAKE + 0x1000), 1),             # misaligned; o aliases k
     (dict(o=FAKE + 0x1000 + 0x20), 1), (dict(A=FAKE + 0x4100), 1),      # o inside k; A inside S (1024 bytes)
     (dict(o=FAKE + 0x4000 + 0x3f0), 1), (dict(u=FAKE + 0x3000 - 0x10), 1),   # o inside S; u ends inside o
-    (dict(d_k=48, d_v=48), 2), (dict(d_k=96, d_v=32, normalise_output=1), 2),
-    (dict(d_k=32, d_v=64, refresh_period=2), 2), (dict(d_k=64, d_v=32, feature_map=1), 2),   # rectangular: no options
+    (dict(d_k=48, d_v=48), 2), (dict(d_k=96, d_v=48, normalise_output=1), 2),
+    (dict(d_k=32, d_v=24, refresh_period=2), 2), (dict(d_k=8, d_v=32, feature_map=1), 2),   # sizes outside the set
     (dict(u=FAKE + 2), 1), (dict(zkey_T=FAKE + 4), 1), (dict(refresh_period=-2), 1),   # option arguments are checked too
 ])
 def test_decode_step_host_side_validation(kw, status):

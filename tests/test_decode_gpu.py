@@ -139,7 +139,7 @@ def test_decode_steps_with_the_optional_lines_of_algorithm_1(d, name, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("dk,dv", [(dk, dv) for dk in (16, 32, 64, 96, 128) for dv in (16, 32, 64, 96, 128) if dk != dv])
 def test_decode_steps_with_value_heads_of_another_size(dk, dv, dtype):
-    """d_k != d_v in the decode step: S is d_v x d_k, A is d_k x d_k; options are refused for these shapes."""
+    """d_k != d_v in the decode step: S is d_v x d_k, A is d_k x d_k."""
     import torch
 
     import paper_2605_11196_amd as vla
@@ -167,7 +167,43 @@ def test_decode_steps_with_value_heads_of_another_size(dk, dv, dtype):
     errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(to_np(S), ref["S_T"], 2),
                 A=slab_rel_err(to_np(A), ref["A_T"], 2))
     assert max(errs.values()) <= TOL[dtype], errs
-    with pytest.raises(vla.VlaError) as e:
-        vla.vla_decode_step(tq[:, :, 0].contiguous(), tk[:, :, 0].contiguous(), tv[:, :, 0].contiguous(), S, A,
-                            feature_map=True)
-    assert e.value.status == 2
+
+
+@pytest.mark.parametrize("name", sorted(OPTION_SETS))
+@pytest.mark.parametrize("dk,dv", [(dk, dv) for dk in (16, 32, 64, 96, 128) for dv in (16, 32, 64, 96, 128) if dk != dv])
+def test_decode_steps_with_options_and_value_heads_of_another_size(dk, dv, name):
+    """The optional lines of Algorithm 1 in the decode step with d_k != d_v (refresh phase and key sum carried
+    from call to call), against the oracle run over the same tokens as one sequence."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+
+    B, H, steps = 1, 3, 13
+    opt = dict(OPTION_SETS[name])
+    rng = np.random.default_rng(dk * 11 + dv)
+    q, k = (rng.standard_normal((B, H, steps, dk)).astype(np.float32) for _ in range(2))
+    v = rng.standard_normal((B, H, steps, dv)).astype(np.float32)
+    u = rng.standard_normal((B, H, steps, dk)).astype(np.float32) if opt.pop("u", False) else None
+    if opt.get("u_scale") == "rsqrt_d":
+        opt["u_scale"] = dk ** -0.5
+    S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
+    ref = oracle.forward(q, k, v, S0, None, lambda0=0.1, u=u, **opt)
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    tu = None if u is None else torch.from_numpy(u).to(dev)
+    S = torch.from_numpy(S0).to(dev)
+    A = (torch.eye(dk, device=dev) * (1.0 / np.float32(0.1))).repeat(B, H, 1, 1).contiguous()
+    zkey = torch.zeros(B, H, dk, device=dev) if opt.get("normalise_output") else None
+    outs = []
+    for t in range(steps):
+        outs.append(vla.vla_decode_step(tq[:, :, t].contiguous(), tk[:, :, t].contiguous(),
+                                        tv[:, :, t].contiguous(), S, A, step_offset=t, zkey=zkey,
+                                        u=None if tu is None else tu[:, :, t].contiguous(), **opt))
+    torch.cuda.synchronize()
+    o = to_np(torch.stack(outs, dim=2))
+    assert o.shape == (B, H, steps, dv)
+    errs = dict(o=slab_rel_err(o, ref["o"], 2), S=slab_rel_err(to_np(S), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A), ref["A_T"], 2))
+    if zkey is not None:
+        errs["zkey"] = slab_rel_err(to_np(zkey), ref["zkey_T"], 1)
+    assert max(errs.values()) <= TOL["f32"], errs
