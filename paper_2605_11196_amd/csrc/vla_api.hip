@@ -121,28 +121,28 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   const int with_options = vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
   // the identity refresh breaks A_t = M_t^{-1}, which the segment boundaries rest on
   if (o.refresh_period > 0) return with_options;
-  if (!vla::block_family_supported(d)) {   // d = 16, 96: no segment modes
+  if (!vla::block_family_supported(d)) {   // d = 16: no segment modes
     return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
   }
   const long long heads = static_cast<long long>(B) * H;
   // Measured crossovers against the fused block kernel (bf16, one MI355X; time-parallel against block kernel, ms).
   // The segment kernels gain on the block kernel as the sequence grows (their fixed passes amortise):
-  //   d = 128:  T = 2048: 64 heads 0.75 / 0.96, 96 heads 1.18 / 0.98;   T = 4096: 96 heads 1.92 / 1.94, 128: 2.28 / 1.94;
-  //             T = 8192: 96 heads 3.24 / 3.86, 128: 3.93 / 3.88;       T = 16384: 128 heads 7.39 / 7.75, 192: 11.4 / 7.7
-  //   d =  96:  T = 2048: 64 heads 0.58 / 0.81, 96: 0.93 / 0.82;        T = 4096: 96 heads 1.56 / 1.64, 128: 1.82 / 1.64;
-  //             T = 8192: 128 heads 3.20 / 3.27;                        T = 16384: 128 heads 5.98 / 6.52; 160 (T = 32768): 15.0 / 13.0
+  //   d = 128:  T = 2048: 64 heads 0.66 / 0.96, 80 heads 1.09 / 0.97;   T = 4096: 96 heads 1.67 / 1.93, 128: 1.99 / 1.93;
+  //             T = 8192: 128 heads 3.66 / 3.85, 160: 4.75 / 3.86;      T = 32768: 128 heads 14.2 / 15.4, 160: 18.9 / 15.4
+  //   d =  96:  T = 1024: 64 heads 0.33 / 0.41, 96: 0.55 / 0.41;        T = 2048: 64 heads 0.52 / 0.82, 80: 0.83 / 0.82;
+  //             T = 4096: 128 heads 1.52 / 1.64, 160: 1.91 / 1.64;      T = 32768: 128 heads 10.5 / 13.1, 160: 13.7 / 13.1
   //   d =  64:  T = 2048: 192 heads 0.53 / 0.63, 256: 0.63 / 0.63;      T = 4096: 256 heads 1.11 / 1.25, 320: 1.37 / 1.38;
   //             T = 16384: 256 heads 4.01 / 4.98, 384: 7.43 / 5.45
   //   d =  32:  T = 2048: 512 heads 0.50 / 0.57, 768: 0.59 / 0.58;      T = 16384: 512 heads 3.57 / 4.54, 768: 4.61 / 4.57
-  const long long few = d >= 96 ? (T >= 16384 ? 128 : (T >= 4096 ? 96 : 64))
+  const int t_128 = d == 96 ? 4096 : 8192;   // from here 128 heads still gain at d >= 96
+  const long long few = d >= 96 ? (T >= t_128 ? 128 : (T >= 4096 ? 96 : 64))
                                 : (d >= 64 ? (T >= 4096 ? 256 : 192) : 512);
   // Short sequences (half the length): 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads
-  // 0.19 against 0.17.  At d = 96 (Gram sums and boundary inverses in the d = 128 layout) the crossover sits one
-  // octave higher (T = 1024: 16 heads 0.29 against 0.41 ms, 64 heads 0.43 against 0.41; T = 512: 16 heads 0.26
-  // against 0.21).
+  // 0.19 against 0.17.  Not at d = 96, whose Gram sums and boundary inverses run in the d = 128 layout (T = 512:
+  // 16 heads 0.26 against 0.21).
   const long long few_short = d >= 96 ? 32 : (d >= 64 ? 64 : 128);
-  const int t_long = d == 96 ? 2048 : 1024;
-  const bool take = T >= t_long ? heads <= few : (2 * T >= t_long && heads <= few_short);
+  const int t_short = d == 96 ? 1024 : 512;
+  const bool take = T >= 1024 ? heads <= few : (T >= t_short && heads <= few_short);
   if (take) return VLA_MODE_TIME_PARALLEL;
   return needs_general_kernel(o) ? with_options : VLA_MODE_CHUNKED;
 }

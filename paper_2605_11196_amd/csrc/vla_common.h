@@ -86,7 +86,7 @@ struct SegmentPlan {
   int n_seg;       // >= 1
   int seg_blocks;  // 16-token blocks per segment
 };
-SegmentPlan plan_segments(int n_heads, int T, int requested);
+SegmentPlan plan_segments(int n_heads, int T, int d, int requested);
 size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments);
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream);

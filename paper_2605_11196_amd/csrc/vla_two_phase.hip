@@ -1039,13 +1039,19 @@ hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream
 // count) and one workgroup on short ones (segments of at least 2 blocks).  Measured at d = 64: 16 heads are
 // fastest with 16 segments from T = 512 (0.10 ms, fused block kernel 0.16 ms) to T = 4096 (0.20 ms), 64 heads
 // with 4 segments up to T = 1024 and 8 at T = 2048, 128 heads with 2-4.
-SegmentPlan plan_segments(int n_heads, int T, int requested) {
+// From d = 96 the A scan holds two workgroups per compute unit and the d^3 work per segment (boundary inverse,
+// composition of the maps) weighs four to eight times more: 512 pairs (one resident round) and segments of at
+// least 32 blocks.  Measured at d = 128, 16 heads: T = 32768 2.00 ms with 32 segments against 2.28 with 64 and
+// 2.52 with 24 (three quarters of a round take as long as a whole one); T = 8192 0.65 with 16 against 0.73 with
+// 32; 8 heads, T = 32768: 1.22 with 64 against 1.59 with 128; d = 96, 16 heads, T = 32768: 1.52 against 1.84.
+SegmentPlan plan_segments(int n_heads, int T, int d, int requested) {
   const int nblk = (T + C - 1) / C;
   int ns = requested;
   if (ns <= 0) {
     const int heads = n_heads < 1 ? 1 : n_heads;
-    const int by_chip = 1024 / heads;
-    const int by_length = nblk / 16;
+    const bool wide = d >= 96;
+    const int by_chip = (wide ? 512 : 1024) / heads;
+    const int by_length = nblk / (wide ? 32 : 16);
     int one_per_cu = 256 / heads;
     if (one_per_cu > nblk / 2) one_per_cu = nblk / 2;
     ns = by_length > one_per_cu ? by_length : one_per_cu;
@@ -1085,14 +1091,14 @@ TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
 }  // namespace
 
 size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments) {
-  const SegmentPlan p = plan_segments(n_heads, T, requested_segments);
+  const SegmentPlan p = plan_segments(n_heads, T, d, requested_segments);
   if (p.n_seg <= 1) return two_phase_workspace_bytes(n_heads, T, d);
   return tp_layout(n_heads, T, d, p.n_seg).total * sizeof(float);
 }
 
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream) {
-  const SegmentPlan p = plan_segments(a.n_heads, a.T, requested_segments);
+  const SegmentPlan p = plan_segments(a.n_heads, a.T, d, requested_segments);
   if (p.n_seg <= 1) return launch_two_phase(a, d, io_dtype, stream);
   const TpLayout l = tp_layout(a.n_heads, a.T, d, p.n_seg);
   ForwardArgs args = a;

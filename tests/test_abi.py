@@ -214,6 +214,11 @@ def test_time_parallel_workspace_follows_the_segment_plan():
     # the library's own choice: about 1024 (head, segment) pairs, segments of at least 16 blocks
     auto = tp(0)
     assert auto == two + B * H * 32 * (d * d * 6 + d * 3) * 4    # 512 blocks / 16 = 32 < 1024 / 16 heads = 64
+    # from d = 96: about 512 pairs, segments of at least 32 blocks
+    for (T2, want) in ((8192, 16), (32768, 32), (131072, 32)):
+        two2 = vla.vla_forward_workspace_bytes(B, H, T2, 128, 128, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
+        got = vla.vla_forward_workspace_bytes(B, H, T2, 128, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL)
+        assert got == two2 + B * H * want * (128 * 128 * 6 + 128 * 3) * 4, T2
 
 
 def test_torch_front_end_refuses_cpu_tensors():
