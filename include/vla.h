@@ -125,7 +125,9 @@ void vla_default_opts(vla_opts* opts);
 
 /* Bytes of device workspace vla_forward needs for these arguments (0 for the
  * modes that need none).  Returns 0 as well when the arguments are invalid --
- * vla_forward will then report the error. */
+ * vla_forward will then report the error.  Pass the options of the call itself: with `segments` left at 0
+ * the number of segments, and so the size, also depends on whether u, normalise_output or the zkey
+ * pointers are set (a workspace sized for other options may be refused with VLA_ERR_WORKSPACE). */
 size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io_dtype,
                                    const vla_opts* opts);
 

@@ -217,7 +217,9 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   if (!mode_available(mode, d_k, d_v, o)) return 0;
   if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return 0;
   if (mode == VLA_MODE_TWO_PHASE) return vla::two_phase_workspace_bytes(B * H, T, d_k);
-  if (mode == VLA_MODE_TIME_PARALLEL) return vla::time_parallel_workspace_bytes(B * H, T, d_k, o.segments);
+  if (mode == VLA_MODE_TIME_PARALLEL) {
+    return vla::time_parallel_workspace_bytes(B * H, T, d_k, needs_general_kernel(o), o.segments);
+  }
   return 0;
 }
 

@@ -86,8 +86,9 @@ struct SegmentPlan {
   int n_seg;       // >= 1
   int seg_blocks;  // 16-token blocks per segment
 };
-SegmentPlan plan_segments(int n_heads, int T, int d, int requested);
-size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments);
+// `general`: the call carries a separate penalty direction or the normalised read-out
+SegmentPlan plan_segments(int n_heads, int T, int d, bool general, int requested);
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, bool general, int requested_segments);
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream);
 // Boundary kernels (vla_segments.hip).  All buffers are device memory inside the caller's workspace.

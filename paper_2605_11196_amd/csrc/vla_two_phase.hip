@@ -960,6 +960,12 @@ hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
                          dim3(a.n_heads * a.n_seg), dim3(64 * (D / 16) * (MAP ? 2 : 1)), params, 0, stream);
 }
 
+// true when the call switches on a separate penalty direction or the normalised read-out (the feature map
+// alone runs on the plain kernels)
+bool runs_on_option_kernel(const ForwardArgs& a) {
+  return a.u != nullptr || a.normalise_output != 0 || a.zkey0 != nullptr || a.zkey_T != nullptr;
+}
+
 // Phase 1 and 2 over every (head, segment) of `a`.
 template <int D, int NW, typename IO>
 hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
@@ -969,7 +975,7 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   if (hs * (D / 8) > 0x7fffffffLL) return hipErrorInvalidValue;   // the largest grid below: 2 D/16 waves per pair
   // A separate penalty direction or the normalised read-out: the A chain of the block kernel that carries
   // them; its records have the layout the S-row kernels below read.
-  const bool general = a.u != nullptr || a.normalise_output != 0 || a.zkey0 != nullptr || a.zkey_T != nullptr;
+  const bool general = runs_on_option_kernel(a);
   // Up to d = 64 the plain A scan also forms the per-segment affine maps of S (its registers hold them beside A).
   constexpr bool kFusedMap = D <= 64;
   // Worth it once the (head, segment) pairs fill the chip (measured at 16 heads, d = 64: 3 % faster at 1024
@@ -1044,14 +1050,19 @@ hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream
 // least 32 blocks.  Measured at d = 128, 16 heads: T = 32768 2.00 ms with 32 segments against 2.28 with 64 and
 // 2.52 with 24 (three quarters of a round take as long as a whole one); T = 8192 0.65 with 16 against 0.73 with
 // 32; 8 heads, T = 32768: 1.22 with 64 against 1.59 with 128; d = 96, 16 heads, T = 32768: 1.52 against 1.84.
-SegmentPlan plan_segments(int n_heads, int T, int d, int requested) {
+// With the options (`general`: the A chain runs on the option kernel, three workgroups per compute unit at
+// d = 64) a resident round is 768 pairs at d = 64, and the longer chain favours segments of 32 blocks there too:
+// 16 heads, T = 131072: 3.04 ms with 48 segments against 3.15 with 64; T = 16384: 0.49 with 32 against 0.55
+// with 64; 8 heads, T = 65536: 0.90 with 96 against 1.00 with 128.
+SegmentPlan plan_segments(int n_heads, int T, int d, bool general, int requested) {
   const int nblk = (T + C - 1) / C;
   int ns = requested;
   if (ns <= 0) {
     const int heads = n_heads < 1 ? 1 : n_heads;
     const bool wide = d >= 96;
-    const int by_chip = (wide ? 512 : 1024) / heads;
-    const int by_length = nblk / (wide ? 32 : 16);
+    const bool long_chain = wide || (general && d == 64);
+    const int by_chip = (wide ? 512 : (long_chain ? 768 : 1024)) / heads;
+    const int by_length = nblk / (long_chain ? 32 : 16);
     int one_per_cu = 256 / heads;
     if (one_per_cu > nblk / 2) one_per_cu = nblk / 2;
     ns = by_length > one_per_cu ? by_length : one_per_cu;
@@ -1090,15 +1101,15 @@ TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
 }
 }  // namespace
 
-size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int requested_segments) {
-  const SegmentPlan p = plan_segments(n_heads, T, d, requested_segments);
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, bool general, int requested_segments) {
+  const SegmentPlan p = plan_segments(n_heads, T, d, general, requested_segments);
   if (p.n_seg <= 1) return two_phase_workspace_bytes(n_heads, T, d);
   return tp_layout(n_heads, T, d, p.n_seg).total * sizeof(float);
 }
 
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream) {
-  const SegmentPlan p = plan_segments(a.n_heads, a.T, d, requested_segments);
+  const SegmentPlan p = plan_segments(a.n_heads, a.T, d, runs_on_option_kernel(a), requested_segments);
   if (p.n_seg <= 1) return launch_two_phase(a, d, io_dtype, stream);
   const TpLayout l = tp_layout(a.n_heads, a.T, d, p.n_seg);
   ForwardArgs args = a;

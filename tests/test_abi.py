@@ -214,6 +214,13 @@ def test_time_parallel_workspace_follows_the_segment_plan():
     # the library's own choice: about 1024 (head, segment) pairs, segments of at least 16 blocks
     auto = tp(0)
     assert auto == two + B * H * 32 * (d * d * 6 + d * 3) * 4    # 512 blocks / 16 = 32 < 1024 / 16 heads = 64
+    # with a separate penalty direction or the normalised read-out at d = 64: about 768 pairs, 32 blocks
+    for (T2, want) in ((131072, 48), (16384, 32), (4096, 16)):
+        two2 = vla.vla_forward_workspace_bytes(B, H, T2, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE,
+                                               normalise_output=1)
+        got = vla.vla_forward_workspace_bytes(B, H, T2, d, d, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL,
+                                              normalise_output=1)
+        assert got == two2 + B * H * want * (d * d * 6 + d * 3) * 4, T2
     # from d = 96: about 512 pairs, segments of at least 32 blocks
     for (T2, want) in ((8192, 16), (32768, 32), (131072, 32)):
         two2 = vla.vla_forward_workspace_bytes(B, H, T2, 128, 128, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
