@@ -13,6 +13,7 @@
 // The S recurrence is affine in S (eq. (s-update)): S_end = S_start P + Q per segment.  P and Q come from the
 // map pass of the S-rows kernel; combine_kernel composes them from left to right.
 #include "vla_mfma_util.h"
+#include <type_traits>
 
 namespace vla {
 namespace {
@@ -29,10 +30,12 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 // B[k = l / 16][j = l % 16] and receives D[i = l / 16 + 4 r][j = l % 16] in element r), both operands being the
 // same staged tile widened as it is read: a product of two float32 values is exact in float64.  A wave
 // holds at most 16 result tiles: up to D = 64 every wave covers the whole matrix and the waves take the
-// tokens of a tile in turn (summed through LDS at the end); at D = 128 each wave owns two tile rows.
+// tokens of a tile in turn (summed through LDS at the end); at D = 128 wave w owns the tile rows w and
+// DL/16 - 1 - w from the diagonal on (DL/16 + 1 tiles whatever w: the sum is symmetric, the tiles below the
+// diagonal are mirrored at the end).
 // DL: the head size of the data; D >= DL: the size the tiles are laid out for.  They differ for d = 96, which
 // runs in the d = 128 layout with the columns from 96 on held at zero (the loads, the staging and the final
-// stores skip them).
+// stores skip them; three of the four waves then form the products).
 template <int D, int DL, typename IO>
 __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(ForwardArgs a, double* G) {
   static_assert(DL <= D && DL % 16 == 0, "padded layout");
@@ -46,9 +49,14 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   constexpr int EPT = TT * D / kThreads;                     // elements of the tile each thread stages
   constexpr int TPR = D / EPT;                               // threads per token row
   static_assert(RGW * NGW * 64 == kThreads && KS % NGW == 0 && (TPR == 4 || TPR == 8) && EPT % 4 == 0, "layout");
-  // The sum of k^ k^T is symmetric: where a wave covers the whole matrix it forms the tiles on and above the
-  // diagonal only (10 of 16 at d = 64).
-  constexpr bool SYM = RGW == 1;
+  // The sum of k^ k^T is symmetric: only the tiles on and above the diagonal are formed (10 of 16 at d = 64,
+  // 36 of 64 at d = 128).  Where a wave cannot hold the whole matrix the tile rows are paired so that every
+  // wave has the same number of them.
+  constexpr bool PAIR = RGW > 1;
+  constexpr int NTL = DL / 16;                               // tile rows that hold data
+  constexpr int NPT = NTL + 1;                               // tiles of a wave's pair of rows
+  static_assert(PAIR ? (NTL % 2 == 0 && NTL / 2 <= RGW && NGW == 1) : (RGW == 1 && D == DL),
+                "row w pairs with row NTL - 1 - w; otherwise every wave covers the whole matrix");
   __shared__ __align__(16) float ktb[2][TT * LDK];   // double-buffered: one barrier per tile
   static_assert(NGW == 1 || 2 * TT * LDK * sizeof(float) >= D * D * sizeof(double),
                 "the final sum over the waves reuses the tile buffers");
@@ -62,7 +70,6 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   const int lane = tid & 63;
   const int c = lane & 15;
   const int g = lane >> 4;
-  const int rgw = w % RGW;      // which tile rows
   const int tgrp = w / RGW;     // which k-steps
   const int tb = seg * a.seg_blocks * C;
   const int te = min(a.T, tb + a.seg_blocks * C);
@@ -74,11 +81,14 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
   const int srow = tid / TPR;
   const int scol = (tid % TPR) * EPT;
 
-  d4 acc[TR][NTI];
+  d4 acc[PAIR ? 1 : TR][PAIR ? 1 : NTI];   // every wave covers the whole matrix, or whole tile rows
+  d4 pacc[PAIR ? NPT : 1];                 // paired rows: row w from its diagonal tile on, then row NTL - 1 - w
 #pragma unroll
-  for (int i = 0; i < TR; ++i)
+  for (int i = 0; i < (PAIR ? 1 : TR); ++i)
 #pragma unroll
-    for (int j = 0; j < NTI; ++j) acc[i][j] = d4{0, 0, 0, 0};
+    for (int j = 0; j < (PAIR ? 1 : NTI); ++j) acc[i][j] = d4{0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < (PAIR ? NPT : 1); ++i) pacc[i] = d4{0, 0, 0, 0};
 
   // Fragments of the next PF tiles are kept in flight in raw form (a few registers each): with a thousand
   // workgroups streaming at once the memory latency is several tiles' worth of work.
@@ -117,19 +127,65 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     for (int e = 0; e < EPT; e += 4)
       *reinterpret_cast<f4*>(&kt[srow * LDK + scol + e]) = f4{x[e] * rn, x[e + 1] * rn, x[e + 2] * rn, x[e + 3] * rn};
   };
-  auto products = [&](const float* kt) {
+  // paired rows, for the wave W (a compile-time copy of w): tiles (W, W..NTL-1) then (R1, R1..NTL-1)
+  auto pair_products = [&](auto wtag, const float* kt) {
+    constexpr int W = decltype(wtag)::value;
+    constexpr int R1 = NTL - 1 - W;
 #pragma unroll
-    for (int kk = tgrp; kk < KS; kk += NGW) {
+    for (int kk = 0; kk < KS; ++kk) {
       const float* row = &kt[(4 * kk + g) * LDK + c];
-      double bv[NTI];
+      double bv[NTL];
 #pragma unroll
-      for (int j = 0; j < NTI; ++j) bv[j] = static_cast<double>(row[16 * j]);
+      for (int j = W; j < NTL; ++j) bv[j] = static_cast<double>(row[16 * j]);
 #pragma unroll
-      for (int i = 0; i < TR; ++i) {
-        const double av = RGW == 1 ? bv[i] : static_cast<double>(row[16 * (rgw * TR + i)]);
+      for (int j = W; j < NTL; ++j)
+        pacc[j - W] = __builtin_amdgcn_mfma_f64_16x16x4f64(bv[W], bv[j], pacc[j - W], 0, 0, 0);
 #pragma unroll
-        for (int j = (SYM ? i : 0); j < NTI; ++j)   // SYM: tiles below the diagonal are mirrored at the end
-          acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[j], acc[i][j], 0, 0, 0);
+      for (int j = R1; j < NTL; ++j)
+        pacc[NTL - W + j - R1] = __builtin_amdgcn_mfma_f64_16x16x4f64(bv[R1], bv[j], pacc[NTL - W + j - R1], 0, 0, 0);
+    }
+  };
+  // element r of the tile (i, j) is G[16 i + g + 4 r][16 j + c]; its mirror image fills the tile (j, i)
+  auto pair_store = [&](auto wtag, double* Gh) {
+    constexpr int W = decltype(wtag)::value;
+    constexpr int R1 = NTL - 1 - W;
+    auto put = [&](int i, int j, const d4& t) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = 16 * i + g + 4 * r, col = 16 * j + c;
+        Gh[row * DL + col] = t[r];
+        if (j > i) Gh[col * DL + row] = t[r];
+      }
+    };
+#pragma unroll
+    for (int j = W; j < NTL; ++j) put(W, j, pacc[j - W]);
+#pragma unroll
+    for (int j = R1; j < NTL; ++j) put(R1, j, pacc[NTL - W + j - R1]);
+  };
+  // the wave's own copy of the two above (w is uniform over the wave)
+  auto for_my_rows = [&](auto&& f) {
+    if constexpr (PAIR) {
+      if (w == 0) f(std::integral_constant<int, 0>{});
+      if (w == 1 && NTL >= 4) f(std::integral_constant<int, (NTL >= 4 ? 1 : 0)>{});
+      if (w == 2 && NTL >= 6) f(std::integral_constant<int, (NTL >= 6 ? 2 : 0)>{});
+      if (w == 3 && NTL >= 8) f(std::integral_constant<int, (NTL >= 8 ? 3 : 0)>{});
+    }
+  };
+  auto products = [&](const float* kt) {
+    if constexpr (PAIR) {
+      for_my_rows([&](auto wtag) { pair_products(wtag, kt); });
+    } else {
+#pragma unroll
+      for (int kk = tgrp; kk < KS; kk += NGW) {
+        const float* row = &kt[(4 * kk + g) * LDK + c];
+        double bv[NTI];
+#pragma unroll
+        for (int j = 0; j < NTI; ++j) bv[j] = static_cast<double>(row[16 * j]);
+#pragma unroll
+        for (int i = 0; i < TR; ++i)
+#pragma unroll
+          for (int j = i; j < NTI; ++j)   // tiles below the diagonal are mirrored at the end
+            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(bv[i], bv[j], acc[i][j], 0, 0, 0);
       }
     }
   };
@@ -152,41 +208,29 @@ __global__ void __launch_bounds__(kThreads, D <= 64 ? 3 : 2) gram_kernel(Forward
     }
   }
 
-  // element r of tile (i, j) is G[16 (rgw TR + i) + g + 4 r][16 j + c]
   double* Gh = G + static_cast<size_t>(blockIdx.x) * DL * DL;
-  if constexpr (NGW == 1) {
-#pragma unroll
-    for (int i = 0; i < TR; ++i)
-#pragma unroll
-      for (int j = (SYM ? i : 0); j < NTI; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = 16 * (rgw * TR + i) + g + 4 * r, col = 16 * j + c;
-          if (D == DL || (row < DL && col < DL)) {
-            Gh[row * DL + col] = acc[i][j][r];
-            if (SYM && j > i) Gh[col * DL + row] = acc[i][j][r];
-          }
-        }
+  if constexpr (PAIR) {
+    for_my_rows([&](auto wtag) { pair_store(wtag, Gh); });
   } else {
+    // element r of tile (i, j) is G[16 i + g + 4 r][16 j + c]; the waves' partial sums meet in LDS
     __syncthreads();   // every wave is done with the tile buffers
     for (int gi = 0; gi < NGW; ++gi) {
       if (tgrp == gi) {
 #pragma unroll
         for (int i = 0; i < TR; ++i)
 #pragma unroll
-          for (int j = (SYM ? i : 0); j < NTI; ++j)
+          for (int j = i; j < NTI; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const int o = (16 * (rgw * TR + i) + g + 4 * r) * D + 16 * j + c;
+              const int o = (16 * i + g + 4 * r) * D + 16 * j + c;
               red[o] = gi == 0 ? acc[i][j][r] : red[o] + acc[i][j][r];
             }
       }
       __syncthreads();
     }
-    static_assert(NGW == 1 || D == DL, "the padded layout is only used where each wave owns its tile rows");
     for (int o = tid; o < D * D; o += kThreads) {
       const int row = o / D, col = o - row * D;
-      Gh[o] = (SYM && row / 16 > col / 16) ? red[col * D + row] : red[o];   // tile below the diagonal: mirror
+      Gh[o] = row / 16 > col / 16 ? red[col * D + row] : red[o];   // tile below the diagonal: mirror
     }
   }
 }
