@@ -11,7 +11,7 @@ kernel (HIP-event timed on the launch stream) and the fp64 oracle timed on the h
 cores on a bounded sample of the same workload (a reported baseline, not a target).
 The default run adds a `secondary` array to the same line: the other head size the
 metric is quoted at (d_h = 64 at large batch), the long-context sweep (five sequence
-lengths, the library's own choice of mode), the large-batch workload with every optional
+lengths at d_h = 64 and one at d_h = 128, the library's own choice of mode), the large-batch workload with every optional
 line of Algorithm 1 switched on, and the decode step; each entry is timed the same way
 (median of at least 10 launches) and checked against the oracle on a few heads.
 """
@@ -377,6 +377,8 @@ def main():
         for T in make_case("long_context")["T_sweep"]:
             sec.append(secondary_entry(f"long_context_T{T}", forward_case(
                 make_case("long_context", T=T), steps=k3, warmup=w3, oracle_heads=2)))
+        sec.append(secondary_entry("long_context_T32768_d128", forward_case(
+            make_case("long_context", T=32768, d=128), steps=k3, warmup=w3, oracle_heads=1)))
         sec.append(secondary_entry("long_context_T131072_options_no_refresh", forward_case(
             make_case("long_context", T=131072), options="paper_no_refresh", steps=k3, warmup=w3, oracle_heads=2)))
         sec.append(secondary_entry("large_batch_options_paper", forward_case(
