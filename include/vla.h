@@ -46,8 +46,8 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
 /* Which kernel family runs the recurrence.
  *   AUTO     : the library picks: CHUNKED when the identity refresh is switched on or the shape has no
  *              segment kernels; else TIME_PARALLEL for few heads (d = 128 and 96: B*H <= 64, 96 from
- *              T = 4096, 128 from T = 8192 (from 4096 at d = 96); d = 64: 192, 256 from T = 4096;
- *              d = 32: 512) and T >= 1024, or from T = 512 for B*H <= 32, 64, 128 heads at d = 128, 64,
+ *              T = 4096, 128 from T = 8192 (from 4096 at d = 96); d = 64: 192, 320 from T = 4096;
+ *              d = 32: 512) and T >= 1024, or from T = 512 for B*H <= 32, 64, 256 heads at d = 128, 64,
  *              32, if the caller passed the workspace
  *              vla_forward_workspace_bytes() asks for (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S

@@ -131,16 +131,16 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   //             T = 8192: 128 heads 3.66 / 3.85, 160: 4.75 / 3.86;      T = 32768: 128 heads 14.2 / 15.4, 160: 18.9 / 15.4
   //   d =  96:  T = 1024: 64 heads 0.33 / 0.41, 96: 0.55 / 0.41;        T = 2048: 64 heads 0.52 / 0.82, 80: 0.83 / 0.82;
   //             T = 4096: 128 heads 1.52 / 1.64, 160: 1.91 / 1.64;      T = 32768: 128 heads 10.5 / 13.1, 160: 13.7 / 13.1
-  //   d =  64:  T = 2048: 192 heads 0.53 / 0.63, 256: 0.63 / 0.63;      T = 4096: 256 heads 1.11 / 1.25, 320: 1.37 / 1.38;
-  //             T = 16384: 256 heads 4.01 / 4.98, 384: 7.43 / 5.45
-  //   d =  32:  T = 2048: 512 heads 0.50 / 0.57, 768: 0.59 / 0.58;      T = 16384: 512 heads 3.57 / 4.54, 768: 4.61 / 4.57
+  //   d =  64:  T = 2048: 192 heads 0.51 / 0.63, 256: 0.60 / 0.63, 320: 0.73 / 0.69;   T = 4096: 320 heads 1.33 / 1.38,
+  //             384: 1.78 / 1.38;                                       T = 16384: 320 heads 5.13 / 5.48, 384: 7.02 / 5.47
+  //   d =  32:  T = 2048: 512 heads 0.51 / 0.57, 640: 0.59 / 0.58;      T = 16384: 512 heads 3.71 / 4.54, 640: 4.59 / 4.56
   const int t_128 = d == 96 ? 4096 : 8192;   // from here 128 heads still gain at d >= 96
   const long long few = d >= 96 ? (T >= t_128 ? 128 : (T >= 4096 ? 96 : 64))
-                                : (d >= 64 ? (T >= 4096 ? 256 : 192) : 512);
-  // Short sequences (half the length): 16 and 64 heads at d = 64, T = 512: 0.10 and 0.13 against 0.16 ms; 128 heads
-  // 0.19 against 0.17.  Not at d = 96, whose Gram sums and boundary inverses run in the d = 128 layout (T = 512:
+                                : (d >= 64 ? (T >= 4096 ? 320 : 192) : 512);
+  // Short sequences (half the length): 64 heads at d = 64, T = 512: 0.11 against 0.16 ms, 128 heads 0.16 against
+  // 0.16; 256 heads at d = 32: 0.12 against 0.14, 512 heads 0.15 against 0.15.  Not at d = 96, whose Gram sums and boundary inverses run in the d = 128 layout (T = 512:
   // 16 heads 0.26 against 0.21).
-  const long long few_short = d >= 96 ? 32 : (d >= 64 ? 64 : 128);
+  const long long few_short = d >= 96 ? 32 : (d >= 64 ? 64 : 256);
   const int t_short = d == 96 ? 1024 : 512;
   const bool take = T >= 1024 ? heads <= few : (T >= t_short && heads <= few_short);
   if (take) return VLA_MODE_TIME_PARALLEL;

@@ -19,7 +19,7 @@ SHAPES = [  # (d, heads, T)
     (128, 8, 1500), (128, 24, 700), (128, 40, 9000), (128, 80, 6000), (128, 112, 20000), (128, 160, 4096), (128, 512, 2048),
     (32, 32, 800), (32, 200, 3000), (32, 300, 6000), (32, 1500, 2048),
     (96, 16, 1500), (96, 40, 6000), (96, 112, 20000), (96, 200, 3000), (96, 48, 1100), (96, 120, 5000),
-    (128, 120, 10000), (128, 8, 40000),
+    (128, 120, 10000), (128, 8, 40000), (64, 300, 6000), (32, 200, 600),
 ]
 
 
