@@ -989,9 +989,11 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
                            : hipLaunchKernel(scan_fn, dim3(static_cast<unsigned>(hs)), dim3(64 * NW), params, 0,
                                              stream);
   if (err != hipSuccess) return err;
-  // With enough (head, segment) pairs to fill the chip the block operands are shared through LDS by a
-  // workgroup per pair; with few, one wave per slab of S and deep register prefetch give the most waves.
-  const bool shared = hs >= 256;
+  // From half a chip of (head, segment) pairs the block operands are shared through LDS by a workgroup per
+  // pair; with fewer, one wave per slab of S and deep register prefetch (measured, whole call, LDS kernel
+  // against the other: 240 to 255 pairs -7 to -13 % at d = 64, -8 to -25 % at d = 128; 128 pairs -3.5 and
+  // -0.4 %; 9 to 32 pairs +2 to +8 %).
+  const bool shared = hs >= 128;
   auto rows = [&](auto map_tag) -> hipError_t {
     constexpr bool kMap = decltype(map_tag)::value;
     return shared ? launch_s_rows_lds<D, IO, kMap>(a, stream) : launch_s_rows<D, IO, kMap>(a, stream);
