@@ -1063,12 +1063,22 @@ SegmentPlan plan_segments(int n_heads, int T, int d, bool general, int requested
     const int heads = n_heads < 1 ? 1 : n_heads;
     const bool wide = d >= 96;
     const bool long_chain = wide || (general && d == 64);
-    const int by_chip = (wide ? 512 : (long_chain ? 768 : 1024)) / heads;
+    const int most_pairs = wide ? 512 : (long_chain ? 768 : 1024);
+    const int by_chip = most_pairs / heads;
     const int by_length = nblk / (long_chain ? 32 : 16);
     int one_per_cu = 256 / heads;
     if (one_per_cu > nblk / 2) one_per_cu = nblk / 2;
     ns = by_length > one_per_cu ? by_length : one_per_cu;
     if (ns > by_chip) ns = by_chip;
+    // Whole rounds of 256 pairs: a compute unit that gets a second workgroup of the S-row kernels while others
+    // have one takes twice as long over it.  24 heads, d = 64, T = 16384: 21 segments (504 pairs) 0.57 ms, 22
+    // segments 0.68; T = 4096: 16 segments (384 pairs) 0.23, 21 segments 0.22, 10 segments 0.23, 11 segments 0.30;
+    // d = 128, T = 8192: 16 segments 1.05, 21 segments 0.92.
+    if (heads <= 128 && ns * heads > 256) {
+      int rounds = (ns * heads + 128) / 256;
+      if (rounds > most_pairs / 256) rounds = most_pairs / 256;
+      ns = 256 * rounds / heads;
+    }
   }
   if (ns > 256) ns = 256;
   if (ns > nblk) ns = nblk;

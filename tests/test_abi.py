@@ -221,6 +221,11 @@ def test_time_parallel_workspace_follows_the_segment_plan():
         got = vla.vla_forward_workspace_bytes(B, H, T2, d, d, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL,
                                               normalise_output=1)
         assert got == two2 + B * H * want * (d * d * 6 + d * 3) * 4, T2
+    # whole rounds of 256 pairs: 24 heads x 16 segments would be a round and a half; two rounds = 21 segments
+    # asked for, 256 blocks in segments of ceil(256 / 21) = 13 blocks -> 20 segments
+    two24 = vla.vla_forward_workspace_bytes(1, 24, 4096, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
+    got = vla.vla_forward_workspace_bytes(1, 24, 4096, d, d, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL)
+    assert got == two24 + 24 * 20 * (d * d * 6 + d * 3) * 4
     # from d = 96: about 512 pairs, segments of at least 32 blocks
     for (T2, want) in ((8192, 16), (32768, 32), (131072, 32)):
         two2 = vla.vla_forward_workspace_bytes(B, H, T2, 128, 128, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
