@@ -324,103 +324,103 @@ __global__ void __launch_bounds__(kThreads) keysum_prefix_kernel(const double* p
 
 // ------------------------------------------------------------------------------------------ boundary
 // Gauss-Jordan inverse, in place, of a symmetric positive definite D x D matrix spread over the workgroup's
-// registers (no pivoting needed for such a matrix): thread (rg, j) holds m[n] = M[rg + RG n][j].
+// registers (no pivoting needed for such a matrix) in the result layout of the float64 matrix instruction:
+// wave w holds the tile row w, lane (g, c) of it acc[tj][r] = M[16 w + g + 4 r][16 tj + c].
 //
-// The sweep eliminates KB pivots at a time.  With P the pivot indices of a step, B = M[P][P], C = M[:, P] and
-// R = M[P, :], the in-place step is  M <- M - C' R'  with
+// The sweep eliminates KB = 4 pivots at a time.  With P the pivot indices of a step, B = M[P][P], C = M[:, P]
+// and R = M[P, :], the in-place step is  M <- M - C' R'  with
 //   C'[i] = C[i] (i not in P),  C'[P] = B - I;     R'[:, j] = B^{-1} R[:, j] (j not in P),  R'[:, P] = I + B^{-1}
 // which is the usual block sweep (Schur complement off the pivot rows and columns, -C B^{-1} in the pivot
 // columns, B^{-1} R in the pivot rows, B^{-1} in the pivot block) written so that every element takes the same
-// KB fused multiply-adds and no thread has to pick out "its" pivot elements.  The pivot rows are not fetched at
+// rank-4 update: one v_mfma_f64_16x16x4_f64 per 16 x 16 tile and step.  The pivot rows are not fetched at
 // all: after the earlier steps the not yet eliminated part of M is a Schur complement (symmetric) and the
 // eliminated part of a pivot row is minus the transposed column, so R[a][j] = C[j][a] for j after P and -C[j][a]
-// for j before it.  Only the KB pivot columns go through LDS (their owners copy their registers out, with the
-// identity already subtracted from the pivot block), double-buffered: one barrier per KB pivots.  Every thread
-// factors the KB x KB block B = L diag(dd) L^T for itself in registers and applies B^{-1} to its own column
-// entries by two triangular solves (B^{-1} itself is never formed; the pivot columns get theirs from the
-// identity x = e_e - B^{-1} e_e that the stored B - I gives them).  With few workgroups per compute unit the
-// latency of a step (LDS round trip, barrier, reciprocals) is what the sweep costs, with many the instruction
-// count: 4 pivots per step on 4 D threads take 0.054 ms for 1024 matrices of 64 x 64 where one pivot per step
-// on 256 threads took 0.086 ms (0.35 against 0.46 ms at 128 x 128).
+// for j before it.  Only the four pivot columns go through LDS (the lanes that hold them copy their registers
+// out, with the identity already subtracted from the pivot block), double-buffered: one barrier per step.
+// Every lane factors the 4 x 4 block B = L diag(dd) L^T for itself in registers and solves for the one row of
+// B^{-1} it needs (row g: a lane supplies R'[g][16 tj + c] as the B operand of tile tj and C'[16 w + c][g] as
+// the A operand); the pivot columns get theirs from the identity x = e_e - B^{-1} e_e that the stored B - I gives
+// them.  A lane reads 4 tj + 15 doubles from LDS per step; with the matrix spread as a quarter of a column per
+// thread and the update on the vector units it read D + 14, and the LDS pipe was what the sweep waited for
+// (d = 128, 496 matrices: 0.18 ms).
 template <int D>
 struct SpdInverse {
-  static constexpr int RG = 4;             // row groups: 4 D threads, each holding a quarter of a column
-  static constexpr int NT = RG * D;
-  static constexpr int NR = D / RG;        // rows per thread
-  static constexpr int KB = 4;             // pivots per step
-  static constexpr int STRIDE = D;         // doubles per pivot column: a thread's NR rows contiguous
+  static constexpr int NTL = D / 16;        // tile rows (one wave each) and tile columns
+  static constexpr int NT = 64 * NTL;       // 4 D threads
+  static constexpr int KB = 4;              // pivots per step: the contraction length of the matrix instruction
+  static constexpr int STRIDE = D;          // doubles per pivot column
   static constexpr int LDS_DOUBLES = 2 * KB * STRIDE;
-  static_assert(NR % 2 == 0 && D % KB == 0, "the columns are copied out in 16-byte pieces, KB at a time");
-  double* colp;                            // LDS [2][KB][STRIDE]
-  static __device__ __forceinline__ int slot(int i) { return (i % RG) * NR + i / RG; }   // where row i sits
+  double* colp;                             // LDS [2][KB][STRIDE]
   static __device__ __forceinline__ double recip(double d) {   // hardware estimate refined twice: full precision
     const double y = __builtin_amdgcn_rcp(d);
     const double y1 = y * fma(-d, y, 2.0);
     return y1 * fma(-d, y1, 2.0);
   }
-  __device__ __forceinline__ void run(double (&m)[NR]) const {
-    typedef double d2 __attribute__((ext_vector_type(2)));
-    const int j = threadIdx.x % D;
-    const int rg = threadIdx.x / D;
-    const int jslot = slot(j);
-    for (int p0 = 0; p0 < D; p0 += KB) {
-      double* cp = colp + ((p0 / KB) & 1) * (KB * STRIDE);
-      const int e = j - p0;                // this thread's column is pivot e of the step when 0 <= e < KB
-      if (e >= 0 && e < KB) {
-        double* mine = cp + e * STRIDE + rg * NR;
-        const int nd = (rg == j % RG) ? j / RG : -1;   // the register holding the diagonal element M[j][j]
+  __device__ __forceinline__ void run(d4 (&acc)[NTL]) const {
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = lane & 15;
+    const int g = lane >> 4;
 #pragma unroll
-        for (int n = 0; n < NR; n += 2)
-          *reinterpret_cast<d2*>(&mine[n]) = d2{m[n] - (n == nd ? 1.0 : 0.0), m[n + 1] - (n + 1 == nd ? 1.0 : 0.0)};
-      }
-      __syncthreads();
-      // B = L diag(dd) L^T (unit lower triangular L, no pivoting: B is symmetric positive definite), every
-      // thread for itself in registers; lo[a][c] holds B's lower triangle, then t = L diag(dd) below the diagonal
-      double lo[KB][KB], l[KB][KB], inv[KB];
+    for (int tp = 0; tp < NTL; ++tp) {       // the tile column that holds the pivots
+      for (int ps = 0; ps < 4; ++ps) {       // its columns 4 ps .. 4 ps + 3
+        const int p0 = 16 * tp + KB * ps;
+        double* cp = colp + (ps & 1) * (KB * STRIDE);
+        if ((c >> 2) == ps) {                // this lane's column of tile tp is pivot e of the step
+          double* mine = cp + (c & 3) * STRIDE + 16 * w + g;
 #pragma unroll
-      for (int a = 0; a < KB; ++a)
-#pragma unroll
-        for (int c = 0; c <= a; ++c) {
-          const double x = cp[c * STRIDE + slot(p0 + a)];
-          lo[a][c] = (a == c) ? x + 1.0 : x;
+          for (int r = 0; r < 4; ++r) mine[4 * r] = acc[tp][r] - ((w == tp && g + 4 * r == c) ? 1.0 : 0.0);
         }
+        __syncthreads();
+        // B = L diag(dd) L^T (unit lower triangular L, no pivoting: B is symmetric positive definite), every
+        // lane for itself in registers; lo[a][c] holds B's lower triangle, then t = L diag(dd) below the diagonal
+        double lo[KB][KB], l[KB][KB], inv[KB];
 #pragma unroll
-      for (int c = 0; c < KB; ++c) {
-        // column c: t[a][c] = B[a][c] - sum_{k<c} l[a][k] t[c][k];  dd_c = t[c][c];  l[a][c] = t[a][c] / dd_c
+        for (int a = 0; a < KB; ++a)
 #pragma unroll
-        for (int a = c; a < KB; ++a)
+          for (int k = 0; k <= a; ++k) {
+            const double x = cp[k * STRIDE + p0 + a];
+            lo[a][k] = (a == k) ? x + 1.0 : x;
+          }
 #pragma unroll
-          for (int k = 0; k < c; ++k) lo[a][c] = fma(-l[a][k], lo[c][k], lo[a][c]);
-        inv[c] = recip(lo[c][c]);
+        for (int k = 0; k < KB; ++k) {
+          // column k: t[a][k] = B[a][k] - sum_{i<k} l[a][i] t[k][i];  dd_k = t[k][k];  l[a][k] = t[a][k] / dd_k
 #pragma unroll
-        for (int a = c + 1; a < KB; ++a) l[a][c] = lo[a][c] * inv[c];
-      }
-      // x = B^{-1} (M[j][P])^T by the two triangular solves; then r[a] = R'[a][j]:
-      //   j after the pivots:   R[:, j] = +M[j][P]^T            -> r = x
-      //   j before the pivots:  R[:, j] = -M[j][P]^T            -> r = -x
-      //   j = pivot e:          the column holds (B - I)[:, e]  -> x = e_e - B^{-1} e_e,  r = e_e + B^{-1} e_e = 2 e_e - x
-      double r[KB];
+          for (int a = k; a < KB; ++a)
 #pragma unroll
-      for (int c = 0; c < KB; ++c) r[c] = cp[c * STRIDE + jslot];
+            for (int i = 0; i < k; ++i) lo[a][k] = fma(-l[a][i], lo[k][i], lo[a][k]);
+          inv[k] = recip(lo[k][k]);
 #pragma unroll
-      for (int a = 1; a < KB; ++a)
+          for (int a = k + 1; a < KB; ++a) l[a][k] = lo[a][k] * inv[k];
+        }
+        // y = row g of B^{-1} (= column g: B is symmetric), by the two triangular solves on e_g
+        double y[KB];
 #pragma unroll
-        for (int k = 0; k < a; ++k) r[a] = fma(-l[a][k], r[k], r[a]);
+        for (int a = 0; a < KB; ++a) y[a] = (a == g) ? 1.0 : 0.0;
 #pragma unroll
-      for (int a = 0; a < KB; ++a) r[a] *= inv[a];
+        for (int a = 1; a < KB; ++a)
 #pragma unroll
-      for (int a = KB - 2; a >= 0; --a)
+          for (int k = 0; k < a; ++k) y[a] = fma(-l[a][k], y[k], y[a]);
 #pragma unroll
-        for (int k = a + 1; k < KB; ++k) r[a] = fma(-l[k][a], r[k], r[a]);
-      const double sgn = j >= p0 + KB ? 1.0 : -1.0;
+        for (int a = 0; a < KB; ++a) y[a] *= inv[a];
 #pragma unroll
-      for (int a = 0; a < KB; ++a) r[a] = fma(sgn, r[a], e == a ? 2.0 : 0.0);
-      const double* crow = cp + rg * NR;
+        for (int a = KB - 2; a >= 0; --a)
 #pragma unroll
-      for (int n = 0; n < NR; ++n) {
+          for (int k = a + 1; k < KB; ++k) y[a] = fma(-l[k][a], y[k], y[a]);
+        const double cv = cp[g * STRIDE + 16 * w + c];   // C'[16 w + c][g]
+        // x = (B^{-1} (M[j][P])^T)[g] for the lane's column j of every tile; then R'[g][j]:
+        //   j after the pivots:   R[:, j] = +M[j][P]^T            -> x
+        //   j before the pivots:  R[:, j] = -M[j][P]^T            -> -x
+        //   j = pivot e:          the column holds (B - I)[:, e]  -> x = (e_e - B^{-1} e_e)[g],  R' = 2 [e = g] - x
 #pragma unroll
-        for (int c = 0; c < KB; ++c) m[n] = fma(-crow[c * STRIDE + n], r[c], m[n]);
-        if (n % 2 == 1) asm volatile("" ::: "memory");   // keep at most 8 LDS reads in flight (registers)
+        for (int tj = 0; tj < NTL; ++tj) {
+          const int j = 16 * tj + c;
+          double x = y[0] * cp[j];
+#pragma unroll
+          for (int k = 1; k < KB; ++k) x = fma(y[k], cp[k * STRIDE + j], x);
+          const double rr = (j >= p0 + KB) ? x : ((j - p0 == g) ? 2.0 - x : -x);
+          acc[tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(cv, -rr, acc[tj], 0, 0, 0);
+        }
       }
     }
   }
@@ -433,63 +433,69 @@ struct SpdInverse {
 template <int D, int DL>
 __global__ void __launch_bounds__(SpdInverse<D>::NT, D <= 64 ? 4 : 2) boundary_kernel(ForwardArgs a, const double* G, float* seg_A) {
   static_assert(DL <= D, "padded layout");
-  constexpr int RG = SpdInverse<D>::RG;
-  constexpr int NR = SpdInverse<D>::NR;
+  constexpr int NTL = SpdInverse<D>::NTL;
+  constexpr int NT = SpdInverse<D>::NT;
   __shared__ __align__(16) double colp[SpdInverse<D>::LDS_DOUBLES];
 
   const int head = blockIdx.x / a.n_seg;
   const int seg = blockIdx.x - head * a.n_seg;
-  const int j = threadIdx.x % D;
-  const int rg = threadIdx.x / D;
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 15;
+  const int i0 = 16 * (threadIdx.x >> 6) + (lane >> 4);   // acc[tj][r] = M[i0 + 4 r][16 tj + c]
   const float* A0 = a.A0 ? a.A0 + static_cast<size_t>(head) * DL * DL : nullptr;
   float* out = seg_A + static_cast<size_t>(blockIdx.x) * DL * DL;
   const float diag = 1.0f / a.lambda0;   // the same float32 value the first segment starts from
-  const bool jin = D == DL || j < DL;    // column j belongs to the data
 
   if (seg == 0) {   // the first segment starts from the caller's A0, bit for bit
-    if (jin) {
-      for (int i = rg; i < DL; i += RG) out[i * DL + j] = A0 ? A0[i * DL + j] : (i == j ? diag : 0.0f);
-    }
+    for (int e = threadIdx.x; e < DL * DL; e += NT) out[e] = A0 ? A0[e] : (e / DL == e % DL ? diag : 0.0f);
     return;
   }
+  auto data = [&](int i, int j) { return D == DL || (i < DL && j < DL); };   // inside the DL x DL matrix
   const SpdInverse<D> inv{colp};
-  double m[NR];
+  d4 acc[NTL];
   if (A0) {
 #pragma unroll
-    for (int n = 0; n < NR; ++n) {
-      const int i = rg + RG * n;
-      m[n] = (jin && (D == DL || i < DL))
-                 ? 0.5 * (static_cast<double>(A0[i * DL + j]) + static_cast<double>(A0[j * DL + i]))
-                 : (i == j ? 1.0 : 0.0);
-    }
-    inv.run(m);
+    for (int tj = 0; tj < NTL; ++tj)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + 4 * r, j = 16 * tj + c;
+        acc[tj][r] = data(i, j) ? 0.5 * (static_cast<double>(A0[i * DL + j]) + static_cast<double>(A0[j * DL + i]))
+                                : (i == j ? 1.0 : 0.0);
+      }
+    inv.run(acc);
     __syncthreads();   // the pivot buffers are reused by the second inversion
   } else {
 #pragma unroll
-    for (int n = 0; n < NR; ++n) {
-      const int i = rg + RG * n;
-      m[n] = (i == j) ? ((jin) ? 1.0 / static_cast<double>(diag) : 1.0) : 0.0;
-    }
+    for (int tj = 0; tj < NTL; ++tj)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + 4 * r, j = 16 * tj + c;
+        acc[tj][r] = (i == j) ? (data(i, j) ? 1.0 / static_cast<double>(diag) : 1.0) : 0.0;
+      }
   }
   // G holds inclusive prefix sums: G[head][seg - 1] covers every token before this segment
   const double* Gh = G + (static_cast<size_t>(blockIdx.x) - 1) * DL * DL;
 #pragma unroll
-  for (int n = 0; n < NR; ++n) {
-    const int i = rg + RG * n;
-    if (jin && (D == DL || i < DL)) m[n] += Gh[i * DL + j];
-  }
-  inv.run(m);
+  for (int tj = 0; tj < NTL; ++tj)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + 4 * r, j = 16 * tj + c;
+      if (data(i, j)) acc[tj][r] += Gh[i * DL + j];
+    }
+  inv.run(acc);
   // The inverse of a symmetric matrix is symmetric up to rounding; store the lower triangle's values on both
   // sides so that the float32 matrix the recurrence starts from is exactly symmetric.
 #pragma unroll
-  for (int n = 0; n < NR; ++n) {
-    const int i = rg + RG * n;
-    const float v = static_cast<float>(m[n]);
-    if (i >= j && (D == DL || i < DL)) {
-      out[i * DL + j] = v;
-      out[j * DL + i] = v;
+  for (int tj = 0; tj < NTL; ++tj)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + 4 * r, j = 16 * tj + c;
+      const float v = static_cast<float>(acc[tj][r]);
+      if (i >= j && data(i, j)) {
+        out[i * DL + j] = v;
+        out[j * DL + i] = v;
+      }
     }
-  }
 }
 
 // ------------------------------------------------------------------------------------------ combine
