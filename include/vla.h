@@ -147,10 +147,10 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
  *          returns VLA_ERR_INVALID_ARG -- with three exceptions: S_T == S0, A_T == A0 and
  *          zkey_T == zkey0 (the same pointer: the state is then updated in place).
  *   B, H   >= 1;  T >= 0 (T == 0 copies the initial state to S_T / A_T)
- *   d_k, d_v in {16, 32, 64, 96, 128}, any pair.  With d_k == d_v: SCAN and CHUNKED at every size,
- *          TWO_PHASE and TIME_PARALLEL from 32.  With d_k != d_v (S is d_v x d_k): SCAN and CHUNKED for
- *          every pair and every option (the waves of a head share out the d_v / 16 row tiles of S);
- *          AUTO picks CHUNKED; no segment modes
+ *   d_k, d_v in {16, 32, 64, 96, 128}, any pair (S is d_v x d_k).  SCAN and CHUNKED for every pair and
+ *          every option (with d_k != d_v the waves of a head share out the d_v / 16 row tiles of S);
+ *          TWO_PHASE and TIME_PARALLEL for d_k >= 32 with any d_v (every option but the identity
+ *          refresh); AUTO routes by d_k as above
  *   opts   host pointer or NULL
  *   workspace, workspace_bytes: device scratch of at least
  *          vla_forward_workspace_bytes(...) bytes (may be NULL/0 when that is 0)

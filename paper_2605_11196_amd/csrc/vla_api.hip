@@ -117,7 +117,6 @@ bool general_path(const vla_opts& o) { return needs_general_kernel(o) || o.featu
 int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   if (o.mode != VLA_MODE_AUTO) return o.mode;
   if (!vla::chunk_supported(d, d_v)) return VLA_MODE_SCAN;
-  if (d != d_v) return VLA_MODE_CHUNKED;   // rectangular heads: the two block kernels, no segment modes
   const int with_options = vla::general_block_supported(d) ? VLA_MODE_CHUNKED : VLA_MODE_SCAN;
   // the identity refresh breaks A_t = M_t^{-1}, which the segment boundaries rest on
   if (o.refresh_period > 0) return with_options;
@@ -135,8 +134,18 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
   //             384: 1.78 / 1.38;                                       T = 16384: 320 heads 5.13 / 5.48, 384: 7.02 / 5.47
   //   d =  32:  T = 2048: 512 heads 0.51 / 0.57, 640: 0.59 / 0.58;      T = 16384: 512 heads 3.71 / 4.54, 640: 4.59 / 4.56
   const int t_128 = d == 96 ? 4096 : 8192;   // from here 128 heads still gain at d >= 96
-  const long long few = d >= 96 ? (T >= t_128 ? 128 : (T >= 4096 ? 96 : 64))
-                                : (d >= 64 ? (T >= 4096 ? 320 : 192) : 512);
+  long long few = d >= 96 ? (T >= t_128 ? 128 : (T >= 4096 ? 96 : 64))
+                          : (d >= 64 ? (T >= 4096 ? 320 : 192) : 512);
+  // Value heads of another size than the key heads: the same thresholds by the key head size, a notch higher
+  // where measured (the block kernel shares the row tiles of S out unevenly, the S rows kernel of the segment
+  // modes takes them in turn).  T = 4096: d_k = 64, d_v = 128: 384 heads 2.45 / 2.89, 448: 3.05 / 2.88; d_v = 16:
+  // 384 heads 1.56 / 1.68;  d_k = 128, d_v = 64: 128 heads 1.50 / 1.62, 160: 1.88 / 1.63; d_v = 16: 128 heads
+  // 1.36 / 1.59;  d_k = 32, d_v = 128: 1280 heads 3.25 / 3.58 (T = 1024: 0.83 / 0.90).
+  if (d != d_v) {
+    if (d == 64 && T >= 4096) few = 384;
+    if (d == 128 && T >= 4096) few = 128;
+    if (d == 32 && d_v == 128) few = 1280;
+  }
   // Short sequences (half the length): 64 heads at d = 64, T = 512: 0.11 against 0.16 ms, 128 heads 0.16 against
   // 0.16; 256 heads at d = 32: 0.12 against 0.14, 512 heads 0.15 against 0.15.  Not at d = 96, whose Gram sums and boundary inverses run in the d = 128 layout (T = 512:
   // 16 heads 0.26 against 0.21).
@@ -150,7 +159,6 @@ int pick_mode(int B, int H, int T, int d, int d_v, const vla_opts& o) {
 bool mode_available(int mode, int d, int d_v, const vla_opts& o) {
   if (mode == VLA_MODE_SCAN) return true;   // every pair of head sizes, with or without options
   if (!vla::chunk_supported(d, d_v)) return false;
-  if (d != d_v) return mode == VLA_MODE_CHUNKED;   // the two block kernels
   if (mode == VLA_MODE_CHUNKED) return !needs_general_kernel(o) || vla::general_block_supported(d);
   // the segment modes carry every option but the identity refresh (A at a segment boundary is the explicit
   // inverse of a prefix sum only without it)
@@ -218,7 +226,7 @@ size_t vla_forward_workspace_bytes(int B, int H, int T, int d_k, int d_v, int io
   if (!segment_grid_fits(mode, static_cast<long long>(B) * H, d_k)) return 0;
   if (mode == VLA_MODE_TWO_PHASE) return vla::two_phase_workspace_bytes(B * H, T, d_k);
   if (mode == VLA_MODE_TIME_PARALLEL) {
-    return vla::time_parallel_workspace_bytes(B * H, T, d_k, needs_general_kernel(o), o.segments);
+    return vla::time_parallel_workspace_bytes(B * H, T, d_k, d_v, needs_general_kernel(o), o.segments);
   }
   return 0;
 }
@@ -291,6 +299,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* S0, c
   a.refresh_period = op.refresh_period; a.refresh_eta = op.refresh_eta; a.step_offset = op.step_offset;
   a.normalise_output = op.normalise_output; a.feature_map = op.feature_map;
   a.zkey0 = op.zkey0; a.zkey_T = op.zkey_T;
+  a.d_v = d_v;
 
   hipError_t err = hipSuccess;
   switch (mode) {

@@ -37,6 +37,9 @@ struct ForwardArgs {
   const float* seg_S = nullptr;   // [n_heads][n_seg][d][d]  S at the start of every segment
   float* seg_PQ = nullptr;        // [n_heads][n_seg][2][d][d]  per-segment affine map of the S recurrence
   const float* seg_zkey = nullptr;  // [n_heads][n_seg][d]  key sum at the start of every segment (normalised read-out)
+  // Rows of S (size of the value heads) where a segment kernel takes it at run time; 0: as many as columns.
+  // With d_v != d the per-segment arrays hold seg_S [d_v][d] and seg_PQ P [d][d] then Q [d_v][d].
+  int d_v = 0;
 };
 
 // bf16 <-> f32 helpers on raw bit patterns (bf16 is the upper half of an IEEE float32).
@@ -77,6 +80,7 @@ hipError_t launch_a_scan_general(const ForwardArgs& a, int d, int io_dtype, hipS
 
 
 // Two-phase split (vla_two_phase.hip): A recurrence first, then the rows of S on many workgroups.
+// (d: key heads; the value head size is a.d_v: any supported size)
 size_t two_phase_workspace_bytes(int n_heads, int T, int d);
 hipError_t launch_two_phase(const ForwardArgs& a, int d, int io_dtype, hipStream_t stream);
 
@@ -88,14 +92,14 @@ struct SegmentPlan {
 };
 // `general`: the call carries a separate penalty direction or the normalised read-out
 SegmentPlan plan_segments(int n_heads, int T, int d, bool general, int requested);
-size_t time_parallel_workspace_bytes(int n_heads, int T, int d, bool general, int requested_segments);
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int d_v, bool general, int requested_segments);
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream);
 // Boundary kernels (vla_segments.hip).  All buffers are device memory inside the caller's workspace.
 //   gram:      G[h][s] = sum over the tokens of segments 0..s of u u^T (u = k^ unless the caller supplies
 //              penalty directions), float64 [d][d]
 //   boundary:  seg_A[h][s] = inverse(inverse(A0[h]) + G[h][s-1]) rounded to float32
-//   combine:   seg_S[h][0] = S0[h];  seg_S[h][s+1] = seg_S[h][s] P[h][s] + Q[h][s]
+//   combine:   seg_S[h][0] = S0[h];  seg_S[h][s+1] = seg_S[h][s] P[h][s] + Q[h][s]  (a.d_v rows)
 hipError_t launch_gram(const ForwardArgs& a, int d, int io_dtype, double* G, hipStream_t stream);
 hipError_t launch_boundary(const ForwardArgs& a, int d, const double* G, float* seg_A, hipStream_t stream);
 hipError_t launch_combine(const ForwardArgs& a, int d, float* seg_S, hipStream_t stream);

@@ -506,14 +506,19 @@ __global__ void __launch_bounds__(SpdInverse<D>::NT, D <= 64 ? 4 : 2) boundary_k
 // straight back as the MFMA B operand), computes its own slice of x P + Q and hands it to the other waves
 // through LDS.  The chain is sequential in s and short per step, so the operands of the next three
 // segments are kept in flight in rotating register sets.
+// S has a.d_v rows (value heads of another size than the key heads: more or fewer slabs per head, P stays D x D).
 template <int D>
 __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, float* seg_S) {
   constexpr int NB = D / 16;
   constexpr int LDX = D + 4;
   constexpr int LA = 3;   // segments of lookahead
   __shared__ __align__(16) float xs[2][16 * LDX];
-  const int head = blockIdx.x / NB;
-  const int row0 = (blockIdx.x - head * NB) * 16;
+  const int dv = a.d_v > 0 ? a.d_v : D;
+  const int nbv = dv / 16;                       // slabs per head
+  const size_t ssz = static_cast<size_t>(dv) * D;            // floats of S and of Q
+  const size_t pqsz = static_cast<size_t>(D) * D + ssz;      // floats of one segment's P then Q
+  const int head = blockIdx.x / nbv;
+  const int row0 = (blockIdx.x - head * nbv) * 16;
   const int jb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // column slice of this wave
   const int lane = threadIdx.x & 63;
   const int c = lane & 15;
@@ -527,7 +532,7 @@ __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, f
     f4 q;              // Q[row0 + c][16 jb + 4g ..]
   };
   auto load = [&](int s, Seg& o) {
-    const float* P = a.seg_PQ + (hbase + s) * 2 * D * D;
+    const float* P = a.seg_PQ + (hbase + s) * pqsz;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -537,11 +542,11 @@ __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, f
 
   f4 xt[NB];
   {
-    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr;
+    const float* S0 = a.S0 ? a.S0 + static_cast<size_t>(head) * ssz : nullptr;
 #pragma unroll
     for (int b = 0; b < NB; ++b) xt[b] = S0 ? *reinterpret_cast<const f4*>(S0 + ro + 16 * b) : f4{0, 0, 0, 0};
     const f4 mine = S0 ? *reinterpret_cast<const f4*>(S0 + ro + 16 * jb) : f4{0, 0, 0, 0};
-    *reinterpret_cast<f4*>(seg_S + hbase * D * D + ro + 16 * jb) = mine;
+    *reinterpret_cast<f4*>(seg_S + hbase * ssz + ro + 16 * jb) = mine;
   }
 
   auto step = [&](int s, const Seg& o) {
@@ -550,7 +555,7 @@ __global__ void __launch_bounds__(64 * (D / 16)) combine_kernel(ForwardArgs a, f
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int r = 0; r < 4; ++r) nx = mfma16(o.pa[b][r], xt[b][r], nx);
-    *reinterpret_cast<f4*>(seg_S + (hbase + s + 1) * D * D + ro + 16 * jb) = nx;
+    *reinterpret_cast<f4*>(seg_S + (hbase + s + 1) * ssz + ro + 16 * jb) = nx;
     float* x = xs[s & 1];
     *reinterpret_cast<f4*>(&x[c * LDX + 16 * jb + 4 * g]) = nx;
     __syncthreads();
@@ -598,7 +603,8 @@ template <int D>
 hipError_t launch_combine_d(const ForwardArgs& a, float* seg_S, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args, &seg_S};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&combine_kernel<D>), dim3(a.n_heads * (D / 16)),
+  const int dv = a.d_v > 0 ? a.d_v : D;
+  return hipLaunchKernel(reinterpret_cast<const void*>(&combine_kernel<D>), dim3(a.n_heads * (dv / 16)),
                          dim3(64 * (D / 16)), params, 0, stream);
 }
 

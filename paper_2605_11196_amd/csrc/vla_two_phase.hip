@@ -697,10 +697,16 @@ hipError_t launch_s_rows(const ForwardArgs& a, hipStream_t stream) {
 // written to LDS stage n % 2 in iteration n - 1 (after that iteration's barrier, which every wave reaches only
 // when it is done reading the stage for block n - 2) and consumed in iteration n.  Registers are capped at 128
 // so that four workgroups (d <= 64) share a compute unit and 1024 (head, segment) pairs run in one round.
-template <int D, typename IO, bool MAP>
-__global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_kernel(ForwardArgs a) {
+//
+// RECT: value heads of another size than the key heads (S has a.d_v rows, D columns).  The workgroup keeps its
+// D / 16 waves per run (they stage the operands, whose size follows D) and the d_v / 16 row slabs of S go to
+// them in turn: slab t to wave t % (D / 16), NJV = slots per wave; a wave with no slab in a slot skips it.
+// The P run always has D / 16 slabs, one per wave.
+template <int D, int NJV, bool RECT, typename IO, bool MAP>
+__global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), NJV == 1 ? 4 : 2) s_rows_lds_kernel(ForwardArgs a) {
+  static_assert(RECT || NJV == 1, "square heads: one slab per wave");
   constexpr int NB = D / 16;
-  constexpr int NSLAB = D / 16;
+  constexpr int NSLAB = D / 16;                  // waves of a run
   constexpr int NT = 64 * NSLAB * (MAP ? 2 : 1);
   constexpr int LD = D + 4;
   constexpr int CH = 4 * D;                     // 16-byte pieces of K^ (and of W, and 4-element pieces of q)
@@ -726,7 +732,11 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const int c = lane & 15;
   const int g = lane >> 4;
   const bool p_run = MAP && w >= NSLAB;          // identity rows, v = 0
-  const int row0 = (w % NSLAB) * 16;
+  const int DV = RECT ? a.d_v : D;               // rows of S
+  const int wq = w % NSLAB;
+  // slot jn of this wave: rows row_of(jn) .. + 15 of S (of the identity in the P run, which has D rows)
+  auto row_of = [&](int jn) { return 16 * (wq + NSLAB * jn); };
+  auto owns = [&](int jn) { return jn == 0 ? (p_run || 16 * wq < DV) : (!p_run && row_of(jn) < DV); };
   const int nblk = (a.T + C - 1) / C;
   const int bb = seg * a.seg_blocks;
   const int be = min(nblk, bb + a.seg_blocks);
@@ -741,21 +751,29 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const IO* kh = static_cast<const IO*>(a.k) + slab;
   const bool fmap = a.feature_map != 0;   // q and k are replaced by ELU(x) + 1 as they are consumed
   const bool norm_out = a.normalise_output != 0;   // o_t is divided by max(q_t . zkey_t, eps)
-  const IO* vh = static_cast<const IO*>(a.v) + slab;
-  IO* oh = static_cast<IO*>(a.o) + slab;
+  const size_t vslab = static_cast<size_t>(head) * static_cast<size_t>(a.T) * DV;
+  const IO* vh = static_cast<const IO*>(a.v) + vslab;
+  IO* oh = static_cast<IO*>(a.o) + vslab;
+  const size_t ssz = static_cast<size_t>(DV) * D;   // floats of S (and of Q)
 
-  f4 st[NB];   // st[b][r] = S[row0 + c][16b + 4g + r]
+  f4 st[NJV][NB];   // st[jn][b][r] = S[row_of(jn) + c][16b + 4g + r]
   if constexpr (MAP) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int jn = 0; jn < NJV; ++jn)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st[b][r] = (p_run && row0 + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          st[jn][b][r] = (p_run && jn == 0 && 16 * wq + c == 16 * b + 4 * g + r) ? 1.0f : 0.0f;
   } else {
-    const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * D * D
-                              : (a.S0 ? a.S0 + static_cast<size_t>(head) * D * D : nullptr);
+    const float* S0 = a.seg_S ? a.seg_S + static_cast<size_t>(hs) * ssz
+                              : (a.S0 ? a.S0 + static_cast<size_t>(head) * ssz : nullptr);
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-      st[b] = S0 ? *reinterpret_cast<const f4*>(S0 + (row0 + c) * D + 16 * b + 4 * g) : f4{0, 0, 0, 0};
+    for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        st[jn][b] = (S0 && owns(jn)) ? *reinterpret_cast<const f4*>(S0 + (row_of(jn) + c) * D + 16 * b + 4 * g)
+                                     : f4{0, 0, 0, 0};
   }
 
   // ---- this thread's share of a block's operands
@@ -777,7 +795,7 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     f4 wx, sx, cx;
     RawRow<IO, 4> kx, qx;
     float krn;          // 1 / max(||k||, eps) of token row krow (0 past the end)
-    IO v[4];
+    IO v[NJV][4];
   };
   // Byte offsets inside a block's records are per-thread constants (32 bits); the block's base addresses are
   // uniform (scalar registers).  Only the ragged last block has to clamp its token rows (rows past the end read
@@ -792,24 +810,32 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
   const unsigned sm_off = t16;
   const unsigned c_off = static_cast<unsigned>(2 * C * C) * 4u + t16;
   const unsigned rn_off = static_cast<unsigned>(krow) * 4u;
-  const unsigned v_off = static_cast<unsigned>(4 * g * D + row0 + c) * ES;
+  unsigned v_off[NJV];   // token row 4 g, column row_of(jn) + c of a block of v (and of o)
+#pragma unroll
+  for (int jn = 0; jn < NJV; ++jn) v_off[jn] = static_cast<unsigned>(4 * g * DV + row_of(jn) + c) * ES;
+  const bool reads_v = !p_run;   // the P run starts from v = 0 (and its rows need not exist in v)
   auto at = [](const void* base, unsigned byte_off) { return static_cast<const char*>(base) + byte_off; };
   auto fetch = [&](int blk, Regs& r) {
     const size_t tok = static_cast<size_t>(blk) * (C * D);
     const IO* kb = kh + tok;
     const IO* qb = qh + tok;
-    const IO* vb = vh + tok;
+    const IO* vb = vh + static_cast<size_t>(blk) * (C * DV);
     const float* wb = WT + tok;
     const float* sb = SMp + static_cast<size_t>(blk) * SMB;
     const float* rb = RN + static_cast<size_t>(blk) * C;
     const int lim = T - 1 - blk * C;   // last live token row of the block
-    unsigned kq = kq_off, vo[4];
+    unsigned kq = kq_off, vo[NJV][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) vo[i] = v_off + static_cast<unsigned>(i * D) * ES;
+    for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vo[jn][i] = v_off[jn] + static_cast<unsigned>(i * DV) * ES;
     if (lim < C - 1) {   // uniform
       kq = static_cast<unsigned>(min(krow, lim) * D + kcol) * ES;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) vo[i] = static_cast<unsigned>(min(4 * g + i, lim) * D + row0 + c) * ES;
+      for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          vo[jn][i] = static_cast<unsigned>(min(4 * g + i, lim) * DV + row_of(jn) + c) * ES;
     }
     if (do_w) r.wx = *reinterpret_cast<const f4*>(at(wb, w_off));
     if (do_sm) r.sx = *reinterpret_cast<const f4*>(at(sb, sm_off));
@@ -822,7 +848,15 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     }
     if constexpr (!MAP) r.qx.load(reinterpret_cast<const IO*>(at(qb, kq)));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = *reinterpret_cast<const IO*>(at(vb, vo[i]));
+    for (int jn = 0; jn < NJV; ++jn) {
+      if (RECT ? (reads_v && owns(jn)) : true) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.v[jn][i] = *reinterpret_cast<const IO*>(at(vb, vo[jn][i]));
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.v[jn][i] = IO{};
+      }
+    }
   };
   auto put = [&](const Regs& r, Stage& s) {
     if (do_k) {   // k^ = k / max(||k||, eps): the same product the A scan formed it with
@@ -854,49 +888,53 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
       *reinterpret_cast<f4*>(&s.Qs[krow * LD + kcol]) = f4{x[0], x[1], x[2], x[3]};
     }
   };
-  auto compute = [&](int blk, const Stage& s, const IO (&vv)[4]) {
+  auto compute = [&](int blk, const Stage& s, const IO (&vv)[NJV][4]) {
     const int t0 = blk * C;
-    f4 ft, ot = f4{0, 0, 0, 0};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(vv[r]) : 0.0f;
+    for (int jn = 0; jn < NJV; ++jn) {
+      if (RECT && !owns(jn)) continue;   // uniform over the wave
+      f4 ft, ot = f4{0, 0, 0, 0};
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const f4 ka = lds4(&s.Ks[c * LD + 16 * b + 4 * g]);
-      f4 qa;
-      if constexpr (!MAP) qa = lds4(&s.Qs[c * LD + 16 * b + 4 * g]);
+      for (int r = 0; r < 4; ++r) ft[r] = (!p_run && t0 + 4 * g + r < T) ? -widen(vv[jn][r]) : 0.0f;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        ft = mfma16(ka[r], st[b][r], ft);
-        if constexpr (!MAP) ot = mfma16(qa[r], st[b][r], ot);
-      }
-    }
-    const f4 za = lds4(&s.Zs[c * LT + 4 * g]);
-    f4 et = f4{0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
-    if constexpr (!MAP) {
-      const f4 nqa = lds4(&s.NQs[c * LT + 4 * g]);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
-      if (norm_out) ot *= lds4(&s.cv[C + 4 * g]);
-      // uniform block base + this lane's 32-bit byte offset (the one its v loads use)
-      IO* ob = reinterpret_cast<IO*>(reinterpret_cast<char*>(oh + static_cast<size_t>(blk) * (C * D)) + v_off);
-      if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
-        io_store2(ob, ob + D, ot[0], ot[1]);
-        io_store2(ob + 2 * D, ob + 3 * D, ot[2], ot[3]);
-      } else {
+      for (int b = 0; b < NB; ++b) {
+        const f4 ka = lds4(&s.Ks[c * LD + 16 * b + 4 * g]);
+        f4 qa;
+        if constexpr (!MAP) qa = lds4(&s.Qs[c * LD + 16 * b + 4 * g]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          if (t0 + 4 * g + r < T) io_store(ob + r * D, ot[r]);
+          ft = mfma16(ka[r], st[jn][b][r], ft);
+          if constexpr (!MAP) ot = mfma16(qa[r], st[jn][b][r], ot);
         }
       }
-    }
-    const f4 ce = et * lds4(&s.cv[4 * g]);
+      const f4 za = lds4(&s.Zs[c * LT + 4 * g]);
+      f4 et = f4{0, 0, 0, 0};
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const f4 wa = lds4(&s.Wb[(16 * b + c) * LT + 4 * g]);
+      for (int r = 0; r < 4; ++r) et = mfma16(za[r], ft[r], et);
+      if constexpr (!MAP) {
+        const f4 nqa = lds4(&s.NQs[c * LT + 4 * g]);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st[b] = mfma16(wa[r], ce[r], st[b]);
+        for (int r = 0; r < 4; ++r) ot = mfma16(nqa[r], et[r], ot);
+        if (norm_out) ot *= lds4(&s.cv[C + 4 * g]);
+        // uniform block base + this lane's 32-bit byte offset (the one its v loads use)
+        IO* ob = reinterpret_cast<IO*>(reinterpret_cast<char*>(oh + static_cast<size_t>(blk) * (C * DV)) + v_off[jn]);
+        if (t0 + C <= T) {   // uniform: only the ragged last block predicates its stores
+          io_store2(ob, ob + DV, ot[0], ot[1]);
+          io_store2(ob + 2 * DV, ob + 3 * DV, ot[2], ot[3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (t0 + 4 * g + r < T) io_store(ob + r * DV, ot[r]);
+          }
+        }
+      }
+      const f4 ce = et * lds4(&s.cv[4 * g]);
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const f4 wa = lds4(&s.Wb[(16 * b + c) * LT + 4 * g]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) st[jn][b] = mfma16(wa[r], ce[r], st[jn][b]);
+      }
     }
   };
 
@@ -906,9 +944,14 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     fetch(bb, r0);
     put(r0, stg[0]);
   }
-  IO vcur[4];
+  auto copy_v = [](IO (&dst)[NJV][4], const IO (&src)[NJV][4]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) vcur[i] = r0.v[i];
+    for (int jn = 0; jn < NJV; ++jn)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[jn][i] = src[jn][i];
+  };
+  IO vcur[NJV][4];
+  copy_v(vcur, r0.v);
   if (bb + 1 < be) fetch(bb + 1, r0);
   if (bb + 2 < be) fetch(bb + 2, r1);
   // iteration n (block bb + n): r0 holds block n+1, r1 block n+2 when n is even, the other way round when odd
@@ -916,48 +959,69 @@ __global__ void __launch_bounds__(64 * (D / 16) * (MAP ? 2 : 1), 4) s_rows_lds_k
     {
       const int blk = bb + n;
       __syncthreads();
-      IO vnext[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) vnext[i] = r0.v[i];
+      IO vnext[NJV][4];
+      copy_v(vnext, r0.v);
       if (blk + 1 < be) put(r0, stg[(n + 1) % NST]);
       if (blk + 3 < be) fetch(blk + 3, r0);
       compute(blk, stg[n % NST], vcur);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) vcur[i] = vnext[i];
+      copy_v(vcur, vnext);
     }
     if (bb + n + 1 < be) {
       const int blk = bb + n + 1;
       __syncthreads();
-      IO vnext[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) vnext[i] = r1.v[i];
+      IO vnext[NJV][4];
+      copy_v(vnext, r1.v);
       if (blk + 1 < be) put(r1, stg[(n + 2) % NST]);
       if (blk + 3 < be) fetch(blk + 3, r1);
       compute(blk, stg[(n + 1) % NST], vcur);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) vcur[i] = vnext[i];
+      copy_v(vcur, vnext);
     }
   }
 
   float* out = nullptr;
-  if constexpr (MAP) {
-    out = a.seg_PQ + (static_cast<size_t>(hs) * 2 + (p_run ? 0 : 1)) * D * D;
+  if constexpr (MAP) {   // per (head, segment): P [D][D], then Q [DV][D]
+    out = a.seg_PQ + static_cast<size_t>(hs) * (static_cast<size_t>(D) * D + ssz) + (p_run ? 0 : D * D);
   } else if (a.S_T && seg == a.n_seg - 1) {
-    out = a.S_T + static_cast<size_t>(head) * D * D;
+    out = a.S_T + static_cast<size_t>(head) * ssz;
   }
   if (out) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-      *reinterpret_cast<f4*>(out + (row0 + c) * D + 16 * b + 4 * g) = st[b];
+    for (int jn = 0; jn < NJV; ++jn) {
+      if (RECT && !owns(jn)) continue;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        *reinterpret_cast<f4*>(out + (row_of(jn) + c) * D + 16 * b + 4 * g) = st[jn][b];
+    }
   }
 }
 
-template <int D, typename IO, bool MAP>
-hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
+template <int D, int NJV, bool RECT, typename IO, bool MAP>
+hipError_t launch_s_rows_lds_n(const ForwardArgs& a, hipStream_t stream) {
   ForwardArgs args = a;
   void* params[] = {&args};
-  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_lds_kernel<D, IO, MAP>),
+  return hipLaunchKernel(reinterpret_cast<const void*>(&s_rows_lds_kernel<D, NJV, RECT, IO, MAP>),
                          dim3(a.n_heads * a.n_seg), dim3(64 * (D / 16) * (MAP ? 2 : 1)), params, 0, stream);
+}
+// Square heads, or (a.d_v != D) value heads of another size: slots per wave = ceil((d_v / 16) / (D / 16)).
+template <int D, typename IO, bool MAP>
+hipError_t launch_s_rows_lds(const ForwardArgs& a, hipStream_t stream) {
+  const int dv = a.d_v > 0 ? a.d_v : D;
+  if (dv == D) return launch_s_rows_lds_n<D, 1, false, IO, MAP>(a, stream);
+  if (dv % 16 != 0 || dv < 16) return hipErrorInvalidValue;
+  constexpr int NW = D / 16;
+  constexpr int kMaxSlots = (128 / 16 + NW - 1) / NW;   // value heads up to 128
+  const int slots = (dv / 16 + NW - 1) / NW;
+  if (slots == 1) return launch_s_rows_lds_n<D, 1, true, IO, MAP>(a, stream);
+  if constexpr (kMaxSlots >= 2) {
+    if (slots == 2) return launch_s_rows_lds_n<D, 2, true, IO, MAP>(a, stream);
+  }
+  if constexpr (kMaxSlots >= 3) {
+    if (slots == 3) return launch_s_rows_lds_n<D, 3, true, IO, MAP>(a, stream);
+  }
+  if constexpr (kMaxSlots >= 4) {
+    if (slots == 4) return launch_s_rows_lds_n<D, 4, true, IO, MAP>(a, stream);
+  }
+  return hipErrorInvalidValue;
 }
 
 // true when the call switches on a separate penalty direction or the normalised read-out (the feature map
@@ -980,7 +1044,8 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   constexpr bool kFusedMap = D <= 64;
   // Worth it once the (head, segment) pairs fill the chip (measured at 16 heads, d = 64: 3 % faster at 1024
   // pairs, 5 % slower at 512 and below, where a block's latency counts and the maps lengthen it).
-  const bool fused_map = kFusedMap && !general && a.n_seg > 1 && hs >= 768;
+  const bool rect = a.d_v > 0 && a.d_v != D;   // value heads of another size: the A scan is the same, S has d_v rows
+  const bool fused_map = kFusedMap && !general && !rect && a.n_seg > 1 && hs >= 768;
   const void* scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, false>);
   if constexpr (kFusedMap) {
     if (fused_map) scan_fn = reinterpret_cast<const void*>(&a_scan_kernel<D, NW, IO, true>);
@@ -993,7 +1058,8 @@ hipError_t launch_phases(const ForwardArgs& a, hipStream_t stream) {
   // pair; with fewer, one wave per slab of S and deep register prefetch (measured, whole call, LDS kernel
   // against the other: 240 to 255 pairs -7 to -13 % at d = 64, -8 to -25 % at d = 128; 128 pairs -3.5 and
   // -0.4 %; 9 to 32 pairs +2 to +8 %).
-  const bool shared = hs >= 128;
+  // (value heads of another size: the LDS kernel at any count)
+  const bool shared = rect || hs >= 128;
   auto rows = [&](auto map_tag) -> hipError_t {
     constexpr bool kMap = decltype(map_tag)::value;
     return shared ? launch_s_rows_lds<D, IO, kMap>(a, stream) : launch_s_rows<D, IO, kMap>(a, stream);
@@ -1094,16 +1160,17 @@ namespace {
 struct TpLayout {
   size_t gram, seg_A, seg_PQ, seg_S, key_part, seg_zkey, total;
 };
-TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
+TpLayout tp_layout(int n_heads, int T, int d, int d_v, int n_seg) {
   const int nblk = (T + C - 1) / C;
   const size_t mats = static_cast<size_t>(n_heads) * n_seg * d * d;  // one d x d float matrix per (head, seg)
+  const size_t smats = static_cast<size_t>(n_heads) * n_seg * d_v * d;  // one d_v x d matrix (S, Q) per (head, seg)
   TpLayout l;
   size_t off = static_cast<size_t>(n_heads) * head_stride(nblk, d);
   off = (off + 3) & ~static_cast<size_t>(3);  // 16-byte alignment
   l.gram = off;   off += 2 * mats;            // float64
   l.seg_A = off;  off += mats;
-  l.seg_PQ = off; off += 2 * mats;
-  l.seg_S = off;  off += mats;
+  l.seg_PQ = off; off += mats + smats;
+  l.seg_S = off;  off += smats;
   const size_t vecs = static_cast<size_t>(n_heads) * n_seg * d;      // one d-vector per (head, seg)
   l.key_part = off; off += 2 * vecs;          // float64
   l.seg_zkey = off; off += vecs;
@@ -1113,17 +1180,17 @@ TpLayout tp_layout(int n_heads, int T, int d, int n_seg) {
 }
 }  // namespace
 
-size_t time_parallel_workspace_bytes(int n_heads, int T, int d, bool general, int requested_segments) {
+size_t time_parallel_workspace_bytes(int n_heads, int T, int d, int d_v, bool general, int requested_segments) {
   const SegmentPlan p = plan_segments(n_heads, T, d, general, requested_segments);
   if (p.n_seg <= 1) return two_phase_workspace_bytes(n_heads, T, d);
-  return tp_layout(n_heads, T, d, p.n_seg).total * sizeof(float);
+  return tp_layout(n_heads, T, d, d_v, p.n_seg).total * sizeof(float);
 }
 
 hipError_t launch_time_parallel(const ForwardArgs& a, int d, int io_dtype, int requested_segments,
                                 hipStream_t stream) {
   const SegmentPlan p = plan_segments(a.n_heads, a.T, d, runs_on_option_kernel(a), requested_segments);
   if (p.n_seg <= 1) return launch_two_phase(a, d, io_dtype, stream);
-  const TpLayout l = tp_layout(a.n_heads, a.T, d, p.n_seg);
+  const TpLayout l = tp_layout(a.n_heads, a.T, d, a.d_v > 0 ? a.d_v : d, p.n_seg);
   ForwardArgs args = a;
   args.n_seg = p.n_seg;
   args.seg_blocks = p.seg_blocks;

@@ -122,8 +122,8 @@ def call(**kw):
     (dict(mode=3, d_k=64, d_v=64, workspace=FAKE + 0x2800, workspace_bytes=1 << 20), 1),   # workspace over v and o
     (dict(d_k=48, d_v=48), 2), (dict(d_k=16, d_v=48), 2), (dict(d_k=96, d_v=48), 2), (dict(d_k=256, d_v=256), 2),
     (dict(d_k=16, d_v=32, mode=3), 2), (dict(d_k=64, d_v=128, refresh_period=4, mode=3), 2),   # rectangular heads:
-    (dict(d_k=96, d_v=64, mode=4, refresh_period=4), 2), (dict(d_k=128, d_v=32, mode=3, normalise_output=1), 2),   # no segment modes
-    (dict(d_k=64, d_v=128, mode=3), 2), (dict(d_k=128, d_v=64, mode=4), 2),
+    (dict(d_k=96, d_v=64, mode=4, refresh_period=4), 2), (dict(d_k=16, d_v=128, mode=4, normalise_output=1), 2),   # no refresh in the
+    (dict(d_k=16, d_v=64, mode=4), 2), (dict(d_k=64, d_v=48, mode=3), 2),   # segment modes, none of them at d_k = 16, sizes outside the set
 ])
 def test_host_side_validation_returns_status_without_launch(kw, status):
     assert call(**kw) == status
@@ -170,22 +170,29 @@ def test_workspace_query_and_mode_resolution():
     assert vla.resolve_mode(1, 128, 1024, 64, 64, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(1, 16, 131072, 96, 96, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
     assert vla.resolve_mode(1, 16, 131072, 16, 16, vla.VLA_BF16) == vla.MODE_CHUNKED   # no segment modes at d = 16
-    assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_CHUNKED   # d_k != d_v: plain kernels
+    # value heads of another size than the key heads: the same routing by the key head size (few heads on a
+    # long sequence -> time-parallel), every mode; no segment modes at d_k = 16
+    assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(64, 32, 4096, 64, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_SCAN) == vla.MODE_SCAN
-    assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
+    assert vla.resolve_mode(4, 4, 4096, 64, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(4, 4, 4096, 128, 16, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE) == vla.MODE_TWO_PHASE
     assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(4, 4, 4096, 16, 32, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL) == -1
     # every pair of head sizes runs on the block kernels (the waves of a head share out the row tiles of S, evenly
     # or in turn), with or without options
     assert vla.resolve_mode(4, 4, 4096, 16, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 64, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 128, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 96, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 64, 16, vla.VLA_BF16) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 32, 128, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 64, 96, vla.VLA_BF16, feature_map=1) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 128, 32, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 96, 64, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 64, 16, vla.VLA_BF16) == vla.MODE_CHUNKED
+    assert vla.resolve_mode(64, 32, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, u=FAKE, refresh_period=20) == vla.MODE_CHUNKED
     assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_CHUNKED, normalise_output=1) == vla.MODE_CHUNKED
-    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL, normalise_output=1) == -1
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, normalise_output=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL, normalise_output=1) == vla.MODE_TIME_PARALLEL
+    assert vla.resolve_mode(4, 4, 4096, 32, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL, refresh_period=5) == -1
     assert vla.resolve_mode(4, 4, 4096, 32, 48, vla.VLA_BF16) == -1
 
 
@@ -226,6 +233,12 @@ def test_time_parallel_workspace_follows_the_segment_plan():
     two24 = vla.vla_forward_workspace_bytes(1, 24, 4096, d, d, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
     got = vla.vla_forward_workspace_bytes(1, 24, 4096, d, d, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL)
     assert got == two24 + 24 * 20 * (d * d * 6 + d * 3) * 4
+    # value heads of another size: per (head, segment) Gram (float64), A start and P stay d x d, Q and the S start
+    # are d_v x d
+    two_r = vla.vla_forward_workspace_bytes(B, H, T, d, 128, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)
+    assert two_r == two
+    got = vla.vla_forward_workspace_bytes(B, H, T, d, 128, vla.VLA_BF16, mode=vla.MODE_TIME_PARALLEL, segments=8)
+    assert got == two + B * H * 8 * (d * d * 4 + 2 * 128 * d + d * 3) * 4
     # from d = 96: about 512 pairs, segments of at least 32 blocks
     for (T2, want) in ((8192, 16), (32768, 32), (131072, 32)):
         two2 = vla.vla_forward_workspace_bytes(B, H, T2, 128, 128, vla.VLA_BF16, mode=vla.MODE_TWO_PHASE)

@@ -81,7 +81,41 @@ def draw_segment_option_cases(n, seed):
 CASES += draw_segment_option_cases(60, seed=20260512)
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c['i']}-d{c['d']}-T{c['T']}-m{c['mode']}-{c['dtype']}")
+def draw_rect_segment_cases(n, seed):
+    """Value heads of another size than the key heads in the two-phase and time-parallel modes, with and without the
+    options those modes carry."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        d = int(rng.choice([32, 64, 96, 128]))
+        d_v = int(rng.choice([x for x in (16, 32, 64, 96, 128) if x != d]))
+        mode = int(rng.choice([TWO_PHASE, TIME_PARALLEL], p=[0.25, 0.75]))
+        c = dict(i=2000 + i, d=d, d_v=d_v, mode=mode, T=int(rng.integers(1, 700)), B=int(rng.integers(1, 3)),
+                 H=int(rng.integers(1, 6)), dtype=str(rng.choice(["f32", "bf16"])),
+                 given_state=bool(rng.random() < 0.5), zero_frac=float(rng.choice([0.0, 0.0, 0.1])),
+                 seed=int(rng.integers(1 << 30)),
+                 segments=int(rng.integers(0, 12)) if mode == TIME_PARALLEL else None, opts={})
+        o = {}
+        if rng.random() < 0.3:
+            o["with_u"] = True
+            o["u_scale"] = float(rng.choice([1.0, d ** -0.5]))
+        if rng.random() < 0.3:
+            o["normalise_output"] = True
+            o["feature_map"] = True
+        c["opts"] = o
+        cases.append(c)
+    return cases
+
+
+CASES += draw_rect_segment_cases(50, seed=20260513)
+
+
+def _case_id(c):
+    size = f"d{c['d']}" + (f"x{c['d_v']}" if "d_v" in c else "")
+    return f"{c['i']}-{size}-T{c['T']}-m{c['mode']}-{c['dtype']}"
+
+
+@pytest.mark.parametrize("case", CASES, ids=_case_id)
 def test_random_case_matches_the_oracle(case):
     import torch
 
@@ -89,7 +123,8 @@ def test_random_case_matches_the_oracle(case):
 
     B, H, T, d, dtype = case["B"], case["H"], case["T"], case["d"], case["dtype"]
     rng = np.random.default_rng(case["seed"])
-    q, k, v = vla_inputs.gaussian_qkv(B, H, T, d, seed=case["seed"] % 100000)
+    d_v = case.get("d_v", d)
+    q, k, v = vla_inputs.gaussian_qkv(B, H, T, d, seed=case["seed"] % 100000, d_v=d_v)
     opts = dict(case["opts"])
     u = rng.standard_normal(q.shape).astype(np.float32) if opts.pop("with_u", False) else None
     if case["zero_frac"] > 0:
@@ -99,7 +134,7 @@ def test_random_case_matches_the_oracle(case):
             u[rng.random((B, H, T)) < case["zero_frac"]] = 0.0
     S0 = A0 = zkey0 = None
     if case["given_state"]:
-        S0 = rng.standard_normal((B, H, d, d)).astype(np.float32)
+        S0 = rng.standard_normal((B, H, d_v, d)).astype(np.float32)
         m = rng.standard_normal((B, H, d, d)) / np.sqrt(d)
         A0 = (np.eye(d) * 2.0 + m @ m.transpose(0, 1, 3, 2)).astype(np.float32)
         A0 = 0.5 * (A0 + A0.transpose(0, 1, 3, 2))

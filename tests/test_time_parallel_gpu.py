@@ -182,3 +182,62 @@ def test_workspace_and_option_checks():
     rc = vla.vla_forward_raw(*args, mode=TP, segments=-1, workspace=ws.data_ptr(), workspace_bytes=need_tp)
     assert vla.status_string(rc) == "VLA_ERR_INVALID_ARG"
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ value heads of another size than the key heads
+SEG_KEY_SIZES = [32, 64, 96, 128]
+VALUE_SIZES = [16, 32, 64, 96, 128]
+SEG_RECT_PAIRS = [(dk, dv) for dk in SEG_KEY_SIZES for dv in VALUE_SIZES if dk != dv]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dk,dv", SEG_RECT_PAIRS)
+def test_value_heads_of_another_size_run_in_the_segment_modes(dk, dv, dtype):
+    """S is d_v x d_k (eq. (s-update), eq. (output)): the A side of the segment modes only sees the keys, the S rows
+    kernel shares the d_v / 16 row slabs of S out to its d_k / 16 waves in turn (one to four slots per wave, some
+    waves with none), the per-segment maps are P [d_k][d_k] and Q [d_v][d_k].  Four segments of six blocks with a
+    ragged last block and a given S0, time-parallel and two-phase."""
+    B, H, T = 2, 3, 333
+    q, k, v = vla_inputs.gaussian_qkv(B, H, T, dk, seed=1500 + dk + dv, d_v=dv)
+    S0 = np.random.default_rng(dk + dv).standard_normal((B, H, dv, dk)).astype(np.float32)
+    for mode, segments in ((TP, 4), (3, None)):
+        errs, _, _ = check_parity(q, k, v, S0, None, dtype=dtype, lambda0=0.1, mode=mode, segments=segments)
+        print(dk, dv, dtype, mode, errs)
+
+
+@pytest.mark.parametrize("optset", ["normalised read-out", "penalty direction"])
+@pytest.mark.parametrize("dk,dv", [(32, 128), (64, 96), (64, 16), (96, 128), (128, 32), (128, 96)])
+def test_options_on_value_heads_of_another_size_in_the_time_parallel_mode(dk, dv, optset):
+    """The options the segment modes carry (separate penalty directions, normalised read-out with a carried key
+    sum, ELU+1) with d_k != d_v: the A chain of the option kernel feeds the same S rows kernel."""
+    import torch
+
+    import paper_2605_11196_amd as vla
+    from parity_utils import to_np
+
+    B, H, T = 1, 5, 300
+    rng = np.random.default_rng(70 + dk + dv)
+    q, k, u = (rng.standard_normal((B, H, T, dk)).astype(np.float32) for _ in range(3))
+    v = rng.standard_normal((B, H, T, dv)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, dv, dk)).astype(np.float32)
+    z0 = np.abs(rng.standard_normal((B, H, dk))).astype(np.float32)
+    with_u = optset == "penalty direction"
+    opt = dict(lambda0=0.1)
+    if with_u:
+        opt["u_scale"] = dk ** -0.5
+    else:
+        opt.update(normalise_output=True, feature_map=True)
+    norm = bool(opt.get("normalise_output"))
+    ref = oracle.forward(q, k, v, S0, None, u=u if with_u else None, zkey0=z0 if norm else None, **opt)
+    dev = torch.device("cuda:0")
+    t = lambda x: torch.from_numpy(x).to(dev)
+    out = vla.vla_forward(t(q), t(k), t(v), t(S0), None, u=t(u) if with_u else None,
+                          zkey0=t(z0) if norm else None, return_zkey=norm, mode=TP, segments=3, **opt)
+    torch.cuda.synchronize()
+    o, S_T, A_T = out[:3]
+    errs = dict(o=slab_rel_err(to_np(o), ref["o"], 2), S=slab_rel_err(to_np(S_T), ref["S_T"], 2),
+                A=slab_rel_err(to_np(A_T), ref["A_T"], 2))
+    if norm:
+        errs["z"] = slab_rel_err(to_np(out[3]), ref["zkey_T"], 1)
+    print(dk, dv, optset, errs)
+    assert max(errs.values()) <= 1e-4, errs

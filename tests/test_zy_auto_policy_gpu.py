@@ -39,8 +39,23 @@ def _time(fn, reps=7):
     return statistics.median(a.elapsed_time(b) for a, b in ev)
 
 
+RECT_SHAPES = [  # (d_k, d_v, heads, T): value heads of another size than the key heads
+    (64, 128, 16, 6000), (64, 128, 350, 6000), (64, 128, 600, 3000), (128, 64, 120, 5000), (128, 16, 200, 4096),
+    (32, 128, 900, 3000), (64, 16, 16, 20000), (96, 32, 100, 9000), (32, 16, 2000, 2048),
+]
+
+
 @pytest.mark.parametrize("d,heads,T", SHAPES)
 def test_auto_is_close_to_the_best_named_mode(d, heads, T):
+    _check(d, d, heads, T)
+
+
+@pytest.mark.parametrize("d,d_v,heads,T", RECT_SHAPES)
+def test_auto_is_close_to_the_best_named_mode_with_value_heads_of_another_size(d, d_v, heads, T):
+    _check(d, d_v, heads, T)
+
+
+def _check(d, d_v, heads, T):
     import torch
 
     import paper_2605_11196_amd as vla
@@ -48,21 +63,21 @@ def test_auto_is_close_to_the_best_named_mode(d, heads, T):
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev)
     g.manual_seed(d + heads + T)
-    q, k, v = ((torch.randn(1, heads, T, d, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16)
-               for _ in range(3))
+    q, k = ((torch.randn(1, heads, T, d, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16) for _ in range(2))
+    v = (torch.randn(1, heads, T, d_v, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16)
     o = torch.empty_like(v)
     st = torch.cuda.current_stream().cuda_stream
     def measure():
       times = {}
       for mode in (0, CHUNKED, TIME_PARALLEL):
-          if mode and vla.resolve_mode(1, heads, T, d, d, vla.VLA_BF16, mode=mode) != mode:
+          if mode and vla.resolve_mode(1, heads, T, d, d_v, vla.VLA_BF16, mode=mode) != mode:
               continue
-          need = vla.vla_forward_workspace_bytes(1, heads, T, d, d, vla.VLA_BF16, mode=mode)
+          need = vla.vla_forward_workspace_bytes(1, heads, T, d, d_v, vla.VLA_BF16, mode=mode)
           ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
           def call(mode=mode, ws=ws, need=need):
               rc = vla.vla_forward_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), 0, 0, o.data_ptr(), 0, 0, 1, heads,
-                                       T, d, d, vla.VLA_BF16, mode=mode, workspace=ws.data_ptr(),
+                                       T, d, d_v, vla.VLA_BF16, mode=mode, workspace=ws.data_ptr(),
                                        workspace_bytes=need, stream=st)
               assert rc == 0
 
@@ -71,8 +86,8 @@ def test_auto_is_close_to_the_best_named_mode(d, heads, T):
 
     times = measure()
     best = min(t for m, t in times.items() if m)
-    resolved = vla.resolve_mode(1, heads, T, d, d, vla.VLA_BF16)
-    print(f"d={d} heads={heads} T={T}: auto -> mode {resolved}: {times[0]:.3f} ms; "
+    resolved = vla.resolve_mode(1, heads, T, d, d_v, vla.VLA_BF16)
+    print(f"d={d} d_v={d_v} heads={heads} T={T}: auto -> mode {resolved}: {times[0]:.3f} ms; "
           + ", ".join(f"mode {m}: {t:.3f}" for m, t in times.items() if m))
     if times[0] > SLACK * best:      # once more before it counts
         times = measure()
