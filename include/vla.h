@@ -48,7 +48,8 @@ typedef enum { VLA_F32 = 0, VLA_BF16 = 1 } vla_dtype;
  *              segment kernels; else TIME_PARALLEL for few heads (d = 128 and 96: B*H <= 64, 96 from
  *              T = 4096, 128 from T = 8192 (from 4096 at d = 96); d = 64: 192, 320 from T = 4096;
  *              d = 32: 512) and T >= 1024, or from T = 512 for B*H <= 32, 64, 256 heads at d = 128, 64,
- *              32, if the caller passed the workspace
+ *              32 (d_k != d_v: by d_k, with 384 heads at d_k = 64 and 128 at d_k = 128 from T = 4096,
+ *              1280 at d_k = 32 with d_v = 128), if the caller passed the workspace
  *              vla_forward_workspace_bytes() asks for (else CHUNKED); CHUNKED otherwise.
  *   SCAN     : one workgroup per (b,h) walks the tokens one by one with A and S
  *              resident in registers (FP32 vector ALU).
